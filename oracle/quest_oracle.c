@@ -1,0 +1,380 @@
+/*
+ * QuEST quantized-linear oracle: a plain, slow, double-precision CPU statement of
+ * what the hot path computes.  TEST INFRASTRUCTURE ONLY: it exists so that the HIP
+ * kernels can be checked against the paper, and to be timed as a CPU baseline.
+ * Nothing in the product path may call it, and it shares no code, header, table or
+ * helper with the HIP sources.
+ *
+ * Every function follows one passage of the paper (arXiv 2502.05003):
+ *   Hadamard transform ........ Sec. 3.1 "Hadamard Preprocessing", Eq. 3
+ *   RMS + projection .......... Sec. 2 Eq. 1 (grid), Sec. 3.1 "Gaussian Fitting"
+ *   trust mask ................ Sec. 3.2, T = alpha / (2^b - 1)
+ *   forward matmul ............ Algorithm 1 (y = xhat_h what_h^T)
+ *   backward .................. Algorithm 2 (masked inverse transform, 16-bit matmuls)
+ * The clip constant alpha* is NOT in this file: callers pass alpha, and the Python
+ * side of the oracle derives alpha* by minimising the Gaussian MSE.
+ *
+ * Notation.  Row length K, Hadamard block n (power of two dividing K), L = 2^b grid
+ * levels, grid spacing in RMS units D = 2 alpha / (L - 1), cell index
+ * k in [-L/2, L/2 - 1], grid point q_k = alpha (2k + 1) / (L - 1), odd integer
+ * u = 2k + 1, stored code c = k + L/2, per-row scale s = alpha rms / (L - 1) so that
+ * xhat = s u.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py (dense
+ * definition vs recursion, H H^T = n I, norm preservation, nearest-level brute
+ * force, closed-form mask threshold, naive triple loops, adjoint identities).
+ * The outer-trust generalisation for b = 1 is "parity unpinned" away from
+ * outer_trust = 1 (the paper's two descriptions of the factor disagree).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ input widening */
+
+/* bf16 is the upper half of an IEEE binary32; widening to double is exact. */
+void qo_widen_bf16(const uint16_t *src, int64_t count, double *dst)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        uint32_t bits = (uint32_t)src[i] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        dst[i] = (double)f;
+    }
+}
+
+void qo_widen_f32(const float *src, int64_t count, double *dst)
+{
+    for (int64_t i = 0; i < count; ++i)
+        dst[i] = (double)src[i];
+}
+
+/* ------------------------------------------------------------------ Hadamard (Eq. 3) */
+
+static int parity_of_and(uint32_t i, uint32_t j)
+{
+    uint32_t v = i & j;
+    int p = 0;
+    while (v) {
+        p ^= 1;
+        v &= v - 1;
+    }
+    return p;
+}
+
+/* Entry (i, j) of the Sylvester Hadamard matrix in natural order: (-1)^popcount(i & j). */
+int qo_hadamard_entry(uint32_t i, uint32_t j)
+{
+    return parity_of_and(i, j) ? -1 : 1;
+}
+
+/* Fill an n x n row-major int8 array with the +-1 matrix. */
+void qo_hadamard_matrix(int64_t n, int8_t *h)
+{
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < n; ++j)
+            h[i * n + j] = (int8_t)qo_hadamard_entry((uint32_t)i, (uint32_t)j);
+}
+
+/*
+ * x_h = x (I_{K/n} (x) H_n) / sqrt(n), row by row, from the dense definition.
+ * O(rows * cols * n): use for n <= 512 or for a handful of rows.
+ */
+void qo_hadamard_dense(const double *x, int64_t rows, int64_t cols, int64_t n, double *xh)
+{
+    const double norm = 1.0 / sqrt((double)n);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t blk = 0; blk < cols / n; ++blk) {
+            const double *in = x + r * cols + blk * n;
+            double *out = xh + r * cols + blk * n;
+            for (int64_t i = 0; i < n; ++i) {
+                double sum = 0.0;
+                for (int64_t j = 0; j < n; ++j)
+                    sum += (double)qo_hadamard_entry((uint32_t)i, (uint32_t)j) * in[j];
+                out[i] = sum * norm;
+            }
+        }
+    }
+}
+
+/* H_{2m} = [[H_m, H_m], [H_m, -H_m]]: apply the two half-size transforms, then combine. */
+static void sylvester_in_place(double *v, int64_t n)
+{
+    if (n == 1)
+        return;
+    const int64_t m = n / 2;
+    sylvester_in_place(v, m);
+    sylvester_in_place(v + m, m);
+    for (int64_t i = 0; i < m; ++i) {
+        const double top = v[i], bottom = v[i + m];
+        v[i] = top + bottom;
+        v[i + m] = top - bottom;
+    }
+}
+
+/* Same transform as qo_hadamard_dense via the Sylvester recursion (full-size runs). */
+void qo_hadamard_sylvester(const double *x, int64_t rows, int64_t cols, int64_t n, double *xh)
+{
+    const double norm = 1.0 / sqrt((double)n);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t blk = 0; blk < cols / n; ++blk) {
+            const double *in = x + r * cols + blk * n;
+            double *out = xh + r * cols + blk * n;
+            memcpy(out, in, (size_t)n * sizeof(double));
+            sylvester_in_place(out, n);
+            for (int64_t i = 0; i < n; ++i)
+                out[i] *= norm;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ RMS, projection, mask */
+
+/* rms = sqrt(mean_j x_h[j]^2) over the whole row (all Hadamard blocks); no epsilon. */
+void qo_row_rms(const double *xh, int64_t rows, int64_t cols, double *rms)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        double sumsq = 0.0;
+        for (int64_t j = 0; j < cols; ++j)
+            sumsq += xh[r * cols + j] * xh[r * cols + j];
+        rms[r] = sqrt(sumsq / (double)cols);
+    }
+}
+
+/*
+ * Gaussian-fit projection of Sec. 3.1 plus the trust mask of Sec. 3.2, per row:
+ *   x_n  = x_h / rms
+ *   k    = clamp(floor(x_n / D), -L/2, L/2 - 1)      nearest point of the zero-free grid;
+ *                                                     a value exactly on a cell boundary
+ *                                                     goes to the upper cell
+ *   xhat = rms * alpha * (2k + 1) / (L - 1)
+ *   M    = 1  iff  |xhat - x_h| <= T_eff * rms,  T = alpha / (L - 1),
+ *          T_eff = T inside the clip range (|x_n| <= alpha), outer_trust * T outside.
+ * outer_trust = 1 is the paper's definition for every b.  A zero row (rms = 0) maps to
+ * k = 0 everywhere with xhat = 0 and M = 1.
+ * Outputs (any may be NULL): rms[rows], scale[rows] = alpha rms / (L - 1), k[rows*cols],
+ * xhat[rows*cols], trust[rows*cols] (one byte per element, 0 or 1).
+ */
+void qo_project(const double *xh, int64_t rows, int64_t cols, int bits, double alpha,
+                double outer_trust, double *rms_out, double *scale_out, int32_t *k_out,
+                double *xhat_out, uint8_t *trust_out)
+{
+    const int64_t L = (int64_t)1 << bits;
+    const double D = 2.0 * alpha / (double)(L - 1);
+    const double T = alpha / (double)(L - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *row = xh + r * cols;
+        double sumsq = 0.0;
+        for (int64_t j = 0; j < cols; ++j)
+            sumsq += row[j] * row[j];
+        const double rms = sqrt(sumsq / (double)cols);
+        if (rms_out)
+            rms_out[r] = rms;
+        if (scale_out)
+            scale_out[r] = alpha * rms / (double)(L - 1);
+        for (int64_t j = 0; j < cols; ++j) {
+            int64_t k = 0;
+            double xhat = 0.0;
+            int trusted = 1;
+            if (rms > 0.0) {
+                const double xn = row[j] / rms;
+                double cell = floor(xn / D);
+                if (cell < (double)(-L / 2))
+                    cell = (double)(-L / 2);
+                if (cell > (double)(L / 2 - 1))
+                    cell = (double)(L / 2 - 1);
+                k = (int64_t)cell;
+                xhat = rms * alpha * (double)(2 * k + 1) / (double)(L - 1);
+                const double err = fabs(xhat - row[j]);
+                const double t_eff = (fabs(xn) <= alpha) ? T : outer_trust * T;
+                trusted = (err <= t_eff * rms) ? 1 : 0;
+            }
+            if (k_out)
+                k_out[r * cols + j] = (int32_t)k;
+            if (xhat_out)
+                xhat_out[r * cols + j] = xhat;
+            if (trust_out)
+                trust_out[r * cols + j] = (uint8_t)trusted;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ storage formats */
+
+/* Container width in bits for a b-bit code: 3-bit codes sit in a nibble. */
+int qo_container_bits(int bits)
+{
+    switch (bits) {
+    case 1: return 1;
+    case 2: return 2;
+    case 3: return 4;
+    case 4: return 4;
+    case 8: return 8;
+    default: return 0;
+    }
+}
+
+/*
+ * c = k + L/2 stored little-endian: element j occupies bits [(j*cb) mod 8, +cb) of byte
+ * floor(j*cb/8) of its row.  packed must hold rows * cols*cb/8 bytes.
+ */
+void qo_pack_codes(const int32_t *k, int64_t rows, int64_t cols, int bits, uint8_t *packed)
+{
+    const int cb = qo_container_bits(bits);
+    const int64_t L = (int64_t)1 << bits;
+    const int64_t row_bytes = cols * cb / 8;
+    memset(packed, 0, (size_t)(rows * row_bytes));
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t j = 0; j < cols; ++j) {
+            const uint32_t c = (uint32_t)(k[r * cols + j] + L / 2);
+            const int64_t bit = j * cb;
+            packed[r * row_bytes + bit / 8] |= (uint8_t)(c << (bit % 8));
+        }
+}
+
+/* Inverse of qo_pack_codes, returning the odd integers u = 2c - (L - 1). */
+void qo_unpack_odd(const uint8_t *packed, int64_t rows, int64_t cols, int bits, int32_t *u)
+{
+    const int cb = qo_container_bits(bits);
+    const int64_t L = (int64_t)1 << bits;
+    const int64_t row_bytes = cols * cb / 8;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t j = 0; j < cols; ++j) {
+            const int64_t bit = j * cb;
+            const uint32_t c = (packed[r * row_bytes + bit / 8] >> (bit % 8)) & ((1u << cb) - 1u);
+            u[r * cols + j] = (int32_t)(2 * (int64_t)c - (L - 1));
+        }
+}
+
+/* Bitmap, LSB first: element j is bit (j mod 8) of byte j/8 of its row; 1 = trusted. */
+void qo_pack_mask(const uint8_t *trust, int64_t rows, int64_t cols, uint8_t *bitmap)
+{
+    const int64_t row_bytes = cols / 8;
+    memset(bitmap, 0, (size_t)(rows * row_bytes));
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t j = 0; j < cols; ++j)
+            if (trust[r * cols + j])
+                bitmap[r * row_bytes + j / 8] |= (uint8_t)(1u << (j % 8));
+}
+
+void qo_unpack_mask(const uint8_t *bitmap, int64_t rows, int64_t cols, uint8_t *trust)
+{
+    const int64_t row_bytes = cols / 8;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t j = 0; j < cols; ++j)
+            trust[r * cols + j] = (uint8_t)((bitmap[r * row_bytes + j / 8] >> (j % 8)) & 1u);
+}
+
+/* ------------------------------------------------------------------ forward matmul (Alg. 1) */
+
+/*
+ * acc[m, n] = sum_k u_x[m, k] * u_w[n, k] in 64-bit integers; both operands are
+ * K-contiguous ("row-major weight", y = xhat what^T).  Returns the largest |acc| so the
+ * caller can assert that it fits 32 bits.
+ */
+int64_t qo_gemm_odd(const int32_t *ux, const int32_t *uw, int64_t M, int64_t N, int64_t K,
+                    int64_t *acc)
+{
+    int64_t worst = 0;
+#pragma omp parallel for schedule(static) reduction(max : worst)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t sum = 0;
+            for (int64_t k = 0; k < K; ++k)
+                sum += (int64_t)ux[m * K + k] * (int64_t)uw[n * K + k];
+            acc[m * N + n] = sum;
+            const int64_t mag = sum < 0 ? -sum : sum;
+            if (mag > worst)
+                worst = mag;
+        }
+    return worst;
+}
+
+/* y[m, n] = acc[m, n] * s_x[m] * s_w[n]  ( = sum_k xhat[m,k] what[n,k] since xhat = s u ). */
+void qo_dequant(const int64_t *acc, const double *sx, const double *sw, int64_t M, int64_t N,
+                double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n)
+            y[m * N + n] = (double)acc[m * N + n] * sx[m] * sw[n];
+}
+
+/* ------------------------------------------------------------------ backward (Alg. 2) */
+
+/*
+ * out = IHT(M (.) g).  The normalised Sylvester transform is symmetric and orthogonal,
+ * hence its own inverse, so IHT is the same block transform as the forward one.
+ * trust: one byte per element (0/1), or NULL for "all trusted" (plain straight-through).
+ */
+void qo_trust_backward(const double *g, const uint8_t *trust, int64_t rows, int64_t cols,
+                       int64_t n, double *out)
+{
+    const double norm = 1.0 / sqrt((double)n);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        double *dst = out + r * cols;
+        for (int64_t j = 0; j < cols; ++j) {
+            const int keep = trust ? (trust[r * cols + j] != 0) : 1;
+            dst[j] = keep ? g[r * cols + j] : 0.0;
+        }
+        for (int64_t blk = 0; blk < cols / n; ++blk) {
+            sylvester_in_place(dst + blk * n, n);
+            for (int64_t i = 0; i < n; ++i)
+                dst[blk * n + i] *= norm;
+        }
+    }
+}
+
+/* G_x[M, K] = dY[M, N] * what[N, K], what[n, k] = s_w[n] * u_w[n, k]  (Alg. 2, first matmul). */
+void qo_grad_input(const double *dy, const int32_t *uw, const double *sw, int64_t M, int64_t N,
+                   int64_t K, double *gx)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            double sum = 0.0;
+            for (int64_t n = 0; n < N; ++n)
+                sum += dy[m * N + n] * (sw[n] * (double)uw[n * K + k]);
+            gx[m * K + k] = sum;
+        }
+}
+
+/*
+ * G_w[N, K] = dY^T[N, M] * xhat[M, K], xhat[m, k] = s_x[m] * u_x[m, k]  (Alg. 2, second
+ * matmul, written with the shape of the row-major weight w[N, K]).
+ */
+void qo_grad_weight(const double *dy, const int32_t *ux, const double *sx, int64_t M, int64_t N,
+                    int64_t K, double *gw)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            double sum = 0.0;
+            for (int64_t m = 0; m < M; ++m)
+                sum += dy[m * N + n] * (sx[m] * (double)ux[m * K + k]);
+            gw[n * K + k] = sum;
+        }
+}
+
+/* Number of threads the row loops run on (1 when built without OpenMP). */
+int qo_threads(void)
+{
+    int count = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp single
+        count = omp_get_num_threads();
+    }
+#endif
+    return count;
+}
