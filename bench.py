@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the QuEST W4A4 linear-layer hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of the 1.6B-model MLP up-projection
+(d = 2048, ffn 5632, 16384 tokens; Algorithm 1 + Algorithm 2 of arXiv 2502.05003):
+    quantize X, quantize W, low-bit GEMM with bf16 epilogue,
+    two 16-bit gradient GEMMs, two trust-masked inverse transforms.
+Inputs are synthetic, seeded and resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+INT8_PEAK_TOPS = 5000.0      # dense INT8 MFMA (5.0 POP/s)
+BF16_PEAK_TFLOPS = 2500.0    # dense bf16 MFMA
+
+WORKLOAD = "mlp_up_1p6b"     # X 16384x2048, W 5632x2048, Hadamard block 2048, b = 4
+KERNELS = ("quantize_x", "quantize_w", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w",
+           "trust_backward_x", "trust_backward_w")
+
+
+def algorithmic_bytes_quantize(rows, cols, cb=4, in_bytes=2):
+    """input + packed codes + mask bitmap + one fp32 scale per row."""
+    return rows * cols * in_bytes + rows * cols * cb // 8 + rows * cols // 8 + 4 * rows
+
+
+def algorithmic_bytes_backward(rows, cols):
+    """bf16 gradient in + bitmap + bf16 out."""
+    return rows * cols * 2 + rows * cols // 8 + rows * cols * 2
+
+
+class BufferSet:
+    """One complete set of device buffers for a step (rotated so that caches cannot serve re-use)."""
+
+    def __init__(self, torch, dev, x_bits, w_bits, dy_bits, cfg):
+        import numpy as np
+        M, N, K = cfg["M"], cfg["N"], cfg["K"]
+
+        def bf16(a):
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+
+        u8, f32, b16 = torch.uint8, torch.float32, torch.bfloat16
+        self.x, self.w, self.dy = bf16(x_bits), bf16(w_bits), bf16(dy_bits)
+        self.x_codes = torch.empty(M, K // 2, dtype=u8, device=dev)
+        self.x_scales = torch.empty(M, dtype=f32, device=dev)
+        self.x_mask = torch.empty(M, K // 8, dtype=u8, device=dev)
+        self.w_codes = torch.empty(N, K // 2, dtype=u8, device=dev)
+        self.w_scales = torch.empty(N, dtype=f32, device=dev)
+        self.w_mask = torch.empty(N, K // 8, dtype=u8, device=dev)
+        self.y = torch.empty(M, N, dtype=b16, device=dev)
+        self.g_x = torch.empty(M, K, dtype=b16, device=dev)
+        self.g_w = torch.empty(N, K, dtype=b16, device=dev)
+        self.dx = torch.empty(M, K, dtype=b16, device=dev)
+        self.dw = torch.empty(N, K, dtype=b16, device=dev)
+
+
+def run_step(q, b, cfg, events=None):
+    """Enqueue the seven kernels of one step; `events` (name -> (start, end)) times each one."""
+    M, N, K, n, bits = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"], cfg["bits"]
+
+    def timed(name, fn):
+        if events is None:
+            fn()
+        else:
+            start, end = events[name]
+            start.record()
+            fn()
+            end.record()
+
+    timed("quantize_x", lambda: q.quest_hadamard_quantize(b.x, n, bits, codes=b.x_codes,
+                                                          scales=b.x_scales, mask=b.x_mask))
+    timed("quantize_w", lambda: q.quest_hadamard_quantize(b.w, n, bits, codes=b.w_codes,
+                                                          scales=b.w_scales, mask=b.w_mask))
+    timed("lowbit_gemm", lambda: q.quest_lowbit_gemm(b.x_codes, b.x_scales, b.w_codes, b.w_scales,
+                                                     K, bits, y=b.y))
+    timed("grad_gemm_x", lambda: q.quest_grad_gemm(0, b.dy, b.w_codes, b.w_scales, bits, M, N, K,
+                                                   out=b.g_x))
+    timed("grad_gemm_w", lambda: q.quest_grad_gemm(1, b.dy, b.x_codes, b.x_scales, bits, M, N, K,
+                                                   out=b.g_w))
+    timed("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx))
+    timed("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw))
+
+
+def cpu_baseline(x_bits, w_bits, dy_bits, cfg):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same step."""
+    import numpy as np
+    from oracle import quest_oracle as qo
+
+    M, N, K, n, bits = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"], cfg["bits"]
+    rows_q = M             # rows of X through HT + projection (W is done whole)
+    rows_g = 2048          # rows of X through the forward matmul and the backward pass
+    qo.threads()
+    t0 = time.perf_counter()
+    px = qo.hadamard_quantize(x_bits[:rows_q], n, bits)
+    pw = qo.hadamard_quantize(w_bits, n, bits)
+    ux, uw = qo.unpack_odd(px.codes[:rows_g], K, bits), qo.unpack_odd(pw.codes, K, bits)
+    acc = qo.gemm_odd(ux, uw)
+    qo.dequant(acc, px.scale[:rows_g], pw.scale)
+    dy = qo.widen(dy_bits[:rows_g])
+    gx = qo.grad_input(dy, uw, pw.scale)
+    qo.trust_backward(gx, px.trust[:rows_g], n)
+    gw = qo.grad_weight(dy, ux, px.scale[:rows_g])
+    qo.trust_backward(gw, pw.trust, n)
+    seconds = time.perf_counter() - t0
+    # the three matmuls dominate the step's operation count; the sample ran rows_g of M rows of each
+    ops = 6.0 * rows_g * N * K
+    return {"value": ops / seconds / 1e12, "unit": "TOPS", "cores": qo.threads(), "kind": "oracle",
+            "sample": (f"quantize {rows_q} of {M} X rows and all of W; forward matmul, both gradient "
+                       f"matmuls and both masked inverse transforms on {rows_g} of {M} token rows; "
+                       f"{seconds:.1f} s; value = 6*{rows_g}*N*K ops / time")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (one MI355X per box); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2502_05003_amd import binding as q
+    from paper_2502_05003_amd import synth
+
+    if not os.path.exists(q.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    q.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    x_bits, w_bits, cfg = synth.make_config(WORKLOAD, seed=0)
+    M, N, K = cfg["M"], cfg["N"], cfg["K"]
+    dy_bits = synth.upstream_gradient(M, N, seed=0)
+    n_sets = 3   # ~0.7 GiB per set: > 1 GiB of other traffic between two uses of any buffer
+    sets = [BufferSet(torch, dev, x_bits, w_bits, dy_bits, cfg) for _ in range(n_sets)]
+    torch.cuda.synchronize()
+
+    for i in range(args.warmup):
+        run_step(q, sets[i % n_sets], cfg)
+    torch.cuda.synchronize()
+
+    events = [{k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for k in KERNELS} for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run_step(q, sets[i % n_sets], cfg, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms = {k: float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in events])) for k in KERNELS}
+    ms_per_step = elapsed * 1e3 / args.steps
+    gemm_ops = 2.0 * M * N * K
+    step_ops = 3.0 * gemm_ops
+
+    def hbm(name, nbytes):
+        gbs = nbytes / (ms[name] * 1e-3) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": None, "ms": ms[name]}
+
+    def mfma(name, peak):
+        t = gemm_ops / (ms[name] * 1e-3) / 1e12
+        return {"kernel": name, "bound": "mfma", "achieved": t, "peak": peak,
+                "unit": "TOPS" if peak == INT8_PEAK_TOPS else "TFLOP/s", "frac": t / peak,
+                "traffic": None, "ms": ms[name]}
+
+    rooflines = {
+        "quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K)),
+        "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K)),
+        "lowbit_gemm": mfma("lowbit_gemm", INT8_PEAK_TOPS),
+        "grad_gemm_x": mfma("grad_gemm_x", BF16_PEAK_TFLOPS),
+        "grad_gemm_w": mfma("grad_gemm_w", BF16_PEAK_TFLOPS),
+        "trust_backward_x": hbm("trust_backward_x", algorithmic_bytes_backward(M, K)),
+        "trust_backward_w": hbm("trust_backward_w", algorithmic_bytes_backward(N, K)),
+    }
+    headline = dict(rooflines["lowbit_gemm"])
+    headline["unit"] = "TFLOP/s"   # integer multiply-adds counted as 2 ops each, in units of 1e12/s
+
+    result = {
+        "metric": "W4A4 QuEST-linear TOPS at d=2048 (forward + backward step; quantizer GB/s in kernels)",
+        "value": step_ops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 (forward matmul) / bf16 (gradient matmuls) / f32 (transform, quantizer)",
+        "data": "synthetic",
+        "config": {"workload": f"{WORKLOAD}: X {M}x{K} bf16 N(0,1) + 0.5% outlier channels x50, "
+                               f"W {N}x{K} bf16 N(0,0.02^2), dY {M}x{N} bf16, Hadamard block "
+                               f"{cfg['had_block']}, b={cfg['bits']}, forward+backward",
+                   "M": M, "N": N, "K": K, "had_block": cfg["had_block"], "bits": cfg["bits"],
+                   "buffer_sets": n_sets},
+        "quantizer_GBps": rooflines["quantize_x"]["achieved"],
+        "gemm_TOPS": rooflines["lowbit_gemm"]["achieved"],
+        "forward_TOPS": gemm_ops / ((ms["quantize_x"] + ms["quantize_w"] + ms["lowbit_gemm"]) * 1e-3) / 1e12,
+        "roofline": headline,
+        "kernels": rooflines,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(x_bits, w_bits, dy_bits, cfg)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

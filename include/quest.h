@@ -1,0 +1,138 @@
+/*
+ * quest.h - C ABI of the QuEST quantized-linear hot path for AMD MI355X (gfx950).
+ *
+ * The operations are those of the QuEST linear layer (arXiv 2502.05003):
+ *   forward  (Algorithm 1): x_h = HT(x), xhat_h = proj(x_h) for activations and weights,
+ *                           y = xhat_h what_h^T, plus the two trust masks;
+ *   backward (Algorithm 2): dL/dxhat_h = dL/dy what_h, dL/dx = IHT(M_x (.) dL/dxhat_h),
+ *                           dL/dwhat_h = (dL/dy)^T xhat_h, dL/dw = IHT(M_w (.) dL/dwhat_h).
+ *
+ * Notation.  K: row length (the matmul dimension).  n: Hadamard block (power of two, n | K).
+ * b: bits, L = 2^b levels.  Per row: rms = sqrt(mean_j x_h[j]^2), grid spacing in RMS units
+ * D = 2 alpha / (L - 1), cell index k = clamp(floor(x_h / (D rms)), -L/2, L/2 - 1), stored code
+ * c = k + L/2 in [0, L - 1], odd integer u = 2k + 1 = 2c - (L - 1), scale s = alpha rms / (L - 1);
+ * the quantized value is xhat_h = s * u (Eq. 1 with the RMS normalisation of Sec. 3.1).
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer unless the comment says "host".  The caller owns
+ *     all buffers; the library allocates nothing, frees nothing and never synchronises: a call
+ *     validates its arguments on the host and enqueues kernels on `stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream).
+ *   - Errors are return codes.  On any code other than QUEST_OK nothing was launched.
+ *   - Outputs must not alias inputs.
+ *   - "bf16" is the upper half of an IEEE binary32, stored as uint16_t.
+ *   - Code container width cb(b): 1 -> 1, 2 -> 2, 3 -> 4, 4 -> 4, 8 -> 8 bits.  Element j of a row
+ *     occupies bits [(j*cb) mod 8, +cb) of byte floor(j*cb/8) (little-endian: at b = 4 the even
+ *     element is the low nibble).  Mask bitmaps use the same order with one bit per element
+ *     (element j = bit j mod 8 of byte j/8); 1 = trusted.
+ */
+#ifndef QUEST_H
+#define QUEST_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QUEST_OK = 0,
+    QUEST_ERR_NULL = 1,    /* a required pointer is NULL */
+    QUEST_ERR_SHAPE = 2,   /* rows/cols/M/N/K/ld out of the supported range */
+    QUEST_ERR_BITS = 3,    /* bits not in {1,2,3,4,8} (quantizer) or not supported by the GEMM */
+    QUEST_ERR_BLOCK = 4,   /* had_block not a power of two, or does not divide cols */
+    QUEST_ERR_ALIGN = 5,   /* pointer or leading dimension not 16-byte aligned */
+    QUEST_ERR_DTYPE = 6,   /* unknown quest_dtype */
+    QUEST_ERR_LAUNCH = 7,  /* the HIP runtime refused the launch */
+    QUEST_ERR_ARG = 8      /* any other invalid argument (e.g. non-finite alpha) */
+} quest_status;
+
+typedef enum { QUEST_F32 = 0, QUEST_BF16 = 1 } quest_dtype;
+
+/* Limits checked by the entry points. */
+#define QUEST_MAX_COLS 16384      /* longest row the quantizer / trust backward accept */
+#define QUEST_MAX_HAD_BLOCK 16384 /* largest Hadamard block */
+
+/*
+ * Algorithm 1, one operand (call once for x, once for w):
+ *   x_h = HT(x) (Sec. 3.1, Eq. 3: block-diagonal normalised Sylvester transform along the row),
+ *   xhat_h = proj_alpha(x_h) (Sec. 3.1 "Gaussian Fitting": RMS-normalise, clip at alpha, round to
+ *   the zero-free 2^b-level grid of Eq. 1), and the trust mask M = 1[|xhat_h - x_h| <= T],
+ *   T = alpha / (2^b - 1) in RMS units (Sec. 3.2).
+ *
+ *   x           [rows, ld] row-major, dtype f32 or bf16; ld >= cols is the row stride in elements
+ *   rows        >= 0 (0 is a no-op);  cols: multiple of 8, 8 <= cols <= QUEST_MAX_COLS
+ *   had_block   n: power of two dividing cols; 1 = no transform (the paper's Hadamard ablation)
+ *   bits        b in {1,2,3,4,8}
+ *   alpha       clip in RMS units; <= 0 selects the built-in Gaussian-optimal alpha*(b)
+ *   outer_trust width of the trust region beyond the clip point in units of T; < 0 selects 1,
+ *               which is the paper's mask for every b (Sec. 3.3 "The 1-bit Case" shrinks it at b = 1).
+ *               An element is trusted iff |x_h| <= alpha (1 + outer_trust / (L - 1)) rms.
+ *   codes       out [rows, cols*cb/8] packed codes c
+ *   scales      out [rows] fp32, s = alpha rms / (L - 1)
+ *   mask        out [rows, cols/8] bitmap, or NULL when no backward pass will follow
+ *   xh_out      out [rows, cols] fp32 Hadamard-domain values x_h, or NULL (NULL in production)
+ * Rows whose entries are all zero give s = 0, c = L/2 everywhere and an all-ones mask.
+ * x, codes, mask, xh_out must be 16-byte aligned and ld * sizeof(element) a multiple of 16.
+ */
+quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
+                                     int64_t ld, int32_t had_block, int32_t bits, float alpha,
+                                     float outer_trust, uint8_t *codes, float *scales,
+                                     uint8_t *mask, float *xh_out, void *stream);
+
+/*
+ * Algorithm 1, the matmul y = xhat_h what_h^T, run on the integer codes (Sec. 5 "Kernel
+ * Overview", stage 3): acc[m, n] = sum_k u_a[m, k] u_b[n, k] exactly in int32, then
+ * y[m, n] = bf16(float(acc[m, n]) * a_scales[m] * b_scales[n]).
+ *
+ *   a_codes  [M, K*cb/8] activation codes, a_scales [M];  b_codes [N, K*cb/8] weight codes,
+ *            b_scales [N]; both operands K-contiguous (row-major weight), produced by
+ *            quest_hadamard_quantize with the same had_block and the same bits
+ *   bits     1, 2, 3 or 4 (u fits a signed byte); K: multiple of 64, 64 <= K <= 65536
+ *   y        out bf16 [M, ld_y], ld_y >= N (row stride in elements);  may be NULL if acc_out is given
+ *   acc_out  out int32 [M, N] raw accumulators, or NULL (NULL in production)
+ * M = 0 or N = 0 is a no-op.  Code pointers must be 16-byte aligned.
+ */
+quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,
+                               const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
+                               int32_t bits, void *y, int64_t ld_y, int32_t *acc_out,
+                               void *stream);
+
+/*
+ * Algorithm 2, the two masked inverse transforms: out = IHT(M (.) g) (Sec. 3.2 "Trust Estimators
+ * for the Hadamard Projection").  The normalised Sylvester transform is its own inverse.
+ *
+ *   g        [rows, cols] gradient w.r.t. the quantized tensor in the Hadamard domain
+ *   mask     [rows, cols/8] bitmap from quest_hadamard_quantize; NULL = all trusted (plain STE)
+ *   out      [rows, cols]; g_dtype / out_dtype: f32 or bf16 (bf16 rounds to nearest even)
+ * Same shape limits and alignment rules as quest_hadamard_quantize (ld = cols).
+ */
+quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint8_t *mask,
+                                  int64_t rows, int64_t cols, int32_t had_block, void *out,
+                                  quest_dtype out_dtype, void *stream);
+
+/*
+ * Algorithm 2, the two 16-bit matmuls against a code-packed operand whose value is
+ * bf16(s * u) (the paper runs the backward multiplications in 16-bit precision, Sec. 3.3):
+ *   which = 0:  out[M, K] = dy[M, N] * what_h[N, K]      (q = weight codes [N, K*cb/8], scales [N])
+ *   which = 1:  out[N, K] = dy[M, N]^T * xhat_h[M, K]    (q = activation codes [M, K*cb/8], scales [M])
+ *   dy bf16 [M, N] row-major, out bf16, fp32 accumulation.  bits in {1,2,3,4}.
+ *   M, N, K multiples of 64.
+ */
+quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_codes,
+                             const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,
+                             void *out, void *stream);
+
+/* Host: the built-in Gaussian-MSE-optimal clip alpha*(bits) (Sec. 3.1); 0 for unsupported bits. */
+float quest_alpha_star(int32_t bits);
+
+/* Host: container width in bits for a b-bit code; 0 for unsupported bits. */
+int32_t quest_container_bits(int32_t bits);
+
+/* Host: static description of a status code. */
+const char *quest_status_string(quest_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUEST_H */

@@ -1,0 +1,128 @@
+"""Thin Python binding of libquest.so: argument marshalling only.
+
+Every function has the name and the argument order of the C entry point it wraps
+(include/quest.h).  Tensors are torch device tensors used purely as device memory; every step of
+the path runs in the HIP kernels behind the C ABI, on torch's current stream.  There is no CPU or
+eager fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libquest.so")
+
+QUEST_F32, QUEST_BF16 = 0, 1
+EXPORTS = ("quest_hadamard_quantize", "quest_lowbit_gemm", "quest_trust_backward",
+           "quest_grad_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
+
+_i64, _i32, _f32, _p = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
+_lib = None
+
+
+class QuestError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def load():
+    """dlopen libquest.so (built by __graft_entry__.build()); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.quest_hadamard_quantize.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _i32, _f32, _f32,
+                                                _p, _p, _p, _p, _p]
+        lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p]
+        lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
+        lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
+        for name in ("quest_hadamard_quantize", "quest_lowbit_gemm", "quest_trust_backward",
+                     "quest_grad_gemm"):
+            getattr(lib, name).restype = ctypes.c_int
+        lib.quest_alpha_star.argtypes = [_i32]
+        lib.quest_alpha_star.restype = _f32
+        lib.quest_container_bits.argtypes = [_i32]
+        lib.quest_container_bits.restype = _i32
+        lib.quest_status_string.argtypes = [ctypes.c_int]
+        lib.quest_status_string.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return QUEST_F32
+    if t.dtype == torch.bfloat16:
+        return QUEST_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t: torch.Tensor | None):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise QuestError(status, where)
+
+
+def quest_alpha_star(bits: int) -> float:
+    return float(load().quest_alpha_star(bits))
+
+
+def quest_container_bits(bits: int) -> int:
+    return int(load().quest_container_bits(bits))
+
+
+def status_string(status: int) -> str:
+    return load().quest_status_string(status).decode()
+
+
+def quest_hadamard_quantize(x: torch.Tensor, had_block: int, bits: int, alpha: float = 0.0,
+                            outer_trust: float = -1.0, *, codes: torch.Tensor,
+                            scales: torch.Tensor, mask: torch.Tensor | None = None,
+                            xh_out: torch.Tensor | None = None) -> None:
+    """x [rows, cols] (row stride x.stride(0)) -> codes, scales, mask, xh_out (caller-allocated)."""
+    rows, cols = x.shape
+    _check(load().quest_hadamard_quantize(_ptr(x), _dtype_code(x), rows, cols, x.stride(0),
+                                          had_block, bits, alpha, outer_trust, _ptr(codes),
+                                          _ptr(scales), _ptr(mask), _ptr(xh_out), _stream()),
+           "quest_hadamard_quantize")
+
+
+def quest_lowbit_gemm(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: torch.Tensor,
+                      b_scales: torch.Tensor, K: int, bits: int, *, y: torch.Tensor | None,
+                      acc_out: torch.Tensor | None = None) -> None:
+    """y[M, N] (bf16) and/or acc_out[M, N] (int32) from packed codes [M, K*cb/8] and [N, K*cb/8]."""
+    M, N = a_codes.shape[0], b_codes.shape[0]
+    ld_y = y.stride(0) if y is not None else N
+    _check(load().quest_lowbit_gemm(_ptr(a_codes), _ptr(a_scales), M, _ptr(b_codes), _ptr(b_scales),
+                                    N, K, bits, _ptr(y), ld_y, _ptr(acc_out), _stream()),
+           "quest_lowbit_gemm")
+
+
+def quest_trust_backward(g: torch.Tensor, mask: torch.Tensor | None, had_block: int, *,
+                         out: torch.Tensor) -> None:
+    """out = IHT(mask (.) g) for contiguous g, out of shape [rows, cols]."""
+    rows, cols = g.shape
+    _check(load().quest_trust_backward(_ptr(g), _dtype_code(g), _ptr(mask), rows, cols, had_block,
+                                       _ptr(out), _dtype_code(out), _stream()),
+           "quest_trust_backward")
+
+
+def quest_grad_gemm(which: int, dy: torch.Tensor, q_codes: torch.Tensor, q_scales: torch.Tensor,
+                    bits: int, M: int, N: int, K: int, *, out: torch.Tensor) -> None:
+    """which = 0: out[M, K] = dy what_h;  which = 1: out[N, K] = dy^T xhat_h (bf16)."""
+    _check(load().quest_grad_gemm(which, _ptr(dy), _ptr(q_codes), _ptr(q_scales), bits, M, N, K,
+                                  _ptr(out), _stream()),
+           "quest_grad_gemm")

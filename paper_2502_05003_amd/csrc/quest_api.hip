@@ -1,0 +1,248 @@
+// C-ABI entry points of the QuEST hot path: argument validation and kernel dispatch only.
+// See include/quest.h for the contract of every function.
+#include <math.h>
+
+#include "quest_internal.h"
+
+namespace {
+
+// Gaussian-MSE-optimal clip in RMS units for the 2^b-level zero-free symmetric grid
+// (Sec. 3.1 "Gaussian Fitting" defines alpha*; the paper prints no values).  Obtained by
+// minimising, over alpha, sum over cells of the integral of (xi - q_k)^2 phi(xi); b = 1 has the
+// closed form sqrt(2 / pi).
+constexpr double kAlphaStar1 = 0.7978845608028654;
+constexpr double kAlphaStar2 = 1.4935300066;
+constexpr double kAlphaStar3 = 2.0510680577;
+constexpr double kAlphaStar4 = 2.5140046071;
+constexpr double kAlphaStar8 = 3.9221998115;
+
+double alpha_star(int bits)
+{
+    switch (bits) {
+    case 1: return kAlphaStar1;
+    case 2: return kAlphaStar2;
+    case 3: return kAlphaStar3;
+    case 4: return kAlphaStar4;
+    case 8: return kAlphaStar8;
+    default: return 0.0;
+    }
+}
+
+int container_bits(int bits)
+{
+    switch (bits) {
+    case 1: return 1;
+    case 2: return 2;
+    case 3: return 4;
+    case 4: return 4;
+    case 8: return 8;
+    default: return 0;
+    }
+}
+
+bool aligned16(const void *p)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
+// log2 of a power of two, -1 otherwise
+int exact_log2(int64_t v)
+{
+    if (v <= 0 || (v & (v - 1)))
+        return -1;
+    int l = 0;
+    while ((int64_t(1) << l) < v)
+        ++l;
+    return l;
+}
+
+quest_status shape_checks(int64_t rows, int64_t cols, int32_t had_block, int *log2n)
+{
+    if (rows < 0 || cols < 8 || cols > QUEST_MAX_COLS || (cols & 7))
+        return QUEST_ERR_SHAPE;
+    const int l = exact_log2(had_block);
+    if (l < 0 || had_block > QUEST_MAX_HAD_BLOCK || cols % had_block)
+        return QUEST_ERR_BLOCK;
+    *log2n = l;
+    return QUEST_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+float quest_alpha_star(int32_t bits)
+{
+    return (float)alpha_star(bits);
+}
+
+int32_t quest_container_bits(int32_t bits)
+{
+    return container_bits(bits);
+}
+
+const char *quest_status_string(quest_status status)
+{
+    switch (status) {
+    case QUEST_OK: return "ok";
+    case QUEST_ERR_NULL: return "a required pointer is NULL";
+    case QUEST_ERR_SHAPE: return "shape out of the supported range";
+    case QUEST_ERR_BITS: return "unsupported bit width";
+    case QUEST_ERR_BLOCK: return "Hadamard block must be a power of two that divides cols";
+    case QUEST_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
+    case QUEST_ERR_DTYPE: return "unknown dtype";
+    case QUEST_ERR_LAUNCH: return "the HIP runtime refused the launch";
+    case QUEST_ERR_ARG: return "invalid argument";
+    default: return "unknown status";
+    }
+}
+
+quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
+                                     int64_t ld, int32_t had_block, int32_t bits, float alpha,
+                                     float outer_trust, uint8_t *codes, float *scales,
+                                     uint8_t *mask, float *xh_out, void *stream)
+{
+    if (!x || !codes || !scales)
+        return QUEST_ERR_NULL;
+    if (dtype != QUEST_F32 && dtype != QUEST_BF16)
+        return QUEST_ERR_DTYPE;
+    const int cb = container_bits(bits);
+    if (cb == 0)
+        return QUEST_ERR_BITS;
+    int log2n = 0;
+    const quest_status shape = shape_checks(rows, cols, had_block, &log2n);
+    if (shape != QUEST_OK)
+        return shape;
+    if (ld < cols)
+        return QUEST_ERR_SHAPE;
+    const int64_t elem = dtype == QUEST_BF16 ? 2 : 4;
+    if (!aligned16(x) || !aligned16(codes) || (mask && !aligned16(mask)) ||
+        (xh_out && !aligned16(xh_out)) || ((ld * elem) & 15) ||
+        (reinterpret_cast<uintptr_t>(scales) & 3u))
+        return QUEST_ERR_ALIGN;
+    if (isnan(alpha) || isinf(alpha) || isnan(outer_trust) || isinf(outer_trust))
+        return QUEST_ERR_ARG;
+
+    const int levels = 1 << bits;
+    const double a = alpha > 0.0f ? (double)alpha : alpha_star(bits);
+    const double ot = outer_trust < 0.0f ? 1.0 : (double)outer_trust;
+
+    quest::QuantizeArgs args;
+    args.x = x;
+    args.dtype = dtype;
+    args.rows = rows;
+    args.cols = cols;
+    args.ld = ld;
+    args.log2n = log2n;
+    args.bits = bits;
+    args.cb = cb;
+    args.alpha = (float)a;
+    args.trust_edge = (float)(a * (1.0 + ot / (double)(levels - 1)));
+    args.codes = codes;
+    args.scales = scales;
+    args.mask = mask;
+    args.xh_out = xh_out;
+    return quest::launch_hadamard_quantize(args, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUEST_OK
+               : QUEST_ERR_LAUNCH;
+}
+
+quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,
+                               const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
+                               int32_t bits, void *y, int64_t ld_y, int32_t *acc_out,
+                               void *stream)
+{
+    if (!a_codes || !a_scales || !b_codes || !b_scales || (!y && !acc_out))
+        return QUEST_ERR_NULL;
+    if (bits < 1 || bits > 4)
+        return QUEST_ERR_BITS;
+    if (M < 0 || N < 0 || M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K < 64 ||
+        K > 65536 || (K & 63))
+        return QUEST_ERR_SHAPE;
+    if (y && ld_y < N)
+        return QUEST_ERR_SHAPE;
+    if (!aligned16(a_codes) || !aligned16(b_codes) || (y && !aligned16(y)) ||
+        (acc_out && !aligned16(acc_out)))
+        return QUEST_ERR_ALIGN;
+
+    quest::GemmArgs args;
+    args.a_codes = a_codes;
+    args.a_scales = a_scales;
+    args.b_codes = b_codes;
+    args.b_scales = b_scales;
+    args.M = M;
+    args.N = N;
+    args.K = K;
+    args.bits = bits;
+    args.cb = container_bits(bits);
+    args.y = y;
+    args.ld_y = ld_y;
+    args.acc_out = acc_out;
+    return quest::launch_lowbit_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUEST_OK
+               : QUEST_ERR_LAUNCH;
+}
+
+quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint8_t *mask,
+                                  int64_t rows, int64_t cols, int32_t had_block, void *out,
+                                  quest_dtype out_dtype, void *stream)
+{
+    if (!g || !out)
+        return QUEST_ERR_NULL;
+    if ((g_dtype != QUEST_F32 && g_dtype != QUEST_BF16) ||
+        (out_dtype != QUEST_F32 && out_dtype != QUEST_BF16))
+        return QUEST_ERR_DTYPE;
+    int log2n = 0;
+    const quest_status shape = shape_checks(rows, cols, had_block, &log2n);
+    if (shape != QUEST_OK)
+        return shape;
+    if (!aligned16(g) || !aligned16(out) || (mask && !aligned16(mask)))
+        return QUEST_ERR_ALIGN;
+
+    quest::BackwardArgs args;
+    args.g = g;
+    args.g_dtype = g_dtype;
+    args.mask = mask;
+    args.rows = rows;
+    args.cols = cols;
+    args.log2n = log2n;
+    args.out = out;
+    args.out_dtype = out_dtype;
+    return quest::launch_trust_backward(args, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUEST_OK
+               : QUEST_ERR_LAUNCH;
+}
+
+quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_codes,
+                             const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,
+                             void *out, void *stream)
+{
+    if (!dy || !q_codes || !q_scales || !out)
+        return QUEST_ERR_NULL;
+    if (which != 0 && which != 1)
+        return QUEST_ERR_ARG;
+    if (bits < 1 || bits > 4)
+        return QUEST_ERR_BITS;
+    if (M < 0 || N < 0 || K < 0 || (M & 63) || (N & 63) || (K & 63) || M > (int64_t(1) << 22) ||
+        N > (int64_t(1) << 22) || K > (int64_t(1) << 22))
+        return QUEST_ERR_SHAPE;
+    if (!aligned16(dy) || !aligned16(q_codes) || !aligned16(out))
+        return QUEST_ERR_ALIGN;
+
+    quest::GradGemmArgs args;
+    args.which = which;
+    args.dy = dy;
+    args.q_codes = q_codes;
+    args.q_scales = q_scales;
+    args.bits = bits;
+    args.cb = container_bits(bits);
+    args.M = M;
+    args.N = N;
+    args.K = K;
+    args.out = out;
+    return quest::launch_grad_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUEST_OK
+               : QUEST_ERR_LAUNCH;
+}
+
+}  // extern "C"

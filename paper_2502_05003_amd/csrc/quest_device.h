@@ -1,0 +1,138 @@
+// Device-side helpers shared by the QuEST HIP kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace quest {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16)
+{
+    return __uint_as_float(bits16 << 16);
+}
+
+// Round-to-nearest-even float -> bf16 bits (NaN kept quiet).
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Eight consecutive row elements widened to fp32.  The pointer must be 16-byte aligned.
+__device__ __forceinline__ void load8(const float *p, float (&v)[8])
+{
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+__device__ __forceinline__ void load8(const uint16_t *p, float (&v)[8])
+{
+    const uint4 w = *reinterpret_cast<const uint4 *>(p);
+    v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+    v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+    v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
+    v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ void store8(float *p, const float (&v)[8])
+{
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+__device__ __forceinline__ void store8(uint16_t *p, const float (&v)[8])
+{
+    uint4 w;
+    w.x = float_to_bf16_bits(v[0]) | (float_to_bf16_bits(v[1]) << 16);
+    w.y = float_to_bf16_bits(v[2]) | (float_to_bf16_bits(v[3]) << 16);
+    w.z = float_to_bf16_bits(v[4]) | (float_to_bf16_bits(v[5]) << 16);
+    w.w = float_to_bf16_bits(v[6]) | (float_to_bf16_bits(v[7]) << 16);
+    *reinterpret_cast<uint4 *>(p) = w;
+}
+
+// Un-normalised Sylvester butterflies over the low `STAGES` index bits of a 2^STAGES register
+// array: after the call v[i] = sum_j (-1)^popcount(i & j) v_in[j].
+template <int STAGES>
+__device__ __forceinline__ void butterflies(float (&v)[1 << STAGES])
+{
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s) {
+        const int h = 1 << s;
+#pragma unroll
+        for (int i = 0; i < (1 << STAGES); ++i) {
+            if ((i & h) == 0) {
+                const float a = v[i], b = v[i + h];
+                v[i] = a + b;
+                v[i + h] = a - b;
+            }
+        }
+    }
+}
+
+// Same, for a runtime stage count 0..3 on an 8-element array (stages beyond `stages` skipped).
+__device__ __forceinline__ void butterflies8(float (&v)[8], int stages)
+{
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        if (s < stages) {
+            const int h = 1 << s;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if ((i & h) == 0) {
+                    const float a = v[i], b = v[i + h];
+                    v[i] = a + b;
+                    v[i + h] = a - b;
+                }
+            }
+        }
+    }
+}
+
+// LDS index with one pad word per 32 so that power-of-two strides spread over the banks.
+__device__ __forceinline__ int lds_pad(int i)
+{
+    return i + (i >> 5);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+/*
+ * Remaining butterfly stages (index bits 3 .. log2n-1) of one row held in LDS as padded fp32,
+ * three bits per pass.  Bits 0..2 must already have been applied.  Every thread of the block
+ * must call this; the row is consistent in LDS after the trailing barrier.
+ */
+__device__ __forceinline__ void lds_butterfly_passes(float *row, int cols, int log2n)
+{
+    for (int s = 3; s < log2n; s += 3) {
+        const int r = (log2n - s) < 3 ? (log2n - s) : 3;
+        const int groups = cols >> r;
+        __syncthreads();
+        for (int g = threadIdx.x; g < groups; g += blockDim.x) {
+            const int base = ((g >> s) << (s + r)) | (g & ((1 << s) - 1));
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                v[i] = (i < (1 << r)) ? row[lds_pad(base + (i << s))] : 0.0f;
+            butterflies8(v, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (i < (1 << r))
+                    row[lds_pad(base + (i << s))] = v[i];
+        }
+    }
+    __syncthreads();
+}
+
+}  // namespace quest

@@ -1,0 +1,67 @@
+// Host-side declarations shared by the QuEST translation units: one launcher per kernel family.
+// Launchers assume validated arguments (the C-ABI entry points validate) and only enqueue work.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/quest.h"
+
+namespace quest {
+
+struct QuantizeArgs {
+    const void *x;
+    quest_dtype dtype;
+    int64_t rows, cols, ld;
+    int log2n;         // log2(had_block)
+    int bits;          // b
+    int cb;            // container bits
+    float alpha;       // clip in RMS units
+    float trust_edge;  // alpha * (1 + outer_trust / (L - 1)): trusted iff |x_h| <= trust_edge * rms
+    uint8_t *codes;
+    float *scales;
+    uint8_t *mask;     // may be null
+    float *xh_out;     // may be null
+};
+
+hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream);
+
+struct GemmArgs {
+    const uint8_t *a_codes;
+    const float *a_scales;
+    const uint8_t *b_codes;
+    const float *b_scales;
+    int64_t M, N, K;
+    int bits, cb;
+    void *y;          // bf16, may be null
+    int64_t ld_y;
+    int32_t *acc_out; // may be null
+};
+
+hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream);
+
+struct BackwardArgs {
+    const void *g;
+    quest_dtype g_dtype;
+    const uint8_t *mask;  // may be null
+    int64_t rows, cols;
+    int log2n;
+    void *out;
+    quest_dtype out_dtype;
+};
+
+hipError_t launch_trust_backward(const BackwardArgs &a, hipStream_t stream);
+
+struct GradGemmArgs {
+    int which;
+    const void *dy;
+    const uint8_t *q_codes;
+    const float *q_scales;
+    int bits, cb;
+    int64_t M, N, K;
+    void *out;
+};
+
+hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream);
+
+}  // namespace quest

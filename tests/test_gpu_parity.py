@@ -1,0 +1,239 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import quest_oracle as qo
+from paper_2502_05003_amd import binding as q
+from paper_2502_05003_amd import synth
+
+from gpu_util import (BF16_HALF_ULP, DEV, check_gemm_output, compare_quantizer, gpu_quantize, to_device,
+                      to_host_f64)
+
+pytestmark = pytest.mark.gpu
+
+
+# ------------------------------------------------------------------ quantizer
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_config_full_forward(dtype):
+    """256x512 activations, 512x512 weights, block 512, W4A4: dense-matrix oracle, all outputs."""
+    x, w, cfg = synth.make_config("tiny", seed=0)
+    if dtype == "bf16":
+        x, w = synth.to_bf16_bits(x), synth.to_bf16_bits(w)
+    n, bits, K = cfg["had_block"], cfg["bits"], cfg["K"]
+    gx, gw = gpu_quantize(x, n, bits), gpu_quantize(w, n, bits)
+    px, pw = qo.hadamard_quantize(x, n, bits, dense=True), qo.hadamard_quantize(w, n, bits, dense=True)
+    compare_quantizer(gx, px, K, bits)
+    compare_quantizer(gw, pw, K, bits)
+    # mask density on Gaussian rows ~ the closed-form Gaussian tail (Sec. 3.2 / App. A.1)
+    frac = 1.0 - qo.unpack_mask(gx["mask"], K).mean()
+    assert abs(frac - 7.327e-3) < 1.5e-3
+
+    M, N = x.shape[0], w.shape[0]
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    acc = torch.empty(M, N, dtype=torch.int32, device=DEV)
+    q.quest_lowbit_gemm(gx["dev"]["codes"], gx["dev"]["scales"], gw["dev"]["codes"], gw["dev"]["scales"],
+                        K, bits, y=y, acc_out=acc)
+    torch.cuda.synchronize()
+    ref_acc = qo.gemm_odd(qo.unpack_odd(gx["codes"], K, bits), qo.unpack_odd(gw["codes"], K, bits))
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref_acc)
+    got_y = check_gemm_output(y, ref_acc, gx["scales"], gw["scales"])
+    # and the whole thing approximates x w^T (Sec. 3.3: the transform is unitary)
+    exact = qo.widen(x) @ qo.widen(w).T
+    assert np.linalg.norm(got_y - exact) / np.linalg.norm(exact) < 0.2
+
+
+QUANT_CASES = [
+    # rows, cols, block, bits, dtype   (several tiles, ragged row counts, every container width)
+    (37, 1024, 128, 4, "bf16"), (37, 1024, 1024, 4, "bf16"), (130, 2048, 2048, 4, "bf16"),
+    (70, 5632, 512, 4, "bf16"), (5, 4096, 4096, 4, "bf16"), (3, 16384, 16384, 4, "bf16"),
+    (33, 2048, 2048, 1, "bf16"), (33, 2048, 2048, 2, "bf16"), (33, 2048, 2048, 3, "bf16"),
+    (33, 2048, 2048, 8, "bf16"), (19, 512, 1, 4, "bf16"), (19, 512, 2, 4, "f32"),
+    (19, 512, 4, 2, "f32"), (19, 24, 8, 4, "f32"), (1, 8, 8, 4, "bf16"), (300, 64, 64, 8, "f32"),
+    (21, 1536, 512, 3, "f32"), (9, 11008, 256, 4, "bf16"),
+]
+
+
+@pytest.mark.parametrize("rows,cols,n,bits,dtype", QUANT_CASES)
+def test_quantizer_matches_oracle(rows, cols, n, bits, dtype):
+    x = synth.outlier_activations(rows, cols, 0.01, 20.0, seed=rows + cols + bits, dtype=dtype)
+    got = gpu_quantize(x, n, bits)
+    ref = qo.hadamard_quantize(x, n, bits, dense=(n <= 512))
+    compare_quantizer(got, ref, cols, bits)
+
+
+def test_quantizer_options_and_degenerate_rows():
+    rows, cols, n = 16, 1024, 256
+    x = synth.student_t_activations(rows, cols, 3.0, seed=4, dtype="bf16")
+    x[3] = 0                                  # all-zero row
+    x[5] = 0
+    x[5, 17] = 0x3F80                         # single 1.0
+    x[7] = 0x4000                             # constant row: one nonzero coefficient per block
+    for bits, alpha, ot in ((4, 2.9, 0.5), (1, 0.0, 0.30), (1, 0.0, 1.0), (2, 1.3, 2.0), (8, 0.0, 0.0)):
+        got = gpu_quantize(x, n, bits, alpha=alpha, outer_trust=ot)
+        ref = qo.hadamard_quantize(x, n, bits, alpha=(alpha if alpha > 0 else None), outer_trust=ot)
+        compare_quantizer(got, ref, cols, bits, outer_trust=ot)
+        L = 1 << bits
+        assert got["scales"][3] == 0.0
+        assert np.all(qo.unpack_odd(got["codes"][3:4], cols, bits) == 1)        # k = 0 -> u = +1
+        assert np.all(got["mask"][3] == 0xFF)
+        assert L >= 2
+    # leading dimension larger than cols, no mask, no xh
+    got = gpu_quantize(x, n, 4, want_xh=False, want_mask=False, ld=cols + 64)
+    ref = qo.hadamard_quantize(x, n, 4)
+    compare_quantizer(got, ref, cols, 4)
+
+
+def test_quantizer_full_size_headline_shape():
+    """16384 x 2048 bf16 with outlier channels, block 2048, b = 4: whole tensor against the oracle."""
+    x, _, cfg = synth.make_config("mlp_up_1p6b", seed=0)
+    got = gpu_quantize(x, cfg["had_block"], cfg["bits"], want_xh=False)
+    ref = qo.hadamard_quantize(x, cfg["had_block"], cfg["bits"])
+    n_code, n_mask = compare_quantizer(got, ref, cfg["K"], cfg["bits"])
+    print(f"full size: {n_code} codes and {n_mask} mask bits at a boundary out of {x.size}")
+
+
+# ------------------------------------------------------------------ GEMM
+
+GEMM_CASES = [(256, 512, 512, 4), (130, 200, 1024, 4), (1, 1, 64, 4), (257, 129, 2048, 4),
+              (64, 640, 5632, 4), (96, 160, 256, 3), (96, 160, 256, 2), (96, 160, 256, 1)]
+
+
+@pytest.mark.parametrize("M,N,K,bits", GEMM_CASES)
+def test_gemm_accumulators_exact_and_output_close(M, N, K, bits):
+    rng = np.random.default_rng(M * 7 + N * 3 + K + bits)
+    L = 1 << bits
+    cb = qo.container_bits(bits)
+    ka = rng.integers(-L // 2, L // 2, size=(M, K), dtype=np.int32)
+    kb = rng.integers(-L // 2, L // 2, size=(N, K), dtype=np.int32)
+    ka[0] = L // 2 - 1                      # extreme rows: largest |acc|
+    kb[0] = L // 2 - 1
+    if N > 1:
+        kb[1] = -L // 2
+    from oracle.quest_oracle import _load, _ptr
+    a_codes = np.empty((M, K * cb // 8), dtype=np.uint8)
+    b_codes = np.empty((N, K * cb // 8), dtype=np.uint8)
+    _load().qo_pack_codes(_ptr(ka), M, K, bits, _ptr(a_codes))
+    _load().qo_pack_codes(_ptr(kb), N, K, bits, _ptr(b_codes))
+    sa = (rng.random(M) + 0.5).astype(np.float32)
+    sb = ((rng.random(N) + 0.5) * 0.01).astype(np.float32)
+    y = torch.full((M, N + 2), 7.0, dtype=torch.bfloat16, device=DEV)   # ld_y > N
+    acc = torch.empty(M, N, dtype=torch.int32, device=DEV)
+    q.quest_lowbit_gemm(to_device(a_codes), to_device(sa), to_device(b_codes), to_device(sb), K, bits,
+                        y=y[:, :N], acc_out=acc)
+    torch.cuda.synchronize()
+    ref_acc = qo.gemm_odd(2 * ka + 1, 2 * kb + 1)
+    got_acc = acc.cpu().numpy().astype(np.int64)
+    assert np.array_equal(got_acc, ref_acc)
+    assert got_acc[0, 0] == (L - 1) ** 2 * K
+    check_gemm_output(y[:, :N], ref_acc, sa, sb)
+    assert torch.all(y[:, N:] == 7.0)       # padding columns untouched
+
+
+def test_gemm_full_size_sampled_rows():
+    """M=16384, N=5632, K=2048 in the launch shape the benchmark times; sampled rows vs the oracle."""
+    x, w, cfg = synth.make_config("mlp_up_1p6b", seed=0)
+    K, bits, n = cfg["K"], cfg["bits"], cfg["had_block"]
+    gx = gpu_quantize(x, n, bits, want_xh=False, want_mask=False)
+    gw = gpu_quantize(w, n, bits, want_xh=False, want_mask=False)
+    M, N = x.shape[0], w.shape[0]
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    q.quest_lowbit_gemm(gx["dev"]["codes"], gx["dev"]["scales"], gw["dev"]["codes"], gw["dev"]["scales"],
+                        K, bits, y=y, acc_out=None)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(M, size=48, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    ux = qo.unpack_odd(gx["codes"][rows], K, bits)
+    uw = qo.unpack_odd(gw["codes"], K, bits)
+    got = check_gemm_output(y[torch.from_numpy(rows).to(DEV)], qo.gemm_odd(ux, uw), gx["scales"][rows], gw["scales"])
+    # any-size properties: finite everywhere, and the output approximates x w^T on the sampled rows
+    assert torch.isfinite(y.float()).all()
+    exact = qo.widen(x[rows]) @ qo.widen(w).T
+    assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.25
+
+
+# ------------------------------------------------------------------ backward
+
+BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16"), (70, 5632, 512, "bf16", "f32"),
+              (19, 512, 1, "f32", "f32"), (5, 16384, 16384, "bf16", "bf16"), (300, 64, 64, "f32", "bf16"),
+              (1, 8, 2, "f32", "f32")]
+
+
+@pytest.mark.parametrize("rows,cols,n,gd,od", BACK_CASES)
+def test_trust_backward_matches_oracle(rows, cols, n, gd, od):
+    g = synth.gaussian(rows, cols, 0.03, seed=rows + cols, dtype=gd)
+    rng = np.random.default_rng(cols)
+    trust = (rng.random((rows, cols)) < 0.98).astype(np.uint8)
+    from oracle.quest_oracle import _load, _ptr
+    bitmap = np.empty((rows, cols // 8), dtype=np.uint8)
+    _load().qo_pack_mask(_ptr(trust), rows, cols, _ptr(bitmap))
+    out = torch.empty(rows, cols, dtype=torch.bfloat16 if od == "bf16" else torch.float32, device=DEV)
+    for mask_host, trust_ref in ((bitmap, trust), (None, None)):
+        q.quest_trust_backward(to_device(g), None if mask_host is None else to_device(mask_host), n, out=out)
+        torch.cuda.synchronize()
+        ref = qo.trust_backward(qo.widen(g), trust_ref, n)
+        scale = np.sqrt(np.mean(ref * ref, axis=1, keepdims=True))
+        tol = (BF16_HALF_ULP if od == "bf16" else 1e-5) * np.abs(ref) + 1e-5 * scale + 1e-30
+        assert np.all(np.abs(to_host_f64(out) - ref) <= tol)
+    zeros = to_device(np.zeros((rows, cols // 8), dtype=np.uint8))
+    q.quest_trust_backward(to_device(g), zeros, n, out=out)
+    assert torch.all(out == 0)
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_grad_gemm_matches_oracle(which):
+    M, N, K, bits, n = 192, 128, 256, 4, 256
+    x = synth.gaussian(M, K, 1.0, 11, "bf16")
+    w = synth.gaussian(N, K, 0.02, 12, "bf16")
+    dy = synth.upstream_gradient(M, N, 0, "bf16")
+    src, C = (w, N) if which == 0 else (x, M)
+    gq = gpu_quantize(src, n, bits, want_xh=False)
+    rows_out = M if which == 0 else N
+    out = torch.empty(rows_out, K, dtype=torch.bfloat16, device=DEV)
+    q.quest_grad_gemm(which, to_device(dy), gq["dev"]["codes"], gq["dev"]["scales"], bits, M, N, K, out=out)
+    torch.cuda.synchronize()
+    u = qo.unpack_odd(gq["codes"], K, bits)
+    s = gq["scales"].astype(np.float64)
+    dyd = qo.widen(dy)
+    # the 16-bit operand the paper's backward multiplies with: bf16(s * u), one rounding
+    q16 = qo.widen(synth.to_bf16_bits(gq["scales"][:, None] * u.astype(np.float32)))
+    if which == 0:
+        ref, mirror = qo.grad_input(dyd, u, s), dyd @ q16
+        spread = np.sqrt((dyd ** 2) @ (q16 ** 2))
+    else:
+        ref, mirror = qo.grad_weight(dyd, u, s), dyd.T @ q16
+        spread = np.sqrt((dyd.T ** 2) @ (q16 ** 2))
+    got = to_host_f64(out)
+    # same operand values on both sides: only fp32 accumulation order and the final bf16 rounding differ
+    assert np.all(np.abs(got - mirror) <= BF16_HALF_ULP * 1.001 * np.abs(mirror) + 2e-5 * spread)
+    # against the exact oracle: the operand rounding adds about 2^-9 of the spread of the terms
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+    assert np.linalg.norm(got - ref) <= 4e-3 * np.linalg.norm(ref)
+
+
+def test_full_linear_forward_backward_small():
+    """Algorithm 1 + Algorithm 2 end to end through the C ABI on a small layer."""
+    M, N, K, bits, n = 128, 192, 512, 4, 512
+    x = synth.outlier_activations(M, K, 0.01, 20.0, 5, "bf16")
+    w = synth.gaussian(N, K, 0.02, 6, "bf16")
+    dy = synth.upstream_gradient(M, N, 7, "bf16")
+    gx, gw = gpu_quantize(x, n, bits, want_xh=False), gpu_quantize(w, n, bits, want_xh=False)
+    dyd = to_device(dy)
+    g_x = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
+    g_w = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
+    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x)
+    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w)
+    dx = torch.empty(M, K, dtype=torch.float32, device=DEV)
+    dw = torch.empty(N, K, dtype=torch.float32, device=DEV)
+    q.quest_trust_backward(g_x, gx["dev"]["mask"], n, out=dx)
+    q.quest_trust_backward(g_w, gw["dev"]["mask"], n, out=dw)
+    torch.cuda.synchronize()
+    ux, uw = qo.unpack_odd(gx["codes"], K, bits), qo.unpack_odd(gw["codes"], K, bits)
+    sx, sw = gx["scales"].astype(np.float64), gw["scales"].astype(np.float64)
+    ref_dx = qo.trust_backward(qo.grad_input(qo.widen(dy), uw, sw), qo.unpack_mask(gx["mask"], K), n)
+    ref_dw = qo.trust_backward(qo.grad_weight(qo.widen(dy), ux, sx), qo.unpack_mask(gw["mask"], K), n)
+    for got, ref in ((dx, ref_dx), (dw, ref_dw)):
+        err = np.linalg.norm(to_host_f64(got) - ref) / np.linalg.norm(ref)
+        assert err < 5e-3

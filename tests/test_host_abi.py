@@ -1,0 +1,85 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/quest.h declares, its
+constant table matches the oracle's derivation, and invalid arguments are turned into status
+codes before anything is launched (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_05003_amd import binding as q
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x10000)          # 16-byte aligned, never dereferenced: validation fails first
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(q.LIB_PATH):
+        from paper_2502_05003_amd import build
+        build.build_library()
+    return q.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "quest.h")).read()
+    declared = set(re.findall(r"\b(quest_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(q.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_builtin_alpha_table_matches_the_oracle(lib, alpha_table):
+    for bits, alpha in alpha_table.items():
+        assert q.quest_alpha_star(bits) == pytest.approx(alpha, rel=3e-7)
+    assert q.quest_alpha_star(5) == 0.0
+    assert [q.quest_container_bits(b) for b in (1, 2, 3, 4, 8, 5)] == [1, 2, 4, 4, 8, 0]
+    from oracle import quest_oracle as qo
+    assert all(q.quest_container_bits(b) == qo.container_bits(b) for b in (1, 2, 3, 4, 8))
+
+
+def _hq(lib, x=FAKE, dtype=1, rows=4, cols=512, ld=512, n=512, bits=4, alpha=0.0, ot=-1.0,
+        codes=FAKE, scales=FAKE, mask=FAKE, xh=None):
+    return lib.quest_hadamard_quantize(x, dtype, rows, cols, ld, n, bits, alpha, ot, codes, scales,
+                                       mask, xh, None)
+
+
+def test_quantizer_rejects_bad_arguments(lib):
+    assert _hq(lib, x=None) == 1 and _hq(lib, codes=None) == 1 and _hq(lib, scales=None) == 1
+    assert _hq(lib, dtype=7) == 6
+    for bits in (0, 5, 6, 7, 9, 16, -1):
+        assert _hq(lib, bits=bits) == 3
+    assert _hq(lib, cols=0) == 2 and _hq(lib, cols=508) == 2 and _hq(lib, cols=32768, ld=32768, n=8) == 2
+    assert _hq(lib, rows=-1) == 2 and _hq(lib, ld=256) == 2
+    assert _hq(lib, n=3) == 4 and _hq(lib, n=0) == 4 and _hq(lib, n=1024) == 4 and _hq(lib, cols=768, ld=768, n=512) == 4
+    assert _hq(lib, x=ctypes.c_void_p(0x10008)) == 5 and _hq(lib, mask=ctypes.c_void_p(0x10001)) == 5
+    assert _hq(lib, ld=516) == 5                      # bf16 row stride not a multiple of 16 bytes
+    assert _hq(lib, alpha=float("nan")) == 8 and _hq(lib, ot=float("inf")) == 8
+    assert _hq(lib, rows=0) == 0                      # empty input is a no-op, nothing is launched
+
+
+def test_gemm_backward_and_grad_gemm_reject_bad_arguments(lib):
+    def gemm(a=FAKE, sa=FAKE, M=0, b=FAKE, sb=FAKE, N=0, K=512, bits=4, y=FAKE, ld=0, acc=None):
+        return lib.quest_lowbit_gemm(a, sa, M, b, sb, N, K, bits, y, ld, acc, None)
+    assert gemm() == 0
+    assert gemm(a=None) == 1 and gemm(y=None) == 1 and gemm(y=None, acc=FAKE) == 0
+    assert gemm(bits=8) == 3 and gemm(bits=0) == 3
+    assert gemm(K=96) == 2 and gemm(K=0) == 2 and gemm(M=-1) == 2 and gemm(N=8, ld=4) == 2
+    assert gemm(a=ctypes.c_void_p(0x10004)) == 5
+
+    def back(g=FAKE, gd=1, mask=FAKE, rows=0, cols=512, n=512, out=FAKE, od=1):
+        return lib.quest_trust_backward(g, gd, mask, rows, cols, n, out, od, None)
+    assert back() == 0 and back(mask=None) == 0
+    assert back(g=None) == 1 and back(out=None) == 1 and back(gd=3) == 6 and back(od=-1) == 6
+    assert back(cols=20) == 2 and back(n=48) == 4 and back(out=ctypes.c_void_p(0x10002)) == 5
+
+    def grad(which=0, dy=FAKE, qc=FAKE, qs=FAKE, bits=4, M=0, N=0, K=0, out=FAKE):
+        return lib.quest_grad_gemm(which, dy, qc, qs, bits, M, N, K, out, None)
+    assert grad() == 0
+    assert grad(which=2) == 8 and grad(dy=None) == 1 and grad(bits=8) == 3 and grad(M=32) == 2
+
+
+def test_status_strings(lib):
+    assert q.status_string(0) == "ok"
+    assert len({q.status_string(s) for s in range(9)}) == 9
+    assert "unknown" in q.status_string(99)
