@@ -7,8 +7,10 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libquest.so")
-SOURCES = ["quest_api.hip", "hadamard_quantize.hip", "lowbit_gemm.hip", "trust_backward.hip",
-           "grad_gemm.hip"]
+SOURCES = ["quest_api.hip", "hadamard_quantize.hip", "hadamard_quantize_mfma.hip",
+           "lowbit_gemm.hip", "trust_backward.hip", "grad_gemm.hip"]
+# per-source extra flags: kernels whose MFMA results are consumed by vector code keep them in VGPRs
+EXTRA_FLAGS = {"hadamard_quantize_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms stay off: plain fp32 ops only
@@ -27,7 +29,7 @@ def build_library(verbose: bool = False) -> str:
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objects.append(obj)
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
     for cmd, proc in procs:
         out = proc.communicate()[0].decode()

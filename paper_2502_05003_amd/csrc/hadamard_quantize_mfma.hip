@@ -1,0 +1,429 @@
+// Matrix-core assisted fused Hadamard quantizer for bf16 rows and 4-bit codes (Algorithm 1, one
+// operand; Sec. 3.1 and 3.2 of arXiv 2502.05003).
+//
+// Why matrix cores in a bandwidth-bound kernel: at a block of 2048 the transform alone is 11
+// fp32 add/sub per element, plus about 7 for RMS, rounding, packing and the mask.  Packed fp32
+// math is off, so a CU retires 64 fp32 lane-ops per clock; 18 ops per element then cost more
+// time than the 2.6 bytes per element do at the HBM rate.  The first five stages act on the bf16
+// inputs themselves: as a product with the +-1 matrix H_32 they are exact on the bf16 MFMA
+// (exact products, fp32 accumulation: the same roundings as a butterfly network), and they cost
+// four MFMA instructions per row instead of 160 vector instructions.
+//
+// Data flow, one wavefront per row of 512 * HT elements:
+//   * the row is cut into tiles of 1024 elements seen as 32 x 32 matrices X[p][q] (element
+//     32 p + q); lane (m = l & 31, h = l >> 5) loads the 32 contiguous bytes of row p = m that
+//     hold q = 16 h .. 16 h + 15, which is exactly its share of the MFMA A operand;
+//   * D = X . (I (x) H_min(n,32)) transforms index bits 0..4; lane m then holds column q' = m,
+//     register r holds p = 8 (r >> 2) + 4 h + (r & 3): bits 5, 6 in r & 3, bit 7 in h, bits 8, 9
+//     in r >> 2, bits >= 10 in the tile number;
+//   * the stages on bits 5, 6, 8, 9 and on whole tiles are register-to-register; bit 7 is brought
+//     into registers by one half-wave swap (after which h holds bit 5);
+//   * sum of squares: the block transform is orthonormal, so it is taken from the packed bf16
+//     inputs with the two-way dot instruction;
+//   * codes and mask bits are formed in register order, packed per lane, transposed across lanes
+//     (8 x 8 nibbles, 32 x 32 bits) through the LDS crossbar, and stored as coalesced dwords in
+//     natural element order.
+#include "quest_device.h"
+#include "quest_internal.h"
+
+namespace quest {
+namespace {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+// Launch shape (overridable at build time for tuning experiments).
+#ifndef QUEST_HQ_MAX_BLOCKS
+#define QUEST_HQ_MAX_BLOCKS 1024
+#endif
+#ifndef QUEST_HQ_WAVES_PER_EU
+#define QUEST_HQ_WAVES_PER_EU 4
+#endif
+#ifndef QUEST_HQ_PREFETCH
+#define QUEST_HQ_PREFETCH 0
+#endif
+#ifndef QUEST_HQ_NONTEMPORAL
+#define QUEST_HQ_NONTEMPORAL 1
+#endif
+
+constexpr int kThreads = 256;
+constexpr int kRowsPerBlock = kThreads / 64;
+
+// In-lane element index iota = b6 + 2 b7 + 4 b8 + 8 b9 + 16 tile (bN = index bit N of the
+// element) -> accumulator register within its tile, after the half-wave swap:
+// b7 = r & 1, b6 = (r >> 1) & 1, b8 = (r >> 2) & 1, b9 = r >> 3.
+__host__ __device__ constexpr int reg_of_iota(int iota)
+{
+    return ((iota >> 1) & 1) | ((iota & 1) << 1) | (((iota >> 2) & 1) << 2) |
+           (((iota >> 3) & 1) << 3);
+}
+
+__device__ __forceinline__ void bfly(float &a, float &b)
+{
+    const float t = a;
+    a = t + b;
+    b = t - b;
+}
+
+__device__ __forceinline__ void store_word(uint32_t *p, uint32_t v)
+{
+#if QUEST_HQ_NONTEMPORAL
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+template <int XOR>
+__device__ __forceinline__ uint32_t swizzle_xor(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, (XOR << 10) | 0x1f);
+}
+
+// Per-lane constants of the lane <-> field transposes.  In stage s a lane keeps the fields whose
+// index bit s equals its own lane bit s and takes the others from lane ^ (1 << s), moved by
+// FIELD << s bits.  Moves of 8 or 16 bits are one byte permute; smaller ones a rotate and a
+// three-input select.
+template <int STAGES, int FIELD>
+struct TransposePlan {
+    uint32_t keep[STAGES];   // bit mask of the fields kept            (sub-byte stages)
+    uint32_t rot[STAGES];    // right-rotation applied to the partner  (sub-byte stages)
+    uint32_t sel[STAGES];    // v_perm selector {own, partner}         (byte and halfword stages)
+
+    __device__ __forceinline__ void init(int lane)
+    {
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) {
+            const int sh = FIELD << s;
+            uint32_t lo = 0;  // field positions whose index has bit s clear
+#pragma unroll
+            for (int f = 0; f < (1 << STAGES); ++f)
+                if (((f >> s) & 1) == 0)
+                    lo |= ((1u << FIELD) - 1u) << (f * FIELD);
+            const bool up = (lane >> s) & 1;
+            keep[s] = up ? ~lo : lo;
+            rot[s] = up ? (uint32_t)sh : (uint32_t)(32 - sh);
+            // v_perm_b32(partner, own, sel): selector bytes 0..3 pick from own, 4..7 from partner
+            if (sh == 8)
+                sel[s] = up ? 0x03070105u : 0x06020400u;
+            else if (sh == 16)
+                sel[s] = up ? 0x03020706u : 0x05040100u;
+            else
+                sel[s] = 0;
+        }
+    }
+
+    // After the call, field i of lane a holds what field a of lane i held (lanes modulo 2^STAGES).
+    __device__ __forceinline__ uint32_t apply(uint32_t d) const
+    {
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) {
+            uint32_t partner;
+            if (s == 0) partner = swizzle_xor<1>(d);
+            else if (s == 1) partner = swizzle_xor<2>(d);
+            else if (s == 2) partner = swizzle_xor<4>(d);
+            else if (s == 3) partner = swizzle_xor<8>(d);
+            else partner = swizzle_xor<16>(d);
+            if ((FIELD << s) >= 8) {
+                d = __builtin_amdgcn_perm(partner, d, sel[s]);
+            } else {
+                const uint32_t rotated = __builtin_amdgcn_alignbit(partner, partner, rot[s]);
+                // (keep & d) | (~keep & rotated) as one three-input bit operation
+                d = __builtin_amdgcn_bitop3_b32(keep[s], d, rotated, 0xCA);
+            }
+        }
+        return d;
+    }
+};
+
+/*
+ * HT: row length / 512.  LOG2N: log2 of the Hadamard block when it is >= 32; 5 also stands for
+ * every smaller block (then only the MFMA operand differs, and `log2n` carries the true value).
+ */
+template <int HT, int LOG2N, bool WITH_MASK>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(QUEST_HQ_WAVES_PER_EU)))
+void hq_mfma_kernel(
+    const uint16_t *__restrict__ x, int64_t rows, int64_t ld, int log2n, float alpha,
+    float trust_edge, uint8_t *__restrict__ codes, float *__restrict__ scales,
+    uint8_t *__restrict__ mask, float *__restrict__ xh_out)
+{
+    constexpr int T = (HT + 1) / 2;        // tiles of 1024 elements; the last one may be half
+    constexpr int NI = 8 * HT;             // elements per lane
+    constexpr int cols = 512 * HT;
+    constexpr bool kHalfTail = (HT & 1) != 0;
+    constexpr int kLevels = 16;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+
+    // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
+    v8bf bmat[2];
+    {
+        const int nb = log2n < 5 ? log2n : 5;
+        const int low = (1 << nb) - 1;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int q = 16 * h + 8 * s + e;
+                uint32_t v = 0;
+                if ((q >> nb) == (m >> nb))
+                    v = (__builtin_popcount(q & m & low) & 1) ? 0xBF80u : 0x3F80u;
+                if (e & 1)
+                    w[e >> 1] |= v << 16;
+                else
+                    w[e >> 1] = v;
+            }
+            __builtin_memcpy(&bmat[s], w, 16);
+        }
+    }
+    TransposePlan<3, 4> nibble_plan;
+    nibble_plan.init(lane);
+    TransposePlan<5, 1> bit_plan;
+    if (WITH_MASK)
+        bit_plan.init(lane);
+
+    // sqrt(n) and 1 / sqrt(n), correctly rounded: powers of two, times sqrt(2) for odd log2(n)
+    const float inv_sqrt_n = (log2n & 1) ? 0.70710678118654752440f / (float)(1 << (log2n >> 1))
+                                         : 1.0f / (float)(1 << (log2n >> 1));
+    const float sqrt_n = (log2n & 1) ? 1.41421356237309504880f * (float)(1 << (log2n >> 1))
+                                     : (float)(1 << (log2n >> 1));
+    const int code_word = ((lane >> 3) & 3) + 4 * h + 8 * (lane & 7);
+
+    // Raw inputs of one row: two 16-byte pieces per tile and lane.
+    struct RawRow {
+        uint4 a[T][2];
+    };
+    auto load_row = [&](int64_t row, RawRow &raw) {
+        const uint16_t *src = x + row * ld + 32 * m + 16 * h;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            raw.a[t][0] = make_uint4(0, 0, 0, 0);
+            raw.a[t][1] = make_uint4(0, 0, 0, 0);
+            if (!(kHalfTail && t == T - 1) || m < 16) {
+#if QUEST_HQ_NONTEMPORAL
+                const v4u n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
+                const v4u n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
+                raw.a[t][0] = make_uint4(n0.x, n0.y, n0.z, n0.w);
+                raw.a[t][1] = make_uint4(n1.x, n1.y, n1.z, n1.w);
+#else
+                raw.a[t][0] = *reinterpret_cast<const uint4 *>(src + 1024 * t);
+                raw.a[t][1] = *reinterpret_cast<const uint4 *>(src + 1024 * t + 8);
+#endif
+            }
+        }
+    };
+
+    const int64_t row_stride = (int64_t)gridDim.x * kRowsPerBlock;
+    int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave;
+#if QUEST_HQ_PREFETCH
+    RawRow next_raw;
+    if (row < rows)
+        load_row(row, next_raw);
+#endif
+    for (; row < rows; row += row_stride) {
+#if QUEST_HQ_PREFETCH
+        RawRow raw = next_raw;
+        if (row + row_stride < rows)
+            load_row(row + row_stride, next_raw);
+#else
+        RawRow raw;
+        load_row(row, raw);
+#endif
+        float acc[T][16];
+        float sumsq = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const uint4 a0 = raw.a[t][0], a1 = raw.a[t][1];
+            const uint32_t w[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                v2bf pair;
+                __builtin_memcpy(&pair, &w[i], 4);
+                sumsq = __builtin_amdgcn_fdot2_f32_bf16(pair, pair, sumsq, false);
+            }
+            v8bf f0, f1;
+            __builtin_memcpy(&f0, &a0, 16);
+            __builtin_memcpy(&f1, &a1, 16);
+            v16f z;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                z[r] = 0.0f;
+            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
+            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[t][r] = z[r];
+        }
+        sumsq = wave_sum(sumsq);
+
+        if (LOG2N > 5) {  // bit 5 = register bit 0
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2)
+                    bfly(acc[t][r], acc[t][r + 1]);
+        }
+        if (LOG2N > 6) {  // bit 6 = register bit 1
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (!(r & 2))
+                        bfly(acc[t][r], acc[t][r + 2]);
+        }
+        // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][r]),
+                                                                 __float_as_uint(acc[t][r + 1]),
+                                                                 false, false);
+                acc[t][r] = __uint_as_float(sw[0]);
+                acc[t][r + 1] = __uint_as_float(sw[1]);
+            }
+        if (LOG2N > 7) {
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2)
+                    bfly(acc[t][r], acc[t][r + 1]);
+        }
+        if (LOG2N > 8) {  // bit 8 = register bit 2
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (!(r & 4))
+                        bfly(acc[t][r], acc[t][r + 4]);
+        }
+        if (LOG2N > 9) {  // bit 9 = register bit 3
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    bfly(acc[t][r], acc[t][r + 8]);
+        }
+#pragma unroll
+        for (int k = 0; (1 << k) < T; ++k) {  // bits >= 10 pair whole tiles
+            if (LOG2N > 10 + k) {
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+                    if (!(t & (1 << k)) && (t | (1 << k)) < T) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            bfly(acc[t][r], acc[t | (1 << k)][r]);
+                    }
+            }
+        }
+
+        // Per-row constants in the un-normalised domain (x_h = raw / sqrt(n)).  The reciprocal and
+        // the square root are the hardware approximations (1 ulp): the codes are decided on
+        // raw * raw_to_cell, and a relative error of 1e-7 there is the size of one fp32 rounding.
+        const float rms = __builtin_amdgcn_sqrtf(sumsq * (1.0f / (float)cols));
+        const float clip = alpha * rms;
+        const bool zero_row = !(rms > 0.0f);
+        const float inv_step = zero_row ? 0.0f : (float)(kLevels - 1) * 0.5f * __builtin_amdgcn_rcpf(clip);
+        const float cell16 = inv_step * inv_sqrt_n * 16.0f;     // raw -> 16 * (position in grid cells)
+        const float trust_raw = trust_edge * rms * sqrt_n;
+        if (lane == 0)
+            scales[row] = clip * (1.0f / (float)(kLevels - 1));
+
+        if (xh_out) {
+            float *dst = xh_out + row * cols + lane;   // element = lane + 64 iota
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                dst[64 * i] = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
+        }
+
+        // codes: byte = sat_u8(rne(16 cell + 128 - 1/2)); its high nibble is
+        // clamp(floor(cell) + 8, 0, 15) = c.  Eight per dword in iota order, then the transpose.
+        uint32_t *code_row = reinterpret_cast<uint32_t *>(codes + row * (cols / 2));
+#pragma unroll
+        for (int d = 0; d < HT; ++d) {
+            uint32_t even = 0, odd = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float v = acc[(8 * d + i) >> 4][reg_of_iota((8 * d + i) & 15)];
+                const float t = __fmaf_rn(v, cell16, 127.5f);
+                if (i & 1)
+                    odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
+                else
+                    even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+            }
+            const uint32_t packed = ((even >> 4) & 0x0f0f0f0fu) | (odd & 0xf0f0f0f0u);
+            store_word(code_row + code_word + 64 * d, nibble_plan.apply(packed));
+        }
+
+        // trust mask: one bit per element in iota order (sign of trust_raw - |raw|), then the
+        // 32 x 32 bit transpose; lane m ends up with the bits of 32 consecutive elements
+        if (WITH_MASK) {
+            uint32_t *mask_row = reinterpret_cast<uint32_t *>(mask + row * (cols / 8));
+#pragma unroll
+            for (int c = 0; c * 32 < NI; ++c) {
+                const int count = (NI - 32 * c) < 32 ? (NI - 32 * c) : 32;
+                uint32_t untrusted = 0;
+#pragma unroll
+                for (int i = count - 1; i >= 0; --i) {
+                    const float v = acc[(32 * c + i) >> 4][reg_of_iota((32 * c + i) & 15)];
+                    const float slack = trust_raw - fabsf(v);          // negative <=> untrusted
+                    untrusted = __builtin_amdgcn_alignbit(untrusted, __float_as_uint(slack), 31);
+                }
+                uint32_t trusted = ~untrusted;
+                if (count < 32)
+                    trusted &= (1u << count) - 1u;
+                trusted = bit_plan.apply(trusted);
+                if (m < count)
+                    store_word(mask_row + h + 2 * (m + 32 * c), trusted);
+            }
+        }
+    }
+}
+
+template <int HT, int LOG2N>
+void launch(const QuantizeArgs &a, hipStream_t stream)
+{
+    const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int64_t max_blocks = QUEST_HQ_MAX_BLOCKS;
+    const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
+    const auto *x = static_cast<const uint16_t *>(a.x);
+    if (a.mask)
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, true>), grid, dim3(kThreads), 0, stream, x,
+                           a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
+                           a.xh_out);
+    else
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, false>), grid, dim3(kThreads), 0, stream, x,
+                           a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
+                           a.xh_out);
+}
+
+}  // namespace
+
+// Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
+// Covered: bf16 input, b = 4, rows of 512, 1024, 2048, 4096 or 5632 elements, and a Hadamard
+// block of at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row.
+bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream)
+{
+    if (a.dtype != QUEST_BF16 || a.bits != 4 || (a.cols % 512) != 0)
+        return false;
+    const int ht = (int)(a.cols / 512);
+    const int l = a.log2n <= 5 ? 5 : a.log2n;
+#define QUEST_CASE(HT_, L_)                       \
+    if (ht == HT_ && l == L_) {                   \
+        launch<HT_, L_>(a, stream);               \
+        return true;                              \
+    }
+    QUEST_CASE(1, 5) QUEST_CASE(1, 7) QUEST_CASE(1, 9)
+    QUEST_CASE(2, 5) QUEST_CASE(2, 7) QUEST_CASE(2, 9) QUEST_CASE(2, 10)
+    QUEST_CASE(4, 5) QUEST_CASE(4, 7) QUEST_CASE(4, 9) QUEST_CASE(4, 10) QUEST_CASE(4, 11)
+    QUEST_CASE(8, 5) QUEST_CASE(8, 7) QUEST_CASE(8, 9) QUEST_CASE(8, 10) QUEST_CASE(8, 11) QUEST_CASE(8, 12)
+    QUEST_CASE(11, 5) QUEST_CASE(11, 7) QUEST_CASE(11, 9)
+#undef QUEST_CASE
+    return false;
+}
+
+}  // namespace quest

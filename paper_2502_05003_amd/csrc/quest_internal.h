@@ -25,6 +25,8 @@ struct QuantizeArgs {
 };
 
 hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream);
+// Matrix-core kernel for the common bf16 / 4-bit shapes; false means "not covered, nothing launched".
+bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream);
 
 struct GemmArgs {
     const uint8_t *a_codes;
