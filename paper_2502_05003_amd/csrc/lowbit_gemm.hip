@@ -166,16 +166,287 @@ __global__ __launch_bounds__(kThreads) void lowbit_gemm_kernel(
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Main kernel for b = 4.  Workgroup tile 256 (M) x 128 (N), four waves of 128 x 64 (eight 32 x 32
+// accumulator tiles each), 128 contraction elements per step, two LDS stages, two workgroups per
+// CU so that one group's staging, barriers and epilogue hide behind the other's MFMAs.
+//
+// LDS holds the codes still packed (64 bytes per row and step): the LDS pipe moves 128 bytes per
+// clock and CU, and widened bytes would need three quarters of that.  A fetched 16-byte chunk
+// holds 32 offset-binary codes c; flipping bit 3 of every nibble (done once, while staging) gives
+// the two's-complement cell index k.  A nibble moved to the top of a byte with bit 3 set below it
+// is the signed byte 16 k + 8 = 8 (2k + 1) = 8 u, so widening costs three vector ops per eight
+// codes at the consumer.  Both operands carry the factor 8: the MFMAs accumulate
+// 64 * sum u_a u_b (below 2^31 for K <= 65536), and the epilogue takes the 64 out exactly.
+// ------------------------------------------------------------------------------------------
+
+// two floats -> packed bf16 pair (round to nearest even), low half = first
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    v2bf p;
+    p[0] = (__bf16)lo;
+    p[1] = (__bf16)hi;
+    uint32_t u;
+    __builtin_memcpy(&u, &p, 4);
+    return u;
+}
+
+constexpr int TM = 256, TN = 128, TK = 128;
+constexpr int kTileThreads = 256;
+constexpr int kRowBytes = TK / 2;                      // packed bytes per tile row and step
+constexpr int kStageBytes = (TM + TN) * kRowBytes;     // 24 KiB
+constexpr int kParkBytes = 4 * 128 * 64 * 2;           // epilogue: four waves x 128 x 64 bf16
+constexpr int kTileLds = kParkBytes + TN * 4;          // + the tile's weight scales
+
+// 16-byte chunk c (0..3) of tile row `row` lives at chunk c ^ swz(row): eight consecutive rows
+// reading the same logical chunk touch eight different 16-byte bank groups
+__device__ __forceinline__ int swz(int row)
+{
+    return (row >> 1) & 3;
+}
+
+// eight two's-complement nibbles -> the signed bytes 8 u of the even and of the odd elements
+__device__ __forceinline__ void widen8(uint32_t k, int &even, int &odd)
+{
+    even = (int)(((k << 4) & 0xf0f0f0f0u) | 0x08080808u);
+    odd = (int)((k & 0xf0f0f0f0u) | 0x08080808u);
+}
+
+__global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
+    const uint8_t *__restrict__ a_codes, const float *__restrict__ a_scales,
+    const uint8_t *__restrict__ b_codes, const float *__restrict__ b_scales, int M, int N, int K,
+    int tiles_m, int tiles_n, uint16_t *__restrict__ y, int64_t ld_y,
+    int32_t *__restrict__ acc_out)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (8 of them, each with
+    // its own L2), so give each XCD one contiguous run of tiles, ordered four tile-rows deep:
+    // the tiles an XCD works on at a time share a few row panels of A and column panels of B.
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total)
+        return;
+    const int band = logical / (4 * tiles_n);
+    const int band_rows = min(4, tiles_m - band * 4);
+    const int in_band = logical - band * 4 * tiles_n;
+    const int tile_m = band * 4 + in_band % band_rows;
+    const int tile_n = in_band / band_rows;
+    const int m0 = tile_m * TM, n0 = tile_n * TN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, lh = lane >> 5;
+
+    // staging role: chunk tid % 4 of rows tid / 4 + 64 i (four rows of A, two of B)
+    const int st_row = tid >> 2, st_chunk = tid & 3;
+    const int64_t row_bytes = (int64_t)K / 2;
+    const uint8_t *src[6];
+    int dst_off[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        const int row = st_row + 64 * (i < 4 ? i : i - 4);
+        const uint8_t *base = i < 4 ? a_codes + (int64_t)min(m0 + row, M - 1) * row_bytes
+                                    : b_codes + (int64_t)min(n0 + row, N - 1) * row_bytes;
+        src[i] = base + st_chunk * 16;
+        dst_off[i] = (i < 4 ? 0 : TM * kRowBytes) + row * kRowBytes + ((st_chunk ^ swz(row)) << 4);
+    }
+
+    v16i acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0;
+
+    const int steps = K / TK;
+    uint4 g[6];
+    auto fetch = [&](int i, int step) {
+        g[i] = *reinterpret_cast<const uint4 *>(src[i] + (int64_t)min(step, steps - 1) * kRowBytes);
+    };
+    auto stash = [&](uint8_t *stage, int i) {
+        *reinterpret_cast<uint4 *>(stage + dst_off[i]) =
+            make_uint4(g[i].x ^ 0x88888888u, g[i].y ^ 0x88888888u, g[i].z ^ 0x88888888u,
+                       g[i].w ^ 0x88888888u);
+    };
+
+#pragma unroll
+    for (int i = 0; i < 6; ++i)
+        fetch(i, 0);
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        stash(smem, i);
+        fetch(i, 1);
+    }
+    __syncthreads();
+
+    // fragment addresses: rows lm + 32 i share bits 1..2, hence one swizzle value per lane;
+    // chunk 2 p + lh of a row feeds this lane's share of sub-steps 2 p and 2 p + 1
+    const int x = swz(lm);
+    const int a_off = (wm * 128 + lm) * kRowBytes;
+    const int b_off = TM * kRowBytes + (wn * 64 + lm) * kRowBytes;
+    auto load_frags = [&](const uint8_t *stage, int p, uint4 (&af)[4], uint4 (&bf)[2]) {
+        const int off = ((2 * p + lh) ^ x) << 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            af[i] = *reinterpret_cast<const uint4 *>(stage + a_off + i * 32 * kRowBytes + off);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            bf[j] = *reinterpret_cast<const uint4 *>(stage + b_off + j * 32 * kRowBytes + off);
+    };
+    // the MFMAs of two sub-steps: words (0,1) of each fragment, then words (2,3)
+    auto multiply = [&](const uint4 (&af)[4], const uint4 (&bf)[2]) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            v4i bw[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                int w0, w1, w2, w3;
+                widen8(e ? bf[j].z : bf[j].x, w0, w1);
+                widen8(e ? bf[j].w : bf[j].y, w2, w3);
+                bw[j] = v4i{w0, w1, w2, w3};
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int w0, w1, w2, w3;
+                widen8(e ? af[i].z : af[i].x, w0, w1);
+                widen8(e ? af[i].w : af[i].y, w2, w3);
+                const v4i aw = v4i{w0, w1, w2, w3};
+#pragma unroll
+                for (int j = 0; j < 2; ++j)   // weight fragment as the row operand: transposed tiles
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bw[j], aw, acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+
+    uint4 af[2][4], bf[2][2];
+    load_frags(smem, 0, af[0], bf[0]);
+    for (int step = 0; step < steps; ++step) {
+        uint8_t *cur = smem + (step & 1) * kStageBytes;
+        uint8_t *nxt = smem + ((step + 1) & 1) * kStageBytes;
+        // g[] holds step + 1 (fetched one step ago).  Each chunk is stashed into the idle stage
+        // and its register refilled with step + 2; past the end the fetches repeat the last step
+        // and the stashes land in a stage nobody reads, which keeps the loop body branch-free.
+        load_frags(cur, 1, af[1], bf[1]);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            stash(nxt, i);
+            fetch(i, step + 2);
+        }
+        multiply(af[0], bf[0]);
+#pragma unroll
+        for (int i = 3; i < 6; ++i) {
+            stash(nxt, i);
+            fetch(i, step + 2);
+        }
+        multiply(af[1], bf[1]);
+        __syncthreads();
+        load_frags(nxt, 0, af[0], bf[0]);
+    }
+
+    // Epilogue.  Each accumulator tile is the transpose of an output tile: lane l holds output row
+    // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
+    // consecutive columns.  Each wave converts its 128 x 64 block to bf16, parks it in its own
+    // 16 KiB of LDS (16-byte chunks swizzled by row) and writes it out as 128-byte row segments.
+    float *scale_lds = reinterpret_cast<float *>(smem + kParkBytes);
+    __syncthreads();   // every wave is done with the stages
+    if (tid < TN)
+        scale_lds[tid] = b_scales[min(n0 + tid, N - 1)];
+    __syncthreads();
+
+    if (acc_out) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * 128 + i * 32 + lm;
+                    const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    if (m < M && n < N)
+                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> 6;   // exact: a multiple of 64
+                }
+    }
+    if (!y)
+        return;
+
+    uint8_t *park = smem + wave * (128 * 128);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = i * 32 + lm;   // row within the wave's block
+        // float(64 acc) * (s_a / 64) rounds exactly like float(acc) * s_a
+        const float sa = a_scales[min(m0 + wm * 128 + row, M - 1)] * (1.0f / 64.0f);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = j * 32 + 8 * q + 4 * lh;   // first of four consecutive columns
+                const float4 sb = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + col);
+                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
+                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
+                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
+                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
+                const int chunk = (col >> 3) ^ (row & 7);
+                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
+                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+            }
+        }
+    }
+    // each pass: 8 rows of 128 bytes, lane l takes 16-byte chunk l % 8 of row l / 8
+    uint16_t *y_base = y + (int64_t)(m0 + wm * 128) * ld_y + n0 + wn * 64;
+    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
+                           (n0 + wn * 64 + 64 <= N);
+#pragma unroll 4
+    for (int pass = 0; pass < 16; ++pass) {
+        const int row = pass * 8 + (lane >> 3);
+        const int c = lane & 7;
+        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
+        if (m0 + wm * 128 + row >= M)
+            continue;
+        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
+        if (vector_ok) {
+            *reinterpret_cast<uint4 *>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n0 + wn * 64 + c * 8 + e < N)
+                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream)
 {
     if (a.M == 0 || a.N == 0)
         return hipSuccess;
-    const dim3 grid((unsigned)((a.N + BN - 1) / BN), (unsigned)((a.M + BM - 1) / BM));
-    const dim3 block(kThreads);
     const int levels = 1 << a.bits;
     auto *y = static_cast<uint16_t *>(a.y);
+    if (a.bits == 4 && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
+        const int tiles_m = (int)((a.M + TM - 1) / TM), tiles_n = (int)((a.N + TN - 1) / TN);
+        const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
+            if (err != hipSuccess)
+                return err;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(lowbit_gemm_tile_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kTileThreads),
+                           kTileLds, stream, a.a_codes, a.a_scales, a.b_codes, a.b_scales, (int)a.M,
+                           (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y, a.acc_out);
+        return hipGetLastError();
+    }
+    const dim3 grid((unsigned)((a.N + BN - 1) / BN), (unsigned)((a.M + BM - 1) / BM));
+    const dim3 block(kThreads);
     switch (a.cb) {
     case 4:
         hipLaunchKernelGGL(lowbit_gemm_kernel<4>, grid, block, 0, stream, a.a_codes, a.a_scales,
