@@ -173,10 +173,9 @@ __global__ __launch_bounds__(kThreads) void lowbit_gemm_kernel(
 // CU so that one group's staging, barriers and epilogue hide behind the other's MFMAs.
 //
 // LDS holds the codes still packed (64 bytes per row and step): the LDS pipe moves 128 bytes per
-// clock and CU, and widened bytes would need three quarters of that.  A fetched 16-byte chunk
-// holds 32 offset-binary codes c; flipping bit 3 of every nibble (done once, while staging) gives
-// the two's-complement cell index k.  A nibble moved to the top of a byte with bit 3 set below it
-// is the signed byte 16 k + 8 = 8 (2k + 1) = 8 u, so widening costs three vector ops per eight
+// clock and CU, and widened bytes would need three quarters of that.  A nibble c moved to the top
+// of a byte, with its top bit flipped (c - 8 in two's complement) and bit 3 set below it, is the
+// signed byte 16 (c - 8) + 8 = 8 (2c - 15) = 8 u, so widening costs three vector ops per eight
 // codes at the consumer.  Both operands carry the factor 8: the MFMAs accumulate
 // 64 * sum u_a u_b (below 2^31 for K <= 65536), and the epilogue takes the 64 out exactly.
 // ------------------------------------------------------------------------------------------
@@ -200,18 +199,22 @@ constexpr int kStageBytes = (TM + TN) * kRowBytes;     // 24 KiB
 constexpr int kParkBytes = 4 * 128 * 64 * 2;           // epilogue: four waves x 128 x 64 bf16
 constexpr int kTileLds = kParkBytes + TN * 4;          // + the tile's weight scales
 
-// 16-byte chunk c (0..3) of tile row `row` lives at chunk c ^ swz(row): eight consecutive rows
-// reading the same logical chunk touch eight different 16-byte bank groups
+// 16-byte chunk c (0..3) of tile row `row` lives at chunk c ^ swz(row).  The LDS serves 128-bit
+// accesses sixteen lanes at a time over 64 banks (256 bytes): sixteen consecutive rows reading
+// the same logical chunk must hit sixteen different 16-byte slots modulo 256 bytes (measured).
 __device__ __forceinline__ int swz(int row)
 {
-    return (row >> 1) & 3;
+    return (row >> 2) & 3;
 }
 
-// eight two's-complement nibbles -> the signed bytes 8 u of the even and of the odd elements
-__device__ __forceinline__ void widen8(uint32_t k, int &even, int &odd)
+// Eight offset-binary codes c (one packed dword) -> the signed bytes 8 u = 16 (c - 8) + 8 of the
+// odd and of the even elements.  With the nibble in the top half of its byte this is one
+// three-input bit function of (word, 0xf0f0f0f0, 0x88888888): keep bits 4..6, invert bit 7 (the
+// offset-binary -> two's-complement flip), force bit 3, clear bits 0..2.
+__device__ __forceinline__ void widen8(uint32_t w, uint32_t nibble_mask, int &even, int &odd)
 {
-    even = (int)(((k << 4) & 0xf0f0f0f0u) | 0x08080808u);
-    odd = (int)((k & 0xf0f0f0f0u) | 0x08080808u);
+    odd = (int)__builtin_amdgcn_bitop3_b32(w, nibble_mask, 0x88888888u, 0x6A);
+    even = (int)__builtin_amdgcn_bitop3_b32(w << 4, nibble_mask, 0x88888888u, 0x6A);
 }
 
 __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
@@ -264,28 +267,25 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0;
 
-    const int steps = K / TK;
-    uint4 g[6];
-    auto fetch = [&](int i, int step) {
-        g[i] = *reinterpret_cast<const uint4 *>(src[i] + (int64_t)min(step, steps - 1) * kRowBytes);
-    };
-    auto stash = [&](uint8_t *stage, int i) {
-        *reinterpret_cast<uint4 *>(stage + dst_off[i]) =
-            make_uint4(g[i].x ^ 0x88888888u, g[i].y ^ 0x88888888u, g[i].z ^ 0x88888888u,
-                       g[i].w ^ 0x88888888u);
-    };
+    // kept in a vector register (opaque to constant folding) so that widen8 is one instruction
+    uint32_t nibble_mask = 0xf0f0f0f0u;
+    asm volatile("" : "+v"(nibble_mask));
 
-#pragma unroll
-    for (int i = 0; i < 6; ++i)
-        fetch(i, 0);
-#pragma unroll
-    for (int i = 0; i < 6; ++i) {
-        stash(smem, i);
-        fetch(i, 1);
-    }
+    const int steps = K / TK;
+    uint4 g0, g1, g2, g3, g4, g5;   // six staged chunks (named, so that they live in registers)
+#define QUEST_FETCH(G, I, STEP) \
+    G = *reinterpret_cast<const uint4 *>(src[I] + (int64_t)min((STEP), steps - 1) * kRowBytes)
+#define QUEST_STASH(STAGE, G, I) *reinterpret_cast<uint4 *>((STAGE) + dst_off[I]) = G
+
+    QUEST_FETCH(g0, 0, 0); QUEST_FETCH(g1, 1, 0); QUEST_FETCH(g2, 2, 0);
+    QUEST_FETCH(g3, 3, 0); QUEST_FETCH(g4, 4, 0); QUEST_FETCH(g5, 5, 0);
+    QUEST_STASH(smem, g0, 0); QUEST_STASH(smem, g1, 1); QUEST_STASH(smem, g2, 2);
+    QUEST_STASH(smem, g3, 3); QUEST_STASH(smem, g4, 4); QUEST_STASH(smem, g5, 5);
+    QUEST_FETCH(g0, 0, 1); QUEST_FETCH(g1, 1, 1); QUEST_FETCH(g2, 2, 1);
+    QUEST_FETCH(g3, 3, 1); QUEST_FETCH(g4, 4, 1); QUEST_FETCH(g5, 5, 1);
     __syncthreads();
 
-    // fragment addresses: rows lm + 32 i share bits 1..2, hence one swizzle value per lane;
+    // fragment addresses: rows lm + 32 i share bits 2..3, hence one swizzle value per lane;
     // chunk 2 p + lh of a row feeds this lane's share of sub-steps 2 p and 2 p + 1
     const int x = swz(lm);
     const int a_off = (wm * 128 + lm) * kRowBytes;
@@ -307,15 +307,15 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 int w0, w1, w2, w3;
-                widen8(e ? bf[j].z : bf[j].x, w0, w1);
-                widen8(e ? bf[j].w : bf[j].y, w2, w3);
+                widen8(e ? bf[j].z : bf[j].x, nibble_mask, w0, w1);
+                widen8(e ? bf[j].w : bf[j].y, nibble_mask, w2, w3);
                 bw[j] = v4i{w0, w1, w2, w3};
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 int w0, w1, w2, w3;
-                widen8(e ? af[i].z : af[i].x, w0, w1);
-                widen8(e ? af[i].w : af[i].y, w2, w3);
+                widen8(e ? af[i].z : af[i].x, nibble_mask, w0, w1);
+                widen8(e ? af[i].w : af[i].y, nibble_mask, w2, w3);
                 const v4i aw = v4i{w0, w1, w2, w3};
 #pragma unroll
                 for (int j = 0; j < 2; ++j)   // weight fragment as the row operand: transposed tiles
@@ -333,21 +333,20 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
         // and its register refilled with step + 2; past the end the fetches repeat the last step
         // and the stashes land in a stage nobody reads, which keeps the loop body branch-free.
         load_frags(cur, 1, af[1], bf[1]);
-#pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            stash(nxt, i);
-            fetch(i, step + 2);
-        }
+        QUEST_STASH(nxt, g0, 0); QUEST_FETCH(g0, 0, step + 2);
+        QUEST_STASH(nxt, g1, 1); QUEST_FETCH(g1, 1, step + 2);
+        QUEST_STASH(nxt, g2, 2); QUEST_FETCH(g2, 2, step + 2);
         multiply(af[0], bf[0]);
-#pragma unroll
-        for (int i = 3; i < 6; ++i) {
-            stash(nxt, i);
-            fetch(i, step + 2);
-        }
+        QUEST_STASH(nxt, g3, 3); QUEST_FETCH(g3, 3, step + 2);
+        QUEST_STASH(nxt, g4, 4); QUEST_FETCH(g4, 4, step + 2);
+        QUEST_STASH(nxt, g5, 5); QUEST_FETCH(g5, 5, step + 2);
         multiply(af[1], bf[1]);
         __syncthreads();
         load_frags(nxt, 0, af[0], bf[0]);
     }
+
+#undef QUEST_FETCH
+#undef QUEST_STASH
 
     // Epilogue.  Each accumulator tile is the transpose of an output tile: lane l holds output row
     // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
