@@ -65,31 +65,28 @@ class BufferSet:
         self.dw = torch.empty(N, K, dtype=b16, device=dev)
 
 
-def run_step(q, b, cfg, events=None):
-    """Enqueue the seven kernels of one step; `events` (name -> (start, end)) times each one."""
+def step_kernels(q, b, cfg):
+    """The seven launches of one step as (name, thunk) pairs, in execution order."""
     M, N, K, n, bits = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"], cfg["bits"]
+    return [
+        ("quantize_x", lambda: q.quest_hadamard_quantize(b.x, n, bits, codes=b.x_codes,
+                                                         scales=b.x_scales, mask=b.x_mask)),
+        ("quantize_w", lambda: q.quest_hadamard_quantize(b.w, n, bits, codes=b.w_codes,
+                                                         scales=b.w_scales, mask=b.w_mask)),
+        ("lowbit_gemm", lambda: q.quest_lowbit_gemm(b.x_codes, b.x_scales, b.w_codes, b.w_scales,
+                                                    K, bits, y=b.y)),
+        ("grad_gemm_x", lambda: q.quest_grad_gemm(0, b.dy, b.w_codes, b.w_scales, bits, M, N, K,
+                                                  out=b.g_x)),
+        ("grad_gemm_w", lambda: q.quest_grad_gemm(1, b.dy, b.x_codes, b.x_scales, bits, M, N, K,
+                                                  out=b.g_w)),
+        ("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx)),
+        ("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw)),
+    ]
 
-    def timed(name, fn):
-        if events is None:
-            fn()
-        else:
-            start, end = events[name]
-            start.record()
-            fn()
-            end.record()
 
-    timed("quantize_x", lambda: q.quest_hadamard_quantize(b.x, n, bits, codes=b.x_codes,
-                                                          scales=b.x_scales, mask=b.x_mask))
-    timed("quantize_w", lambda: q.quest_hadamard_quantize(b.w, n, bits, codes=b.w_codes,
-                                                          scales=b.w_scales, mask=b.w_mask))
-    timed("lowbit_gemm", lambda: q.quest_lowbit_gemm(b.x_codes, b.x_scales, b.w_codes, b.w_scales,
-                                                     K, bits, y=b.y))
-    timed("grad_gemm_x", lambda: q.quest_grad_gemm(0, b.dy, b.w_codes, b.w_scales, bits, M, N, K,
-                                                   out=b.g_x))
-    timed("grad_gemm_w", lambda: q.quest_grad_gemm(1, b.dy, b.x_codes, b.x_scales, bits, M, N, K,
-                                                   out=b.g_w))
-    timed("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx))
-    timed("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw))
+def run_step(q, b, cfg):
+    for _, launch in step_kernels(q, b, cfg):
+        launch()
 
 
 def cpu_baseline(x_bits, w_bits, dy_bits, cfg):
@@ -155,16 +152,35 @@ def main():
         run_step(q, sets[i % n_sets], cfg)
     torch.cuda.synchronize()
 
-    events = [{k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for k in KERNELS} for _ in range(args.steps)]
-    torch.cuda.synchronize()
+    # Timed region: exactly `steps` whole steps, host clock, synchronised on both sides.
     t0 = time.perf_counter()
     for i in range(args.steps):
-        run_step(q, sets[i % n_sets], cfg, events[i])
+        run_step(q, sets[i % n_sets], cfg)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    ms = {k: float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in events])) for k in KERNELS}
+    # Per-kernel durations for the rooflines: the same `steps` steps again, each kernel bracketed
+    # by HIP events on the stream it is launched on (torch's current stream).  An event pair around
+    # a single launch also counts idle gaps at both ends, a few microseconds; half the duration of
+    # an empty pair is subtracted (calibrated against the rocprofv3 kernel durations of this same
+    # command, kept under profiles/).
+    events = [{k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for k in KERNELS} for _ in range(args.steps)]
+    empty = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        for name, launch in step_kernels(q, sets[i % n_sets], cfg):
+            start, end = events[i][name]
+            start.record()
+            launch()
+            end.record()
+        empty[i][0].record()
+        empty[i][1].record()
+    torch.cuda.synchronize()
+    gap_ms = 0.5 * float(np.median([a.elapsed_time(b) for a, b in empty]))
+    ms = {k: max(float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in events])) - gap_ms, 1e-6)
+          for k in KERNELS}
     ms_per_step = elapsed * 1e3 / args.steps
     gemm_ops = 2.0 * M * N * K
     step_ops = 3.0 * gemm_ops
@@ -204,7 +220,7 @@ def main():
                                f"W {N}x{K} bf16 N(0,0.02^2), dY {M}x{N} bf16, Hadamard block "
                                f"{cfg['had_block']}, b={cfg['bits']}, forward+backward",
                    "M": M, "N": N, "K": K, "had_block": cfg["had_block"], "bits": cfg["bits"],
-                   "buffer_sets": n_sets},
+                   "buffer_sets": n_sets, "event_gap_us_subtracted": gap_ms * 1e3},
         "quantizer_GBps": rooflines["quantize_x"]["achieved"],
         "gemm_TOPS": rooflines["lowbit_gemm"]["achieved"],
         "forward_TOPS": gemm_ops / ((ms["quantize_x"] + ms["quantize_w"] + ms["lowbit_gemm"]) * 1e-3) / 1e12,
