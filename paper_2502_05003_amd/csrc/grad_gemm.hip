@@ -3,6 +3,8 @@
 // matrix cores with fp32 accumulation.
 //   which = 0:  out[M, K] = dy[M, N]   * what_h[N, K]   (contraction over N)
 //   which = 1:  out[N, K] = dy[M, N]^T * xhat_h[M, K]   (contraction over M)
+#include <utility>
+
 #include "quest_device.h"
 #include "quest_internal.h"
 
@@ -131,11 +133,17 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
     return u;
 }
 
-struct GradStaged {
-    uint4 left[8];     // left operand: eight 16-byte pieces
-    uint32_t code[8];  // right operand: eight codes of each of eight contraction rows
-    float scale[8];    // and the scales of those rows
-};
+// compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>)
+template <int... Is, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
 
 template <bool TRANSPOSED>
 __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
@@ -167,93 +175,21 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     //   direct left operand: chunk tid % 8 of rows tid / 8 + 32 i
     //   transposed operands: 8 x 8 sub-block, contraction group mg = tid % 8, column group cg = tid / 8
     const int mg = tid & 7, cg = tid >> 3;
-    const uint16_t *left_src = TRANSPOSED ? dy + (int64_t)(8 * mg) * ld_dy + r0 + 8 * cg
-                                          : dy + (int64_t)(r0 + (tid >> 3)) * ld_dy + 8 * (tid & 7);
-    const uint8_t *code_src = q_codes + (int64_t)(8 * mg) * q_row_bytes + (k0 + 8 * cg) / 2;
-    const float *scale_src = q_scales + 8 * mg;
+    // every global address is a wave-uniform base plus a 32-bit per-thread byte offset that does not
+    // change from step to step (one register per stream instead of one pointer per piece)
+    // which = 0: the left pieces go from global memory straight into LDS (no registers): lane l of a
+    // wave lands at LDS offset 16 l of the wave's 1 KiB (8 rows x 128 bytes), so it fetches the
+    // logical chunk that belongs in that physical slot
+    const int dma_row = tid >> 3;                                   // + 32 jj
+    const int dma_chunk = (tid & 7) ^ gswz(dma_row);                // gswz(row + 32 jj) = gswz(row)
+    const uint32_t left_toff = TRANSPOSED ? (uint32_t)((8 * mg) * ld_dy + 8 * cg) * 2u
+                                          : (uint32_t)(dma_row * ld_dy + 8 * dma_chunk) * 2u;
+    const uint32_t code_toff = (uint32_t)((8 * mg) * q_row_bytes + 4 * cg);
+    const uint32_t scale_toff = (uint32_t)(8 * mg) * 4u;
+    const char *left_base = reinterpret_cast<const char *>(TRANSPOSED ? dy + r0 : dy + (int64_t)r0 * ld_dy);
+    const char *code_base = reinterpret_cast<const char *>(q_codes + k0 / 2);
+    const char *scale_base = reinterpret_cast<const char *>(q_scales);
     const int steps = C / GC;
-
-    auto fetch = [&](int step, GradStaged &g) {
-        const int64_t c0 = (int64_t)min(step, steps - 1) * GC;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (TRANSPOSED)
-                g.left[i] = *reinterpret_cast<const uint4 *>(left_src + (c0 + i) * ld_dy);
-            else
-                g.left[i] = *reinterpret_cast<const uint4 *>(left_src + (int64_t)(32 * i) * ld_dy + c0);
-            g.code[i] = *reinterpret_cast<const uint32_t *>(code_src + (c0 + i) * q_row_bytes);
-            g.scale[i] = scale_src[c0 + i];
-        }
-    };
-
-    auto stash_left = [&](uint8_t *stage, const GradStaged &g) {
-        if (TRANSPOSED) {
-            // left[r] holds dy[c0 + 8 mg + r][r0 + 8 cg .. + 8]; column j of the sub-block becomes
-            // chunk mg of left row 8 cg + j: halves of rows (2a, 2a+1) are paired by one byte permute
-            const uint32_t w[8][4] = {
-                {g.left[0].x, g.left[0].y, g.left[0].z, g.left[0].w}, {g.left[1].x, g.left[1].y, g.left[1].z, g.left[1].w},
-                {g.left[2].x, g.left[2].y, g.left[2].z, g.left[2].w}, {g.left[3].x, g.left[3].y, g.left[3].z, g.left[3].w},
-                {g.left[4].x, g.left[4].y, g.left[4].z, g.left[4].w}, {g.left[5].x, g.left[5].y, g.left[5].z, g.left[5].w},
-                {g.left[6].x, g.left[6].y, g.left[6].z, g.left[6].w}, {g.left[7].x, g.left[7].y, g.left[7].z, g.left[7].w}};
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                uint32_t d[4];
-#pragma unroll
-                for (int a = 0; a < 4; ++a)
-                    d[a] = __builtin_amdgcn_perm(w[2 * a + 1][j >> 1], w[2 * a][j >> 1],
-                                                 (j & 1) ? 0x07060302u : 0x05040100u);
-                const int row = 8 * cg + j;
-                *reinterpret_cast<uint4 *>(stage + row * kGRowBytes + ((mg ^ gswz(row)) << 4)) =
-                    make_uint4(d[0], d[1], d[2], d[3]);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = (tid >> 3) + 32 * i;
-                *reinterpret_cast<uint4 *>(stage + row * kGRowBytes + (((tid & 7) ^ gswz(row)) << 4)) =
-                    g.left[i];
-            }
-        }
-    };
-
-    // codes of contraction rows (2a, 2a+1), columns 0..7 of the sub-block -> bf16 pairs, i.e. word a
-    // of the eight right-operand chunks.  value = bf16(fp32(s * u)), u = 2 c - (L - 1).
-    auto stash_right_pair = [&](uint8_t *stage, const GradStaged &g, int a, uint32_t (&word)[8]) {
-        (void)stage;
-        float v[2][8];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t q = g.code[2 * a + h];
-            const uint32_t even = q & 0x0f0f0f0fu, odd = (q >> 4) & 0x0f0f0f0fu;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t bytes = (e & 1) ? odd : even;
-                const float c = (float)((bytes >> (8 * (e >> 1))) & 0xffu);
-                v[h][e] = __fmul_rn(g.scale[2 * a + h], __fmaf_rn(c, 2.0f, offset));
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            word[e] = pack2_bf16(v[0][e], v[1][e]);
-    };
-    auto stash_right = [&](uint8_t *stage, const GradStaged &g) {
-        uint32_t chunk[8][4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            uint32_t word[8];
-            stash_right_pair(stage, g, a, word);
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                chunk[e][a] = word[e];
-        }
-        uint8_t *right = stage + GT * kGRowBytes;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int row = 8 * cg + j;
-            *reinterpret_cast<uint4 *>(right + row * kGRowBytes + ((mg ^ gswz(row)) << 4)) =
-                make_uint4(chunk[j][0], chunk[j][1], chunk[j][2], chunk[j][3]);
-        }
-    };
 
     v16f acc[4][4];
 #pragma unroll
@@ -264,52 +200,135 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0.0f;
 
-    GradStaged g;
-    fetch(0, g);
-    stash_left(smem, g);
-    stash_right(smem, g);
-    fetch(1, g);
+    // Staged pieces of one step (plain arrays indexed by compile-time constants only, so that they
+    // live in registers): left operand, eight 16-byte pieces; right operand, eight codes of each of
+    // eight contraction rows and the scales of those rows.
+    uint4 gl[8];
+    uint32_t gq[8];
+    float gs[8];
+    auto fetch_piece = [&](auto rc, int64_t c0) {
+        constexpr int r = decltype(rc)::value;
+        if (TRANSPOSED)
+            gl[r] = *reinterpret_cast<const uint4 *>(left_base + (c0 + r) * ld_dy * 2 + left_toff);
+        gq[r] = *reinterpret_cast<const uint32_t *>(code_base + (c0 + r) * q_row_bytes + code_toff);
+        gs[r] = *reinterpret_cast<const float *>(scale_base + (c0 + r) * 4 + scale_toff);
+    };
+    // which = 0: rows 8 wave + 32 jj .. + 8 of the left tile, global -> LDS
+    auto dma_left_piece = [&](auto jc, uint8_t *stage, int64_t c0) {
+        constexpr int jj = decltype(jc)::value;
+        const char *src = left_base + ((int64_t)(32 * jj) * ld_dy + c0) * 2 + left_toff;
+        uint8_t *dst = stage + (8 * wave + 32 * jj) * kGRowBytes;   // wave-uniform
+        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t *>(src),
+                                         (__attribute__((address_space(3))) uint32_t *)dst, 16, 0, 0);
+    };
+    // which = 1: column jj of the 8 x 8 sub-block, built by one byte permute per pair of rows
+    // (2a, 2a+1), becomes chunk mg of left row 8 cg + jj
+    auto stash_left_piece = [&](auto jc, uint8_t *stage) {
+        constexpr int jj = decltype(jc)::value;
+        uint32_t d[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const uint4 lo = gl[2 * a], hi = gl[2 * a + 1];
+            const uint32_t wl = (jj >> 1) == 0 ? lo.x : (jj >> 1) == 1 ? lo.y : (jj >> 1) == 2 ? lo.z : lo.w;
+            const uint32_t wh = (jj >> 1) == 0 ? hi.x : (jj >> 1) == 1 ? hi.y : (jj >> 1) == 2 ? hi.z : hi.w;
+            d[a] = __builtin_amdgcn_perm(wh, wl, (jj & 1) ? 0x07060302u : 0x05040100u);
+        }
+        const int row = 8 * cg + jj;
+        *reinterpret_cast<uint4 *>(stage + row * kGRowBytes + ((mg ^ gswz(row)) << 4)) =
+            make_uint4(d[0], d[1], d[2], d[3]);
+    };
+    // codes of contraction rows (2a, 2a+1), column e of the sub-block -> one bf16 pair, word a of
+    // right chunk e.  value = bf16(fp32(s * u)), u = 2 c - (L - 1).
+    uint32_t chunk[8][4];
+    auto dequant_pair = [&](auto kc) {
+        constexpr int a = decltype(kc)::value >> 3, e = decltype(kc)::value & 7;
+        float v[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t q = gq[2 * a + h];
+            const uint32_t nib = (e & 1) ? (q >> 4) : q;
+            const float c = (float)((nib >> (8 * (e >> 1))) & 0xfu);
+            v[h] = __fmul_rn(gs[2 * a + h], __fmaf_rn(c, 2.0f, offset));
+        }
+        chunk[e][a] = pack2_bf16(v[0], v[1]);
+    };
+    auto stash_right_piece = [&](auto jc, uint8_t *stage) {
+        constexpr int jj = decltype(jc)::value;
+        const int row = 8 * cg + jj;
+        *reinterpret_cast<uint4 *>(stage + GT * kGRowBytes + row * kGRowBytes + ((mg ^ gswz(row)) << 4)) =
+            make_uint4(chunk[jj][0], chunk[jj][1], chunk[jj][2], chunk[jj][3]);
+    };
+
+    static_for<8>([&](auto r) { fetch_piece(r, 0); });
+    if constexpr (TRANSPOSED)
+        static_for<8>([&](auto j) { stash_left_piece(j, smem); });
+    else
+        static_for<8>([&](auto j) { dma_left_piece(j, smem, 0); });
+    static_for<32>([&](auto k) { dequant_pair(k); });
+    static_for<8>([&](auto j) { stash_right_piece(j, smem); });
+    static_for<8>([&](auto r) { fetch_piece(r, (int64_t)min(1, steps - 1) * GC); });
     __syncthreads();
 
     // fragments: chunk 2 s + lh of a row holds this lane's eight contraction elements of k-step s
     const int left_off = (wr * 128 + lm) * kGRowBytes;
     const int right_off = GT * kGRowBytes + (wc * 128 + lm) * kGRowBytes;
     const int x = gswz(lm);   // rows lm + 32 i share bits 1..3
-    auto load_frags = [&](const uint8_t *stage, int ks, v8bf (&lf)[4], v8bf (&rf)[4]) {
-        const int off = ((2 * ks + lh) ^ x) << 4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lf[i] = *reinterpret_cast<const v8bf *>(stage + left_off + i * 32 * kGRowBytes + off);
-            rf[i] = *reinterpret_cast<const v8bf *>(stage + right_off + i * 32 * kGRowBytes + off);
-        }
-    };
-    auto multiply = [&](const v8bf (&lf)[4], const v8bf (&rf)[4]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)   // right fragment as the row operand: transposed tiles
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf[j], lf[i], acc[i][j], 0, 0, 0);
-    };
-
     v8bf lf[2][4], rf[2][4];
-    load_frags(smem, 0, lf[0], rf[0]);
+    auto load_frag = [&](const uint8_t *stage, int ks, int which_frag) {
+        const int off = ((2 * ks + lh) ^ x) << 4;
+        const int i = which_frag & 3;
+        if (which_frag < 4)
+            lf[ks & 1][i] = *reinterpret_cast<const v8bf *>(stage + left_off + i * 32 * kGRowBytes + off);
+        else
+            rf[ks & 1][i] = *reinterpret_cast<const v8bf *>(stage + right_off + i * 32 * kGRowBytes + off);
+    };
+#pragma unroll
+    for (int f = 0; f < 8; ++f)
+        load_frag(smem, 0, f);
+
+    // One wave per SIMD: nothing else hides the staging work, so it is cut into 64 slices and one
+    // slice follows each of the 64 MFMAs of a step, pinned there by scheduling barriers:
+    //    0..7   left pieces of step + 1: global -> LDS (which = 0) or permute and store (which = 1)
+    //    0..31  dequantize two codes each (rows 2a, 2a+1 of column e) into a word of a right chunk
+    //   32..39  store the eight right chunks (which = 0: and fetch the codes of step + 2)
+    //   48..55  which = 1: fetch step + 2
+    //   (the first eight MFMAs of a k-step also carry the fragment loads of the next one)
     for (int step = 0; step < steps; ++step) {
         uint8_t *cur = smem + (step & 1) * kGStage;
         uint8_t *nxt = smem + ((step + 1) & 1) * kGStage;
-        // g holds step + 1; it is written to the idle stage between the MFMAs and refilled with
-        // step + 2 (past the end: the last step again, into a stage nobody reads)
-        load_frags(cur, 1, lf[1], rf[1]);
-        multiply(lf[0], rf[0]);
-        stash_left(nxt, g);
-        load_frags(cur, 2, lf[0], rf[0]);
-        multiply(lf[1], rf[1]);
-        stash_right(nxt, g);
-        load_frags(cur, 3, lf[1], rf[1]);
-        multiply(lf[0], rf[0]);
-        fetch(step + 2, g);
-        multiply(lf[1], rf[1]);
+        // registers hold step + 1; which = 0 moves the left tile of step + 1 straight into the idle
+        // stage and can refill its (small) code registers early; which = 1 refills late, after its
+        // left pieces have been permuted out of their registers
+        const int64_t c_one = (int64_t)min(step + 1, steps - 1) * GC;
+        const int64_t c_two = (int64_t)min(step + 2, steps - 1) * GC;
+        static_for<64>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            constexpr int ks = k >> 4, i = (k >> 2) & 3, j = k & 3;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf[ks & 1][j], lf[ks & 1][i], acc[i][j], 0, 0, 0);
+            if constexpr ((k & 15) < 8 && ks < 3)
+                load_frag(cur, ks + 1, k & 15);
+            if constexpr (k < 8) {
+                if constexpr (TRANSPOSED)
+                    stash_left_piece(std::integral_constant<int, k & 7>{}, nxt);
+                else
+                    dma_left_piece(std::integral_constant<int, k & 7>{}, nxt, c_one);
+            }
+            if constexpr (k < 32) {
+                dequant_pair(std::integral_constant<int, k & 31>{});
+            } else if constexpr (k < 40) {
+                stash_right_piece(std::integral_constant<int, (k - 32) & 7>{}, nxt);
+                if constexpr (!TRANSPOSED)
+                    fetch_piece(std::integral_constant<int, (k - 32) & 7>{}, c_two);
+            } else if constexpr (k >= 48 && k < 56) {
+                if constexpr (TRANSPOSED)
+                    fetch_piece(std::integral_constant<int, (k - 48) & 7>{}, c_two);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
         __syncthreads();
-        load_frags(nxt, 0, lf[0], rf[0]);
+#pragma unroll
+        for (int f = 0; f < 8; ++f)
+            load_frag(nxt, 0, f);
     }
 
     // Epilogue.  Each accumulator tile is a transposed output tile: lane l holds output row l % 32
