@@ -180,6 +180,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     // which = 0: the left pieces go from global memory straight into LDS (no registers): lane l of a
     // wave lands at LDS offset 16 l of the wave's 1 KiB (8 rows x 128 bytes), so it fetches the
     // logical chunk that belongs in that physical slot
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int dma_row = tid >> 3;                                   // + 32 jj
     const int dma_chunk = (tid & 7) ^ gswz(dma_row);                // gswz(row + 32 jj) = gswz(row)
     const uint32_t left_toff = TRANSPOSED ? (uint32_t)((8 * mg) * ld_dy + 8 * cg) * 2u
@@ -217,9 +218,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     auto dma_left_piece = [&](auto jc, uint8_t *stage, int64_t c0) {
         constexpr int jj = decltype(jc)::value;
         const char *src = left_base + ((int64_t)(32 * jj) * ld_dy + c0) * 2 + left_toff;
-        uint8_t *dst = stage + (8 * wave + 32 * jj) * kGRowBytes;   // wave-uniform
-        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t *>(src),
-                                         (__attribute__((address_space(3))) uint32_t *)dst, 16, 0, 0);
+        lds_dma16(src, lds_address(stage) + (8 * wave_u + 32 * jj) * kGRowBytes);
     };
     // which = 1: column jj of the 8 x 8 sub-block, built by one byte permute per pair of rows
     // (2a, 2a+1), becomes chunk mg of left row 8 cg + jj
@@ -267,6 +266,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     static_for<32>([&](auto k) { dequant_pair(k); });
     static_for<8>([&](auto j) { stash_right_piece(j, smem); });
     static_for<8>([&](auto r) { fetch_piece(r, (int64_t)min(1, steps - 1) * GC); });
+    wait_vmcnt<0>();
     __syncthreads();
 
     // fragments: chunk 2 s + lh of a row holds this lane's eight contraction elements of k-step s
@@ -307,14 +307,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf[ks & 1][j], lf[ks & 1][i], acc[i][j], 0, 0, 0);
             if constexpr ((k & 15) < 8 && ks < 3)
                 load_frag(cur, ks + 1, k & 15);
-            if constexpr (k < 8) {
-                if constexpr (TRANSPOSED)
-                    stash_left_piece(std::integral_constant<int, k & 7>{}, nxt);
-                else
-                    dma_left_piece(std::integral_constant<int, k & 7>{}, nxt, c_one);
-            }
+            if constexpr (k < 8 && TRANSPOSED)
+                stash_left_piece(std::integral_constant<int, k & 7>{}, nxt);
             if constexpr (k < 32) {
                 dequant_pair(std::integral_constant<int, k & 31>{});
+                // after the slice's first use of the code registers: the wait for those (older)
+                // loads must not also cover the transfer just issued
+                if constexpr (k < 8 && !TRANSPOSED)
+                    dma_left_piece(std::integral_constant<int, k & 7>{}, nxt, c_one);
             } else if constexpr (k < 40) {
                 stash_right_piece(std::integral_constant<int, (k - 32) & 7>{}, nxt);
                 if constexpr (!TRANSPOSED)
@@ -325,6 +325,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
             }
             __builtin_amdgcn_sched_barrier(0);
         });
+        if constexpr (!TRANSPOSED)
+            wait_vmcnt<8>();   // the eight transfers (issued before this step's eight code fetches) landed
         __syncthreads();
 #pragma unroll
         for (int f = 0; f < 8; ++f)

@@ -2,11 +2,25 @@
 // packed codes (Algorithm 1, last step; Sec. 5 "Kernel Overview" stage 3 of arXiv 2502.05003).
 // The codes are widened to the signed odd integers u = 2c - (L - 1) on their way into LDS and
 // contracted on the INT8 matrix cores; acc = sum_k u_a u_b is exact in int32.
+#include <utility>
+
 #include "quest_device.h"
 #include "quest_internal.h"
 
 namespace quest {
 namespace {
+
+// compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>)
+template <int... Is, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -196,8 +210,9 @@ constexpr int TM = 256, TN = 128, TK = 128;
 constexpr int kTileThreads = 256;
 constexpr int kRowBytes = TK / 2;                      // packed bytes per tile row and step
 constexpr int kStageBytes = (TM + TN) * kRowBytes;     // 24 KiB
-constexpr int kParkBytes = 4 * 128 * 64 * 2;           // epilogue: four waves x 128 x 64 bf16
-constexpr int kTileLds = kParkBytes + TN * 4;          // + the tile's weight scales
+constexpr int kStages = 3;
+constexpr int kParkBytes = 4 * 128 * 64 * 2;           // epilogue: four waves x 128 x 64 bf16 (reuses the stages)
+constexpr int kTileLds = kStages * kStageBytes + TN * 4;   // 72 KiB + the tile's weight scales
 
 // 16-byte chunk c (0..3) of tile row `row` lives at chunk c ^ swz(row).  The LDS serves 128-bit
 // accesses sixteen lanes at a time over 64 banks (256 bytes): sixteen consecutive rows reading
@@ -244,18 +259,19 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     const int wm = wave >> 1, wn = wave & 1;
     const int lm = lane & 31, lh = lane >> 5;
 
-    // staging role: chunk tid % 4 of rows tid / 4 + 64 i (four rows of A, two of B)
-    const int st_row = tid >> 2, st_chunk = tid & 3;
+    // Staging: codes go from global memory straight into LDS, 16 bytes per lane.  A wave's 64 lanes
+    // fill 1 KiB = 16 tile rows x 64 bytes; lane l lands at offset 16 l, i.e. row l / 4, physical
+    // chunk l % 4, so it fetches the logical chunk that belongs there.  Six such pieces per step and
+    // wave: rows 64 i + 16 wave .. + 16 of A (i < 4) and of B (i = 4, 5).
+    const int st_row = 16 * wave + (lane >> 2);                       // + 64 i
+    const int st_chunk = (lane & 3) ^ swz(st_row);                    // swz(row + 64 i) = swz(row)
     const int64_t row_bytes = (int64_t)K / 2;
-    const uint8_t *src[6];
-    int dst_off[6];
+    uint32_t src_off[6];   // per-thread byte offsets from a_codes / b_codes (rows clamped at the edge)
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
         const int row = st_row + 64 * (i < 4 ? i : i - 4);
-        const uint8_t *base = i < 4 ? a_codes + (int64_t)min(m0 + row, M - 1) * row_bytes
-                                    : b_codes + (int64_t)min(n0 + row, N - 1) * row_bytes;
-        src[i] = base + st_chunk * 16;
-        dst_off[i] = (i < 4 ? 0 : TM * kRowBytes) + row * kRowBytes + ((st_chunk ^ swz(row)) << 4);
+        const int64_t grow = i < 4 ? min(m0 + row, M - 1) : min(n0 + row, N - 1);
+        src_off[i] = (uint32_t)(grow * row_bytes + st_chunk * 16);
     }
 
     v16i acc[4][2];
@@ -272,17 +288,17 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     asm volatile("" : "+v"(nibble_mask));
 
     const int steps = K / TK;
-    uint4 g0, g1, g2, g3, g4, g5;   // six staged chunks (named, so that they live in registers)
-#define QUEST_FETCH(G, I, STEP) \
-    G = *reinterpret_cast<const uint4 *>(src[I] + (int64_t)min((STEP), steps - 1) * kRowBytes)
-#define QUEST_STASH(STAGE, G, I) *reinterpret_cast<uint4 *>((STAGE) + dst_off[I]) = G
+    // piece I of contraction step STEP -> stage at LDS byte address STAGE (wave-uniform)
+    const uint32_t smem_addr = lds_address(smem);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#define QUEST_DMA(STAGE, I, STEP)                                                                  \
+    lds_dma16(((I) < 4 ? a_codes : b_codes) + src_off[I] + (int64_t)min((STEP), steps - 1) * kRowBytes, \
+              (STAGE) + ((I) < 4 ? 0 : TM * kRowBytes) +                                           \
+                  (64 * ((I) < 4 ? (I) : (I)-4) + 16 * wave_u) * kRowBytes)
 
-    QUEST_FETCH(g0, 0, 0); QUEST_FETCH(g1, 1, 0); QUEST_FETCH(g2, 2, 0);
-    QUEST_FETCH(g3, 3, 0); QUEST_FETCH(g4, 4, 0); QUEST_FETCH(g5, 5, 0);
-    QUEST_STASH(smem, g0, 0); QUEST_STASH(smem, g1, 1); QUEST_STASH(smem, g2, 2);
-    QUEST_STASH(smem, g3, 3); QUEST_STASH(smem, g4, 4); QUEST_STASH(smem, g5, 5);
-    QUEST_FETCH(g0, 0, 1); QUEST_FETCH(g1, 1, 1); QUEST_FETCH(g2, 2, 1);
-    QUEST_FETCH(g3, 3, 1); QUEST_FETCH(g4, 4, 1); QUEST_FETCH(g5, 5, 1);
+    static_for<6>([&](auto i) { QUEST_DMA(smem_addr, decltype(i)::value, 0); });
+    static_for<6>([&](auto i) { QUEST_DMA(smem_addr + kStageBytes, decltype(i)::value, 1); });
+    wait_vmcnt<0>();
     __syncthreads();
 
     // fragment addresses: rows lm + 32 i share bits 2..3, hence one swizzle value per lane;
@@ -290,63 +306,71 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     const int x = swz(lm);
     const int a_off = (wm * 128 + lm) * kRowBytes;
     const int b_off = TM * kRowBytes + (wn * 64 + lm) * kRowBytes;
-    auto load_frags = [&](const uint8_t *stage, int p, uint4 (&af)[4], uint4 (&bf)[2]) {
+    uint4 af[2][4], bf[2][2];   // packed fragments of the two sub-step pairs
+    auto load_frag = [&](const uint8_t *stage, int p, int f) {
         const int off = ((2 * p + lh) ^ x) << 4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            af[i] = *reinterpret_cast<const uint4 *>(stage + a_off + i * 32 * kRowBytes + off);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            bf[j] = *reinterpret_cast<const uint4 *>(stage + b_off + j * 32 * kRowBytes + off);
+        if (f < 4)
+            af[p][f] = *reinterpret_cast<const uint4 *>(stage + a_off + f * 32 * kRowBytes + off);
+        else
+            bf[p][f - 4] = *reinterpret_cast<const uint4 *>(stage + b_off + (f - 4) * 32 * kRowBytes + off);
     };
-    // the MFMAs of two sub-steps: words (0,1) of each fragment, then words (2,3)
-    auto multiply = [&](const uint4 (&af)[4], const uint4 (&bf)[2]) {
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            v4i bw[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                int w0, w1, w2, w3;
-                widen8(e ? bf[j].z : bf[j].x, nibble_mask, w0, w1);
-                widen8(e ? bf[j].w : bf[j].y, nibble_mask, w2, w3);
-                bw[j] = v4i{w0, w1, w2, w3};
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int w0, w1, w2, w3;
-                widen8(e ? af[i].z : af[i].x, nibble_mask, w0, w1);
-                widen8(e ? af[i].w : af[i].y, nibble_mask, w2, w3);
-                const v4i aw = v4i{w0, w1, w2, w3};
-#pragma unroll
-                for (int j = 0; j < 2; ++j)   // weight fragment as the row operand: transposed tiles
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bw[j], aw, acc[i][j], 0, 0, 0);
-            }
-        }
-    };
+    static_for<6>([&](auto f) { load_frag(smem, 0, decltype(f)::value); });
 
-    uint4 af[2][4], bf[2][2];
-    load_frags(smem, 0, af[0], bf[0]);
+    // Main loop: 32 MFMAs per step and wave, everything else pinned between them.
+    //   MFMA k: pair p = k / 16, half e = (k / 8) % 2, A tile i = (k / 2) % 4, B tile j = k % 2
+    //   k = 0..5    start the transfer of step + 2 into the stage that was read in step - 1
+    //   k = 0..5    load the fragments of pair 1 (needed from k = 16)
+    //   k = 23      wait for this wave's transfers of step + 1 (issued one step ago: all but the six
+    //               newest), then the workgroup barrier: step + 1 is complete in LDS
+    //   k = 24..29  load the fragments of pair 0 of step + 1
+    // Three stages: a transfer has almost two steps to land, and no wave waits on the barrier with
+    // an empty MFMA queue.
+    int stage_cur = 0;   // byte offsets of the stages holding step, step + 1, step + 2
+    int stage_one = kStageBytes, stage_two = 2 * kStageBytes;
     for (int step = 0; step < steps; ++step) {
-        uint8_t *cur = smem + (step & 1) * kStageBytes;
-        uint8_t *nxt = smem + ((step + 1) & 1) * kStageBytes;
-        // g[] holds step + 1 (fetched one step ago).  Each chunk is stashed into the idle stage
-        // and its register refilled with step + 2; past the end the fetches repeat the last step
-        // and the stashes land in a stage nobody reads, which keeps the loop body branch-free.
-        load_frags(cur, 1, af[1], bf[1]);
-        QUEST_STASH(nxt, g0, 0); QUEST_FETCH(g0, 0, step + 2);
-        QUEST_STASH(nxt, g1, 1); QUEST_FETCH(g1, 1, step + 2);
-        QUEST_STASH(nxt, g2, 2); QUEST_FETCH(g2, 2, step + 2);
-        multiply(af[0], bf[0]);
-        QUEST_STASH(nxt, g3, 3); QUEST_FETCH(g3, 3, step + 2);
-        QUEST_STASH(nxt, g4, 4); QUEST_FETCH(g4, 4, step + 2);
-        QUEST_STASH(nxt, g5, 5); QUEST_FETCH(g5, 5, step + 2);
-        multiply(af[1], bf[1]);
-        __syncthreads();
-        load_frags(nxt, 0, af[0], bf[0]);
+        const uint8_t *cur = smem + stage_cur;
+        const uint8_t *one = smem + stage_one;
+        v4i bw[2];
+        static_for<32>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            constexpr int p = k >> 4, e = (k >> 3) & 1, i = (k >> 1) & 3, j = k & 1;
+            if constexpr ((k & 7) == 0) {   // widen the two B fragments of this half
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    int w0, w1, w2, w3;
+                    widen8(e ? bf[p][jj].z : bf[p][jj].x, nibble_mask, w0, w1);
+                    widen8(e ? bf[p][jj].w : bf[p][jj].y, nibble_mask, w2, w3);
+                    bw[jj] = v4i{w0, w1, w2, w3};
+                }
+            }
+            v4i aw;
+            {
+                int w0, w1, w2, w3;
+                widen8(e ? af[p][i].z : af[p][i].x, nibble_mask, w0, w1);
+                widen8(e ? af[p][i].w : af[p][i].y, nibble_mask, w2, w3);
+                aw = v4i{w0, w1, w2, w3};
+            }
+            // weight fragment as the row operand: transposed accumulator tiles
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bw[j], aw, acc[i][j], 0, 0, 0);
+            if constexpr (k < 6) {
+                QUEST_DMA(smem_addr + stage_two, k, step + 2);
+                load_frag(cur, 1, k);
+            }
+            if constexpr (k == 23) {
+                wait_vmcnt<6>();
+                __builtin_amdgcn_s_barrier();
+            }
+            if constexpr (k >= 24 && k < 30)
+                load_frag(one, 0, k - 24);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        const int t = stage_cur;
+        stage_cur = stage_one;
+        stage_one = stage_two;
+        stage_two = t;
     }
-
-#undef QUEST_FETCH
-#undef QUEST_STASH
+    wait_vmcnt<0>();   // all transfers landed before the stages are reused
+#undef QUEST_DMA
 
     // Epilogue.  Each accumulator tile is the transpose of an output tile: lane l holds output row
     // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four

@@ -135,4 +135,32 @@ __device__ __forceinline__ void lds_butterfly_passes(float *row, int cols, int l
     __syncthreads();
 }
 
+/*
+ * 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
+ * lds_base + 16 l.  lds_base is the wave-uniform LDS byte address.  Written as inline assembly so
+ * that the compiler does not serialise the transfer against later LDS reads of other stages; the
+ * caller orders it explicitly: wait_vmcnt<N>() (transfers complete in issue order) and a barrier
+ * before any wave reads the destination.
+ */
+__device__ __forceinline__ void lds_dma16(const void *global_src, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(global_src), "s"(lds_base)
+                 : "memory");
+}
+
+// LDS byte address of a pointer into shared memory
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+// wait until at most N vector-memory operations of this wave are outstanding (N <= 15)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
+
 }  // namespace quest
