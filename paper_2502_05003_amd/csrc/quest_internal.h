@@ -53,6 +53,8 @@ struct BackwardArgs {
 };
 
 hipError_t launch_trust_backward(const BackwardArgs &a, hipStream_t stream);
+// Matrix-core kernel for bf16 in / bf16 out and the common shapes; false means "not covered".
+bool launch_trust_backward_mfma(const BackwardArgs &a, hipStream_t stream);
 
 struct GradGemmArgs {
     int which;

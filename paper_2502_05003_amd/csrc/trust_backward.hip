@@ -80,6 +80,8 @@ hipError_t launch_trust_backward(const BackwardArgs &a, hipStream_t stream)
 {
     if (a.rows == 0)
         return hipSuccess;
+    if (launch_trust_backward_mfma(a, stream))
+        return hipGetLastError();
     if (a.g_dtype == QUEST_BF16)
         return a.out_dtype == QUEST_BF16 ? launch_generic<uint16_t, uint16_t>(a, stream)
                                          : launch_generic<uint16_t, float>(a, stream);

@@ -1,0 +1,257 @@
+// Matrix-core assisted trust-masked inverse Hadamard transform, bf16 in / bf16 out (Algorithm 2,
+// out = IHT(M (.) g); Sec. 3.2 of arXiv 2502.05003).  Same data flow as the fused quantizer
+// (hadamard_quantize_mfma.hip), which see for the index bookkeeping:
+//   * one wavefront per row of 512 * HT elements, tiles of 1024 elements seen as 32 x 32 matrices;
+//     lane (m = l & 31, h = l >> 5) loads the 32 contiguous bytes of tile row m holding columns
+//     16 h .. 16 h + 15 together with their 16 mask bits, and zeroes the untrusted bf16 values;
+//   * index bits 0..4 are transformed by one exact +-1 bf16 MFMA product per tile, the other stages
+//     run on the fp32 accumulators in registers (bit 7 through one half-wave swap);
+//   * afterwards lane l & 31 holds index bits 0..4, l >> 5 bit 5, and the in-lane index iota the
+//     bits from 6 up; values are scaled by 1 / sqrt(n), rounded to bf16 in pairs (iota, iota + 1),
+//     and one exchange with the neighbouring lane turns those into pairs of adjacent elements, so
+//     that a wave stores 256 contiguous bytes per instruction.
+#include "quest_device.h"
+#include "quest_internal.h"
+
+namespace quest {
+namespace {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+#ifndef QUEST_TB_MAX_BLOCKS
+#define QUEST_TB_MAX_BLOCKS 1024
+#endif
+
+constexpr int kThreads = 256;
+constexpr int kRowsPerBlock = kThreads / 64;
+
+// in-lane element index iota = b6 + 2 b7 + 4 b8 + 8 b9 + 16 tile -> accumulator register in its tile
+// (after the half-wave swap: b7 = r & 1, b6 = (r >> 1) & 1, b8 = (r >> 2) & 1, b9 = r >> 3)
+__host__ __device__ constexpr int reg_of_iota(int iota)
+{
+    return ((iota >> 1) & 1) | ((iota & 1) << 1) | (((iota >> 2) & 1) << 2) |
+           (((iota >> 3) & 1) << 3);
+}
+
+__device__ __forceinline__ void bfly(float &a, float &b)
+{
+    const float t = a;
+    a = t + b;
+    b = t - b;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi)
+{
+    v2bf p;
+    p[0] = (__bf16)lo;
+    p[1] = (__bf16)hi;
+    uint32_t u;
+    __builtin_memcpy(&u, &p, 4);
+    return u;
+}
+
+// zero the halves of `pair` whose mask bits (bit 0: low half, bit 1: high half) are clear
+__device__ __forceinline__ uint32_t keep_trusted(uint32_t pair, uint32_t mask_bits, int first_bit)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe((int)mask_bits, first_bit, 1);      // 0 or ~0
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_sbfe((int)mask_bits, first_bit + 1, 1);
+    return pair & __builtin_amdgcn_perm(hi, lo, 0x07060100u);   // low half from lo, high half from hi
+}
+
+template <int HT, int LOG2N, bool WITH_MASK>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4)))
+void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ mask, int64_t rows,
+                    int log2n, uint16_t *__restrict__ out)
+{
+    constexpr int T = (HT + 1) / 2;
+    constexpr int NI = 8 * HT;
+    constexpr int cols = 512 * HT;
+    constexpr bool kHalfTail = (HT & 1) != 0;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+
+    // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
+    v8bf bmat[2];
+    {
+        const int nb = log2n < 5 ? log2n : 5;
+        const int low = (1 << nb) - 1;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int q = 16 * h + 8 * s + e;
+                uint32_t v = 0;
+                if ((q >> nb) == (m >> nb))
+                    v = (__builtin_popcount(q & m & low) & 1) ? 0xBF80u : 0x3F80u;
+                if (e & 1)
+                    w[e >> 1] |= v << 16;
+                else
+                    w[e >> 1] = v;
+            }
+            __builtin_memcpy(&bmat[s], w, 16);
+        }
+    }
+    const float inv_sqrt_n = (log2n & 1) ? 0.70710678118654752440f / (float)(1 << (log2n >> 1))
+                                         : 1.0f / (float)(1 << (log2n >> 1));
+    // exchange with lane ^ 1: even lanes keep the low halves, odd lanes the high halves
+    const uint32_t pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
+
+    for (int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave; row < rows;
+         row += (int64_t)gridDim.x * kRowsPerBlock) {
+        const uint16_t *src = g + row * cols + 32 * m + 16 * h;
+        const uint8_t *mask_src = mask + row * (cols / 8) + 4 * m + 2 * h;
+        float acc[T][16];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            v4u n0 = {0, 0, 0, 0}, n1 = {0, 0, 0, 0};
+            uint32_t bits = 0xffffu;
+            if (!(kHalfTail && t == T - 1) || m < 16) {
+                n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
+                n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
+                if (WITH_MASK)
+                    bits = *reinterpret_cast<const uint16_t *>(mask_src + 128 * t);
+            }
+            uint32_t w[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+            if (WITH_MASK) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    w[i] = keep_trusted(w[i], bits, 2 * i);
+            }
+            v8bf f0, f1;
+            __builtin_memcpy(&f0, &w[0], 16);
+            __builtin_memcpy(&f1, &w[4], 16);
+            v16f z;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                z[r] = 0.0f;
+            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
+            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[t][r] = z[r];
+        }
+
+        if (LOG2N > 5) {  // bit 5 = register bit 0
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2)
+                    bfly(acc[t][r], acc[t][r + 1]);
+        }
+        if (LOG2N > 6) {  // bit 6 = register bit 1
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (!(r & 2))
+                        bfly(acc[t][r], acc[t][r + 2]);
+        }
+        // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][r]),
+                                                                 __float_as_uint(acc[t][r + 1]),
+                                                                 false, false);
+                acc[t][r] = __uint_as_float(sw[0]);
+                acc[t][r + 1] = __uint_as_float(sw[1]);
+            }
+        if (LOG2N > 7) {
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2)
+                    bfly(acc[t][r], acc[t][r + 1]);
+        }
+        if (LOG2N > 8) {  // bit 8 = register bit 2
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (!(r & 4))
+                        bfly(acc[t][r], acc[t][r + 4]);
+        }
+        if (LOG2N > 9) {  // bit 9 = register bit 3
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    bfly(acc[t][r], acc[t][r + 8]);
+        }
+#pragma unroll
+        for (int k = 0; (1 << k) < T; ++k) {  // bits >= 10 pair whole tiles
+            if (LOG2N > 10 + k) {
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+                    if (!(t & (1 << k)) && (t | (1 << k)) < T) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            bfly(acc[t][r], acc[t | (1 << k)][r]);
+                    }
+            }
+        }
+
+        // element = (lane & 31) + 32 h + 64 iota.  Round (iota, iota + 1) to a bf16 pair, swap halves
+        // with lane ^ 1: an even lane then holds elements (l, l + 1) of iota, an odd lane elements
+        // (l - 1, l) of iota + 1.  A wave instruction stores 2 x 128 contiguous bytes.
+        uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * cols) + (m >> 1) + 16 * h +
+                        32 * (lane & 1);
+#pragma unroll
+        for (int i = 0; i < NI; i += 2) {
+            const float v0 = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
+            const float v1 = __fmul_rn(acc[(i + 1) >> 4][reg_of_iota((i + 1) & 15)], inv_sqrt_n);
+            const uint32_t own = pack_bf16_pair(v0, v1);
+            const uint32_t other = (uint32_t)__builtin_amdgcn_ds_swizzle((int)own, (1 << 10) | 0x1f);
+            __builtin_nontemporal_store(__builtin_amdgcn_perm(other, own, pair_sel), dst + 32 * i);
+        }
+    }
+}
+
+template <int HT, int LOG2N>
+void launch(const BackwardArgs &a, hipStream_t stream)
+{
+    const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int64_t max_blocks = QUEST_TB_MAX_BLOCKS;
+    const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
+    const auto *g = static_cast<const uint16_t *>(a.g);
+    auto *out = static_cast<uint16_t *>(a.out);
+    if (a.mask)
+        hipLaunchKernelGGL((tb_mfma_kernel<HT, LOG2N, true>), grid, dim3(kThreads), 0, stream, g,
+                           a.mask, a.rows, a.log2n, out);
+    else
+        hipLaunchKernelGGL((tb_mfma_kernel<HT, LOG2N, false>), grid, dim3(kThreads), 0, stream, g,
+                           a.mask, a.rows, a.log2n, out);
+}
+
+}  // namespace
+
+// Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
+// Covered: bf16 in and out, rows of 512, 1024, 2048, 4096 or 5632 elements, and a Hadamard block of
+// at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row.
+bool launch_trust_backward_mfma(const BackwardArgs &a, hipStream_t stream)
+{
+    if (a.g_dtype != QUEST_BF16 || a.out_dtype != QUEST_BF16 || (a.cols % 512) != 0)
+        return false;
+    const int ht = (int)(a.cols / 512);
+    const int l = a.log2n <= 5 ? 5 : a.log2n;
+#define QUEST_CASE(HT_, L_)                       \
+    if (ht == HT_ && l == L_) {                   \
+        launch<HT_, L_>(a, stream);               \
+        return true;                              \
+    }
+    QUEST_CASE(1, 5) QUEST_CASE(1, 7) QUEST_CASE(1, 9)
+    QUEST_CASE(2, 5) QUEST_CASE(2, 7) QUEST_CASE(2, 9) QUEST_CASE(2, 10)
+    QUEST_CASE(4, 5) QUEST_CASE(4, 7) QUEST_CASE(4, 9) QUEST_CASE(4, 10) QUEST_CASE(4, 11)
+    QUEST_CASE(8, 5) QUEST_CASE(8, 7) QUEST_CASE(8, 9) QUEST_CASE(8, 10) QUEST_CASE(8, 11) QUEST_CASE(8, 12)
+    QUEST_CASE(11, 5) QUEST_CASE(11, 7) QUEST_CASE(11, 9)
+#undef QUEST_CASE
+    return false;
+}
+
+}  // namespace quest

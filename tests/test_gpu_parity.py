@@ -158,7 +158,9 @@ def test_gemm_full_size_sampled_rows():
 
 BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16"), (70, 5632, 512, "bf16", "f32"),
               (19, 512, 1, "f32", "f32"), (5, 16384, 16384, "bf16", "bf16"), (300, 64, 64, "f32", "bf16"),
-              (1, 8, 2, "f32", "f32")]
+              (1, 8, 2, "f32", "f32"), (70, 5632, 512, "bf16", "bf16"), (33, 4096, 4096, "bf16", "bf16"),
+              (20, 512, 32, "bf16", "bf16"), (16, 2048, 1, "bf16", "bf16"), (9, 1024, 1024, "bf16", "bf16"),
+              (6, 512, 512, "bf16", "bf16"), (11, 2048, 8, "bf16", "bf16")]
 
 
 @pytest.mark.parametrize("rows,cols,n,gd,od", BACK_CASES)
@@ -180,6 +182,20 @@ def test_trust_backward_matches_oracle(rows, cols, n, gd, od):
     zeros = to_device(np.zeros((rows, cols // 8), dtype=np.uint8))
     q.quest_trust_backward(to_device(g), zeros, n, out=out)
     assert torch.all(out == 0)
+
+
+def test_trust_backward_full_size_headline_shape():
+    """16384 x 2048 bf16 gradient, block 2048, mask from the quantizer: whole tensor against the oracle."""
+    x, _, cfg = synth.make_config("mlp_up_1p6b", seed=0)
+    rows, cols, n = x.shape[0], cfg["K"], cfg["had_block"]
+    gq = gpu_quantize(x, n, cfg["bits"], want_xh=False)
+    g = synth.gaussian(rows, cols, 0.03, seed=77, dtype="bf16")
+    out = torch.empty(rows, cols, dtype=torch.bfloat16, device=DEV)
+    q.quest_trust_backward(to_device(g), gq["dev"]["mask"], n, out=out)
+    torch.cuda.synchronize()
+    ref = qo.trust_backward(qo.widen(g), qo.unpack_mask(gq["mask"], cols), n)
+    scale = np.sqrt(np.mean(ref * ref, axis=1, keepdims=True))
+    assert np.all(np.abs(to_host_f64(out) - ref) <= BF16_HALF_ULP * np.abs(ref) + 1e-5 * scale + 1e-30)
 
 
 @pytest.mark.parametrize("M,N,K", [(192, 128, 256), (512, 256, 512), (768, 512, 256)])
