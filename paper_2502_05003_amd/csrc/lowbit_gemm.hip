@@ -444,6 +444,236 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Wide kernel for b = 4 and long contractions (K >= 4096).  Workgroup tile 256 x 256, eight waves of
+// 128 x 64 (two per SIMD), 256 contraction elements per step, two LDS stages of 64 KiB, one
+// workgroup per CU.  The codes of a tile step have to come through the CU's vector-memory path
+// (64 bytes per clock): (TM + TN) * TK / 2 bytes for TM * TN * TK multiply-adds.  256 x 256 tiles move a
+// third less per multiply-add than 256 x 128, and with 256 contraction elements a row contributes a
+// whole 128-byte line per step instead of half of one.  The price is an epilogue that no second
+// workgroup hides, which only pays off when the main loop is long.  Everything else (packed codes
+// in LDS, widening at the consumer, direct global -> LDS transfers, pinned instruction slices,
+// transposed accumulator tiles) is as in the kernel above.
+// ------------------------------------------------------------------------------------------
+
+constexpr int WTM = 256, WTN = 256, WTK = 256;
+constexpr int kWideThreads = 512;
+constexpr int kWideRowBytes = WTK / 2;                      // packed bytes per tile row and step: 128
+constexpr int kWideStageBytes = (WTM + WTN) * kWideRowBytes;     // 64 KiB
+constexpr int kWideParkBytes = 8 * 128 * 64 * 2;           // epilogue: eight waves x 128 x 64 bf16 (reuses the stages)
+constexpr int kWideLds = 2 * kWideStageBytes + WTN * 4;     // 128 KiB + the tile's weight scales
+
+// 16-byte chunk c (0..7) of tile row `row` lives at chunk c ^ wide_swz(row).  The LDS serves 128-bit
+// accesses sixteen lanes at a time over 64 banks (256 bytes): sixteen consecutive rows reading
+// the same logical chunk must hit sixteen different 16-byte slots modulo 256 bytes (measured).
+// Rows are 128 bytes, so even and odd rows already differ; (row >> 1) & 7 separates the rest.
+__device__ __forceinline__ int wide_swz(int row)
+{
+    return (row >> 1) & 7;
+}
+
+__global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
+    const uint8_t *__restrict__ a_codes, const float *__restrict__ a_scales,
+    const uint8_t *__restrict__ b_codes, const float *__restrict__ b_scales, int M, int N, int K,
+    int tiles_m, int tiles_n, uint16_t *__restrict__ y, int64_t ld_y,
+    int32_t *__restrict__ acc_out)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (8 of them, each with
+    // its own L2), so give each XCD one contiguous run of tiles, ordered four tile-rows deep:
+    // the tiles an XCD works on at a time share a few row panels of A and column panels of B.
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total)
+        return;
+    const int band = logical / (4 * tiles_n);
+    const int band_rows = min(4, tiles_m - band * 4);
+    const int in_band = logical - band * 4 * tiles_n;
+    const int tile_m = band * 4 + in_band % band_rows;
+    const int tile_n = in_band / band_rows;
+    const int m0 = tile_m * WTM, n0 = tile_n * WTN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int lm = lane & 31, lh = lane >> 5;
+
+    // Staging: codes go from global memory straight into LDS, 16 bytes per lane.  A wave's 64 lanes
+    // fill 1 KiB = 8 tile rows x 128 bytes; lane l lands at offset 16 l, i.e. row l / 8, physical
+    // chunk l % 8, so it fetches the logical chunk that belongs there.  Eight such pieces per step
+    // and wave: rows 64 i + 8 wave .. + 8 of A (i < 4) and of B (i >= 4).
+    const int st_row = 8 * wave + (lane >> 3);                        // + 64 i
+    const int st_chunk = (lane & 7) ^ wide_swz(st_row);                    // wide_swz(row + 64 i) = wide_swz(row)
+    const int64_t row_bytes = (int64_t)K / 2;
+    uint32_t src_off[8];   // per-thread byte offsets from a_codes / b_codes (rows clamped at the edge)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = st_row + 64 * (i & 3);
+        const int64_t grow = i < 4 ? min(m0 + row, M - 1) : min(n0 + row, N - 1);
+        src_off[i] = (uint32_t)(grow * row_bytes + st_chunk * 16);
+    }
+
+    v16i acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0;
+
+    // kept in a vector register (opaque to constant folding) so that widen8 is one instruction
+    uint32_t nibble_mask = 0xf0f0f0f0u;
+    asm volatile("" : "+v"(nibble_mask));
+
+    const int steps = K / WTK;
+    // piece I of contraction step STEP -> stage at LDS byte address STAGE (wave-uniform)
+    const uint32_t smem_addr = lds_address(smem);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#define QUEST_WIDE_DMA(STAGE, I, STEP)                                                                  \
+    lds_dma16(((I) < 4 ? a_codes : b_codes) + src_off[I] + (int64_t)min((STEP), steps - 1) * kWideRowBytes, \
+              (STAGE) + ((I) < 4 ? 0 : WTM * kWideRowBytes) + (64 * ((I)&3) + 8 * wave_u) * kWideRowBytes)
+
+    static_for<8>([&](auto i) { QUEST_WIDE_DMA(smem_addr, decltype(i)::value, 0); });
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    // fragment addresses: rows lm + 32 i share bits 1..3, hence one swizzle value per lane;
+    // chunk 2 p + lh of a row feeds this lane's share of sub-steps 2 p and 2 p + 1
+    const int x = wide_swz(lm);
+    const int a_off = (wm * 128 + lm) * kWideRowBytes;
+    const int b_off = WTM * kWideRowBytes + (wn * 64 + lm) * kWideRowBytes;
+    uint4 af[2][4], bf[2][2];   // packed fragments of two consecutive sub-step pairs
+    auto load_frag = [&](const uint8_t *stage, int p, int f) {
+        const int off = ((2 * p + lh) ^ x) << 4;
+        if (f < 4)
+            af[p & 1][f] = *reinterpret_cast<const uint4 *>(stage + a_off + f * 32 * kWideRowBytes + off);
+        else
+            bf[p & 1][f - 4] = *reinterpret_cast<const uint4 *>(stage + b_off + (f - 4) * 32 * kWideRowBytes + off);
+    };
+    static_for<6>([&](auto f) { load_frag(smem, 0, decltype(f)::value); });
+
+    // Main loop: 64 MFMAs per step and wave, everything else pinned between them.
+    //   MFMA k: pair p = k / 16, half e = (k / 8) % 2, A tile i = (k / 2) % 4, B tile j = k % 2
+    //   k = 0..7         start the transfer of step + 1 into the other stage (last read in step - 1)
+    //   k = 16 p + 0..5  load the fragments of pair p + 1 (p < 3)
+    //   k = 47           wait for this wave's transfers, then the workgroup barrier: step + 1 is in LDS
+    //   k = 48..53       load the fragments of pair 0 of step + 1
+    // The barrier sits before the last pair, so no wave waits on it with an empty MFMA queue.
+    for (int step = 0; step < steps; ++step) {
+        const uint8_t *cur = smem + (step & 1) * kWideStageBytes;
+        const uint8_t *nxt = smem + ((step + 1) & 1) * kWideStageBytes;
+        const uint32_t nxt_addr = smem_addr + ((step + 1) & 1) * kWideStageBytes;
+        v4i bw[2];
+        static_for<64>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            constexpr int p = k >> 4, e = (k >> 3) & 1, i = (k >> 1) & 3, j = k & 1;
+            if constexpr ((k & 7) == 0) {   // widen the two B fragments of this half
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    int w0, w1, w2, w3;
+                    widen8(e ? bf[p & 1][jj].z : bf[p & 1][jj].x, nibble_mask, w0, w1);
+                    widen8(e ? bf[p & 1][jj].w : bf[p & 1][jj].y, nibble_mask, w2, w3);
+                    bw[jj] = v4i{w0, w1, w2, w3};
+                }
+            }
+            v4i aw;
+            {
+                int w0, w1, w2, w3;
+                widen8(e ? af[p & 1][i].z : af[p & 1][i].x, nibble_mask, w0, w1);
+                widen8(e ? af[p & 1][i].w : af[p & 1][i].y, nibble_mask, w2, w3);
+                aw = v4i{w0, w1, w2, w3};
+            }
+            // weight fragment as the row operand: transposed accumulator tiles
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bw[j], aw, acc[i][j], 0, 0, 0);
+            if constexpr (k < 8)
+                QUEST_WIDE_DMA(nxt_addr, k, step + 1);
+            if constexpr (p < 3 && (k & 15) < 6)
+                load_frag(cur, p + 1, k & 15);
+            if constexpr (k == 47) {
+                wait_vmcnt<0>();
+                __builtin_amdgcn_s_barrier();
+            }
+            if constexpr (k >= 48 && k < 54)
+                load_frag(nxt, 0, k - 48);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+#undef QUEST_WIDE_DMA
+
+    // Epilogue.  Each accumulator tile is the transpose of an output tile: lane l holds output row
+    // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
+    // consecutive columns.  Each wave converts its 128 x 64 block to bf16, parks it in its own
+    // 16 KiB of LDS (16-byte chunks swizzled by row) and writes it out as 128-byte row segments.
+    float *scale_lds = reinterpret_cast<float *>(smem + kWideParkBytes);
+    __syncthreads();   // every wave is done with the stages
+    if (tid < WTN)
+        scale_lds[tid] = b_scales[min(n0 + tid, N - 1)];
+    __syncthreads();
+
+    if (acc_out) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * 128 + i * 32 + lm;
+                    const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    if (m < M && n < N)
+                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> 6;   // exact: a multiple of 64
+                }
+    }
+    if (!y)
+        return;
+
+    uint8_t *park = smem + wave * (128 * 128);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = i * 32 + lm;   // row within the wave's block
+        // float(64 acc) * (s_a / 64) rounds exactly like float(acc) * s_a
+        const float sa = a_scales[min(m0 + wm * 128 + row, M - 1)] * (1.0f / 64.0f);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = j * 32 + 8 * q + 4 * lh;   // first of four consecutive columns
+                const float4 sb = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + col);
+                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
+                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
+                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
+                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
+                const int chunk = (col >> 3) ^ (row & 7);
+                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
+                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+            }
+        }
+    }
+    // each pass: 8 rows of 128 bytes, lane l takes 16-byte chunk l % 8 of row l / 8
+    uint16_t *y_base = y + (int64_t)(m0 + wm * 128) * ld_y + n0 + wn * 64;
+    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
+                           (n0 + wn * 64 + 64 <= N);
+#pragma unroll 4
+    for (int pass = 0; pass < 16; ++pass) {
+        const int row = pass * 8 + (lane >> 3);
+        const int c = lane & 7;
+        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
+        if (m0 + wm * 128 + row >= M)
+            continue;
+        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
+        if (vector_ok) {
+            *reinterpret_cast<uint4 *>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n0 + wn * 64 + c * 8 + e < N)
+                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream)
@@ -452,6 +682,22 @@ hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream)
         return hipSuccess;
     const int levels = 1 << a.bits;
     auto *y = static_cast<uint16_t *>(a.y);
+    if (a.bits == 4 && (a.K % WTK) == 0 && a.K >= 4096 && a.M >= 512 && a.N >= 512) {
+        const int tiles_m = (int)((a.M + WTM - 1) / WTM), tiles_n = (int)((a.N + WTN - 1) / WTN);
+        const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+        static bool wide_attr_set = false;
+        if (!wide_attr_set) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
+            if (err != hipSuccess)
+                return err;
+            wide_attr_set = true;
+        }
+        hipLaunchKernelGGL(lowbit_gemm_wide_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kWideThreads),
+                           kWideLds, stream, a.a_codes, a.a_scales, a.b_codes, a.b_scales, (int)a.M,
+                           (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y, a.acc_out);
+        return hipGetLastError();
+    }
     if (a.bits == 4 && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
         const int tiles_m = (int)((a.M + TM - 1) / TM), tiles_n = (int)((a.N + TN - 1) / TN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;

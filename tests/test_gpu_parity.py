@@ -97,7 +97,9 @@ def test_quantizer_full_size_headline_shape():
 # ------------------------------------------------------------------ GEMM
 
 GEMM_CASES = [(256, 512, 512, 4), (130, 200, 1024, 4), (1, 1, 64, 4), (257, 129, 2048, 4),
-              (64, 640, 5632, 4), (96, 160, 256, 3), (96, 160, 256, 2), (96, 160, 256, 1)]
+              (64, 640, 5632, 4), (96, 160, 256, 3), (96, 160, 256, 2), (96, 160, 256, 1),
+              # shapes that run the 256 x 256 tile kernel: whole tiles, ragged edges, several steps
+              (512, 512, 256, 4), (700, 600, 512, 4), (513, 1025, 1024, 4), (768, 512, 5632, 4)]
 
 
 @pytest.mark.parametrize("M,N,K,bits", GEMM_CASES)
