@@ -3,6 +3,9 @@
 // matrix cores with fp32 accumulation.
 //   which = 0:  out[M, K] = dy[M, N]   * what_h[N, K]   (contraction over N)
 //   which = 1:  out[N, K] = dy[M, N]^T * xhat_h[M, K]   (contraction over M)
+#include <algorithm>
+#include <mutex>
+#include <numeric>
 #include <utility>
 
 #include "quest_device.h"
@@ -13,6 +16,7 @@ namespace {
 
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kTile = 64;      // output tile is 64 x 64, one 32 x 32 quadrant per wave
 constexpr int kStep = 32;      // contraction elements per main-loop step
@@ -97,30 +101,42 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(
 
 
 // ------------------------------------------------------------------------------------------
-// Main kernel: 256 x 256 outputs per workgroup, four waves of 128 x 128 (sixteen 32 x 32 fp32
-// accumulator tiles), 64 contraction elements per step, two LDS stages of 64 KiB, one workgroup
-// per CU.  Both operands sit in LDS as [row][contraction] bf16, 128 bytes per row, so every MFMA
-// fragment is one 128-bit LDS read.
-//   left operand  (rows = output rows):   dy rows as they are (which = 0), or dy columns,
-//                                          transposed 8 x 8 in registers on the way in (which = 1);
-//   right operand (rows = output columns): the code-packed matrix, dequantized to bf16(s u) and
-//                                          transposed on the way in (pairs of contraction rows are
-//                                          converted together, which is the transpose).
+// Main path.  The code-packed operand is first expanded once to bf16(s u), [C, K] row-major, in
+// library-owned device memory (every 256 x 256 output tile would otherwise repeat that work for the
+// whole contraction); the matmul itself is then a plain bf16 x bf16 contraction whose main loop
+// holds nothing but matrix instructions, LDS reads and global -> LDS transfers.
+//
+// 256 x 256 outputs per workgroup, four waves of 128 x 128 (sixteen 32 x 32 fp32 accumulator
+// tiles, one wave per SIMD), 32 contraction elements per step, a ring of LDS stages of 32 KiB that
+// the transfers fill several steps ahead of the step being multiplied.  An operand whose rows are
+// contraction rows in memory ([c][k]: the expanded operand, and dy for which = 1) is staged as it
+// is and read with the transposing LDS load, which hands each lane four contraction elements of
+// one column; an operand whose rows are output rows (dy for which = 0) is read with 128-bit loads.
 // ------------------------------------------------------------------------------------------
 
 constexpr int GT = 256;                        // tile edge
-constexpr int GC = 64;                         // contraction elements per step
+constexpr int GC = 32;                         // contraction elements per step
 constexpr int kGemmThreads = 256;
-constexpr int kGRowBytes = GC * 2;             // 128
-constexpr int kGStage = 2 * GT * kGRowBytes;   // 64 KiB: left rows, then right rows
-constexpr int kGLds = 2 * kGStage;             // 128 KiB, reused by the epilogue
+constexpr int kOperandBytes = GT * GC * 2;     // 16 KiB per operand and step
+constexpr int kGStage = 2 * kOperandBytes;     // left operand, then right operand
+constexpr int kParkBytes = 4 * 32768;          // epilogue: 32 KiB per wave
 
-// chunk c (0..7) of row `row` lives at chunk c ^ gswz(row): sixteen consecutive rows reading the
-// same logical chunk hit sixteen different 16-byte slots modulo 256 bytes
-__device__ __forceinline__ int gswz(int row)
-{
-    return (row >> 1) & 7;
-}
+typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+
+// One LDS read of the main loop: operand, fragment, and which half of the fragment's eight
+// contraction elements a transposing read fetches (-1: a 128-bit read of the row form, both halves).
+struct ReadOp {
+    bool left;
+    int idx, half;
+};
+// right fragment j feeds matrix instructions j, 4 + j, ..., left fragment i instructions 4 i .. 4 i + 3
+constexpr ReadOp kReadsTransposed[16] = {{false, 0, 0}, {false, 0, 1}, {true, 0, 0},  {true, 0, 1},
+                                         {false, 1, 0}, {false, 1, 1}, {false, 2, 0}, {false, 2, 1},
+                                         {false, 3, 0}, {false, 3, 1}, {true, 1, 0},  {true, 1, 1},
+                                         {true, 2, 0},  {true, 2, 1},  {true, 3, 0},  {true, 3, 1}};
+constexpr ReadOp kReadsPlain[12] = {{false, 0, 0}, {false, 0, 1}, {true, 0, -1}, {false, 1, 0},
+                                    {false, 1, 1}, {false, 2, 0}, {false, 2, 1}, {false, 3, 0},
+                                    {false, 3, 1}, {true, 1, -1}, {true, 2, -1}, {true, 3, -1}};
 
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
 {
@@ -145,52 +161,163 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
-template <bool TRANSPOSED>
+// Expands packed codes to bf16(fp32(s * u)), u = 2 c - (L - 1): eight elements per thread.
+__global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__restrict__ codes,
+                                                           const float *__restrict__ scales, int levels,
+                                                           int cb, int K, int64_t groups,
+                                                           uint16_t *__restrict__ qhat)
+{
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;   // group of eight elements
+    if (g >= groups)
+        return;
+    const int per_row = K / 8;
+    const int64_t row = g / per_row;
+    const uint8_t *src = codes + g * cb;
+    uint32_t bits = 0;
+    if (cb == 4) {
+        bits = *reinterpret_cast<const uint32_t *>(src);
+    } else {
+        for (int byte = 0; byte < cb; ++byte)
+            bits |= (uint32_t)src[byte] << (8 * byte);
+    }
+    const float s = scales[row], offset = -(float)(levels - 1);
+    const uint32_t field = (1u << cb) - 1u;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        v[e] = __fmul_rn(s, __fmaf_rn((float)((bits >> (e * cb)) & field), 2.0f, offset));
+    *reinterpret_cast<uint4 *>(qhat + g * 8) = make_uint4(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]),
+                                                          pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7]));
+}
+
+// Work is counted in (tile, step) units: tile t owns the units [t * steps, (t + 1) * steps) and
+// workgroup b (in XCD-major order) the units [b * per_block, (b + 1) * per_block).  With
+// per_block = steps every workgroup computes one whole tile.  When the tiles do not fill the CUs
+// evenly the launcher hands every CU the same number of units instead; a workgroup then computes
+// one segment per tile its range touches, and a segment that is not a whole tile leaves its fp32
+// accumulators in partial-tile slot 2 b (segment continues a tile) or 2 b + 1 (segment starts one)
+// for grad_gemm_fixup_kernel to add up.  A slot is [wave][accumulator quad 0..63][lane] float4.
+//
+// Workgroups that are phase_period apart in that order walk through their tiles at the same
+// contraction position all the time, and with column-major tile order they tend to work on tiles
+// of one tile-row or tile-column, that is on the same operand rows at the same moment.  Such
+// workgroups are placed on one XCD (hardware deals workgroup ids out to the eight XCDs in turn) so
+// that they share the fetch through that XCD's L2.  phase_period = 0: whole tiles, all in phase.
+constexpr int kSlotQuads = 4 * 64 * 64;   // float4 per partial tile (256 KiB)
+
+__device__ __forceinline__ void tile_origin(int tile, int tiles_r, int tiles_k, int phase_period, int &r0,
+                                            int &k0)
+{
+    if (phase_period != 0) {   // split tiles: plain column-major order
+        r0 = (tile % tiles_r) * GT;
+        k0 = (tile / tiles_r) * GT;
+        return;
+    }
+    // four tile-rows deep, column by column: neighbours in the order share operand rows in L2
+    const int band = tile / (4 * tiles_k);
+    const int band_rows = min(4, tiles_r - band * 4);
+    const int in_band = tile - band * 4 * tiles_k;
+    r0 = (band * 4 + in_band % band_rows) * GT;
+    k0 = (in_band / band_rows) * GT;
+}
+
+/*
+ * LDS layouts of one operand of one step (16 KiB), both free of bank conflicts for the reads below.
+ *   row form  [256 rows][4 chunks of 8 contraction elements]: chunk c of row r sits at chunk
+ *             c ^ ((r >> 2) & 3).  Lane l of a 128-bit fragment read takes row l % 32 and chunk
+ *             2 ks + l / 32 of k-step ks.
+ *   column form [32 contraction rows][32 chunks of 8 columns]: chunk c of contraction row q sits at
+ *             chunk c ^ ((q & 3) << 2).  A transposing 64-bit read works on 16 lanes: lanes 4 a ..
+ *             4 a + 3 point at contraction row a of a block of four, sixteen columns wide, and lane
+ *             i receives column i of it (four contraction elements).  Two such reads give a lane
+ *             its eight contraction elements of one matrix-instruction operand.
+ * A transfer instruction moves 1 KiB (lane l to offset 16 l): sixteen rows of the row form, two
+ * contraction rows of the column form; each lane fetches the chunk that belongs in its slot.
+ */
+template <bool TRANSPOSED, int STAGES>
 __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
-    const uint16_t *__restrict__ dy, int64_t ld_dy, const uint8_t *__restrict__ q_codes,
-    const float *__restrict__ q_scales, int levels, int C, int K, int tiles_r, int tiles_k,
-    uint16_t *__restrict__ out)
+    const uint16_t *__restrict__ dy, int64_t ld_dy, const uint16_t *__restrict__ qhat, int C, int K,
+    int tiles_r, int tiles_k, int per_block, int phase_period, uint16_t *__restrict__ out,
+    float4 *__restrict__ partial)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    static_assert(STAGES * kGStage >= kParkBytes, "the epilogue reuses the stages");
 
-    // workgroup -> tile: one contiguous run of tiles per XCD, four tile-rows deep
-    const int total = tiles_r * tiles_k;
-    const int per_xcd = (total + 7) / 8;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= total)
-        return;
-    const int band = logical / (4 * tiles_k);
-    const int band_rows = min(4, tiles_r - band * 4);
-    const int in_band = logical - band * 4 * tiles_k;
-    const int r0 = (band * 4 + in_band % band_rows) * GT;
-    const int k0 = (in_band / band_rows) * GT;
+    const int steps = C / GC;
+    const int64_t total_units = (int64_t)tiles_r * tiles_k * steps;
+    int block;
+    if (phase_period != 0) {
+        // XCD x holds the phase classes x c .. x c + c - 1 (c = phase_period / 8) of every period
+        const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, classes = phase_period >> 3;
+        block = (idx / classes) * phase_period + xcd * classes + idx % classes;
+    } else {
+        block = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);   // one contiguous run per XCD
+    }
+    const int64_t unit_begin = (int64_t)block * per_block;
+    const int64_t unit_end = min(unit_begin + per_block, total_units);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int wr = wave >> 1, wc = wave & 1;
     const int lm = lane & 31, lh = lane >> 5;
-    const int64_t q_row_bytes = (int64_t)K / 2;
-    const float offset = -(float)(levels - 1);
+    const int l16 = lane & 15, lg = lane >> 4;
+    const uint32_t smem_addr = lds_address(smem);
 
-    // staging roles
-    //   direct left operand: chunk tid % 8 of rows tid / 8 + 32 i
-    //   transposed operands: 8 x 8 sub-block, contraction group mg = tid % 8, column group cg = tid / 8
-    const int mg = tid & 7, cg = tid >> 3;
-    // every global address is a wave-uniform base plus a 32-bit per-thread byte offset that does not
-    // change from step to step (one register per stream instead of one pointer per piece)
-    // which = 0: the left pieces go from global memory straight into LDS (no registers): lane l of a
-    // wave lands at LDS offset 16 l of the wave's 1 KiB (8 rows x 128 bytes), so it fetches the
-    // logical chunk that belongs in that physical slot
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int dma_row = tid >> 3;                                   // + 32 jj
-    const int dma_chunk = (tid & 7) ^ gswz(dma_row);                // gswz(row + 32 jj) = gswz(row)
-    const uint32_t left_toff = TRANSPOSED ? (uint32_t)((8 * mg) * ld_dy + 8 * cg) * 2u
-                                          : (uint32_t)(dma_row * ld_dy + 8 * dma_chunk) * 2u;
-    const uint32_t code_toff = (uint32_t)((8 * mg) * q_row_bytes + 4 * cg);
-    const uint32_t scale_toff = (uint32_t)(8 * mg) * 4u;
+    // Transfers: piece q (0..3) of an operand is the 1 KiB at offset (4 q + wave) KiB.  Per-lane
+    // byte offsets from the operand's position of the step:
+    //   row form:    row 16 (4 q + wave) + l / 4, chunk (l % 4) ^ ((l / 16) & 3)
+    //   column form: contraction row 2 (4 q + wave) + l / 32, chunk (l % 32) ^ ((2 wave + l / 32) & 3) << 2
+    uint32_t left_voff[4], right_voff[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int piece = 4 * q + wave;
+        const int crow = 2 * piece + lh;
+        const uint32_t column_form = (uint32_t)(((lane & 31) ^ ((crow & 3) << 2)) << 4);
+        right_voff[q] = (uint32_t)crow * (uint32_t)K * 2u + column_form;
+        if (TRANSPOSED)
+            left_voff[q] = (uint32_t)crow * (uint32_t)ld_dy * 2u + column_form;
+        else
+            left_voff[q] = (uint32_t)(16 * piece + (lane >> 2)) * (uint32_t)ld_dy * 2u +
+                           (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+    }
+    // byte advance per step
+    const int64_t left_step = TRANSPOSED ? (int64_t)GC * ld_dy * 2 : (int64_t)GC * 2;
+    const int64_t right_step = (int64_t)GC * K * 2;
+
+    // Fragment reads, byte offsets from the operand's place in a stage.
+    //   row form, fragment i, k-step ks:      row_off[ks] + 2048 i
+    //   column form, fragment j, k-step ks, half t:  col_off[j] + 512 (16 ks + 4 t)
+    // (column form: lane group g = l / 16 covers columns 16 (g % 2) .. + 16 and contraction rows
+    //  8 (g / 2) .. of the k-step; lane i of the group points at row i / 4, columns 4 (i % 4) ..)
+    auto column_offsets = [&](int w, uint32_t (&off)[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int crow = 8 * (lg >> 1) + (l16 >> 2);
+            const int chunk = ((4 * w + (j ^ (l16 >> 2))) << 2) + 2 * (lg & 1) + ((l16 >> 1) & 1);
+            off[j] = (uint32_t)(crow * 512 + chunk * 16 + 8 * (l16 & 1));
+        }
+    };
+    uint32_t left_off[4], right_off[4];
+    column_offsets(wc, right_off);
+    if (TRANSPOSED) {
+        column_offsets(wr, left_off);
+    } else {
+        const int x = (lm >> 2) & 3;
+        left_off[0] = (uint32_t)((wr * 128 + lm) * 64 + ((lh ^ x) << 4));
+        left_off[1] = (uint32_t)((wr * 128 + lm) * 64 + (((2 + lh) ^ x) << 4));
+        left_off[2] = left_off[3] = 0;
+    }
+
+    for (int64_t unit = unit_begin; unit < unit_end;) {
+    const int tile = (int)(unit / steps);
+    const int s_begin = (int)(unit - (int64_t)tile * steps);
+    const int s_end = (int)min((int64_t)steps, unit_end - (int64_t)tile * steps);
+    unit += s_end - s_begin;
+    int r0, k0;
+    tile_origin(tile, tiles_r, tiles_k, phase_period, r0, k0);
+    // operand positions of contraction step 0 (wave-uniform)
     const char *left_base = reinterpret_cast<const char *>(TRANSPOSED ? dy + r0 : dy + (int64_t)r0 * ld_dy);
-    const char *code_base = reinterpret_cast<const char *>(q_codes + k0 / 2);
-    const char *scale_base = reinterpret_cast<const char *>(q_scales);
-    const int steps = C / GC;
+    const char *right_base = reinterpret_cast<const char *>(qhat + k0);
 
     v16f acc[4][4];
 #pragma unroll
@@ -201,143 +328,108 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0.0f;
 
-    // Staged pieces of one step (plain arrays indexed by compile-time constants only, so that they
-    // live in registers): left operand, eight 16-byte pieces; right operand, eight codes of each of
-    // eight contraction rows and the scales of those rows.
-    uint4 gl[8];
-    uint32_t gq[8];
-    float gs[8];
-    auto fetch_piece = [&](auto rc, int64_t c0) {
-        constexpr int r = decltype(rc)::value;
-        if (TRANSPOSED)
-            gl[r] = *reinterpret_cast<const uint4 *>(left_base + (c0 + r) * ld_dy * 2 + left_toff);
-        gq[r] = *reinterpret_cast<const uint32_t *>(code_base + (c0 + r) * q_row_bytes + code_toff);
-        gs[r] = *reinterpret_cast<const float *>(scale_base + (c0 + r) * 4 + scale_toff);
-    };
-    // which = 0: rows 8 wave + 32 jj .. + 8 of the left tile, global -> LDS
-    auto dma_left_piece = [&](auto jc, uint8_t *stage, int64_t c0) {
-        constexpr int jj = decltype(jc)::value;
-        const char *src = left_base + ((int64_t)(32 * jj) * ld_dy + c0) * 2 + left_toff;
-        lds_dma16(src, lds_address(stage) + (8 * wave_u + 32 * jj) * kGRowBytes);
-    };
-    // which = 1: column jj of the 8 x 8 sub-block, built by one byte permute per pair of rows
-    // (2a, 2a+1), becomes chunk mg of left row 8 cg + jj
-    auto stash_left_piece = [&](auto jc, uint8_t *stage) {
-        constexpr int jj = decltype(jc)::value;
-        uint32_t d[4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const uint4 lo = gl[2 * a], hi = gl[2 * a + 1];
-            const uint32_t wl = (jj >> 1) == 0 ? lo.x : (jj >> 1) == 1 ? lo.y : (jj >> 1) == 2 ? lo.z : lo.w;
-            const uint32_t wh = (jj >> 1) == 0 ? hi.x : (jj >> 1) == 1 ? hi.y : (jj >> 1) == 2 ? hi.z : hi.w;
-            d[a] = __builtin_amdgcn_perm(wh, wl, (jj & 1) ? 0x07060302u : 0x05040100u);
-        }
-        const int row = 8 * cg + jj;
-        *reinterpret_cast<uint4 *>(stage + row * kGRowBytes + ((mg ^ gswz(row)) << 4)) =
-            make_uint4(d[0], d[1], d[2], d[3]);
-    };
-    // codes of contraction rows (2a, 2a+1), column e of the sub-block -> one bf16 pair, word a of
-    // right chunk e.  value = bf16(fp32(s * u)), u = 2 c - (L - 1).
-    uint32_t chunk[8][4];
-    auto dequant_pair = [&](auto kc) {
-        constexpr int a = decltype(kc)::value >> 3, e = decltype(kc)::value & 7;
-        float v[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t q = gq[2 * a + h];
-            const uint32_t nib = (e & 1) ? (q >> 4) : q;
-            const float c = (float)((nib >> (8 * (e >> 1))) & 0xfu);
-            v[h] = __fmul_rn(gs[2 * a + h], __fmaf_rn(c, 2.0f, offset));
-        }
-        chunk[e][a] = pack2_bf16(v[0], v[1]);
-    };
-    auto stash_right_piece = [&](auto jc, uint8_t *stage) {
-        constexpr int jj = decltype(jc)::value;
-        const int row = 8 * cg + jj;
-        *reinterpret_cast<uint4 *>(stage + GT * kGRowBytes + row * kGRowBytes + ((mg ^ gswz(row)) << 4)) =
-            make_uint4(chunk[jj][0], chunk[jj][1], chunk[jj][2], chunk[jj][3]);
-    };
-
-    static_for<8>([&](auto r) { fetch_piece(r, 0); });
-    if constexpr (TRANSPOSED)
-        static_for<8>([&](auto j) { stash_left_piece(j, smem); });
-    else
-        static_for<8>([&](auto j) { dma_left_piece(j, smem, 0); });
-    static_for<32>([&](auto k) { dequant_pair(k); });
-    static_for<8>([&](auto j) { stash_right_piece(j, smem); });
-    static_for<8>([&](auto r) { fetch_piece(r, (int64_t)min(1, steps - 1) * GC); });
-    wait_vmcnt<0>();
-    __syncthreads();
-
-    // fragments: chunk 2 s + lh of a row holds this lane's eight contraction elements of k-step s
-    const int left_off = (wr * 128 + lm) * kGRowBytes;
-    const int right_off = GT * kGRowBytes + (wc * 128 + lm) * kGRowBytes;
-    const int x = gswz(lm);   // rows lm + 32 i share bits 1..3
-    v8bf lf[2][4], rf[2][4];
-    auto load_frag = [&](const uint8_t *stage, int ks, int which_frag) {
-        const int off = ((2 * ks + lh) ^ x) << 4;
-        const int i = which_frag & 3;
-        if (which_frag < 4)
-            lf[ks & 1][i] = *reinterpret_cast<const v8bf *>(stage + left_off + i * 32 * kGRowBytes + off);
+    // eight transfers per wave fill the stage at LDS byte address `stage` with contraction step `step`
+    auto transfer = [&](auto pc, uint32_t stage, int step) {
+        constexpr int p = decltype(pc)::value;
+        const int at = min(step, s_end - 1);   // past the end: a valid step again, never used
+        if constexpr (p < 4)
+            lds_dma16(left_base + at * left_step, left_voff[p], stage + (4 * p + wave_u) * 1024);
         else
-            rf[ks & 1][i] = *reinterpret_cast<const v8bf *>(stage + right_off + i * 32 * kGRowBytes + off);
+            lds_dma16(right_base + at * right_step, right_voff[p - 4],
+                      stage + kOperandBytes + (4 * (p - 4) + wave_u) * 1024);
     };
-#pragma unroll
-    for (int f = 0; f < 8; ++f)
-        load_frag(smem, 0, f);
 
-    // One wave per SIMD: nothing else hides the staging work, so it is cut into 64 slices and one
-    // slice follows each of the 64 MFMAs of a step, pinned there by scheduling barriers:
-    //    0..7   left pieces of step + 1: global -> LDS (which = 0) or permute and store (which = 1)
-    //    0..31  dequantize two codes each (rows 2a, 2a+1 of column e) into a word of a right chunk
-    //   32..39  store the eight right chunks (which = 0: and fetch the codes of step + 2)
-    //   48..55  which = 1: fetch step + 2
-    //   (the first eight MFMAs of a k-step also carry the fragment loads of the next one)
-    for (int step = 0; step < steps; ++step) {
-        uint8_t *cur = smem + (step & 1) * kGStage;
-        uint8_t *nxt = smem + ((step + 1) & 1) * kGStage;
-        // registers hold step + 1; which = 0 moves the left tile of step + 1 straight into the idle
-        // stage and can refill its (small) code registers early; which = 1 refills late, after its
-        // left pieces have been permuted out of their registers
-        const int64_t c_one = (int64_t)min(step + 1, steps - 1) * GC;
-        const int64_t c_two = (int64_t)min(step + 2, steps - 1) * GC;
-        static_for<64>([&](auto kc) {
+    // fragments as halves of four contraction elements: [k-step][fragment][half]
+    v4bf lf[2][4][2], rf[2][4][2];
+    // read number n of k-step ks out of `stage`, in the order the matrix instructions want them
+    auto load_frag = [&](auto nc, const uint8_t *stage, auto ksc) {
+        constexpr int ks = decltype(ksc)::value;
+        constexpr ReadOp op = (TRANSPOSED ? kReadsTransposed : kReadsPlain)[decltype(nc)::value];
+        if constexpr (op.half < 0) {
+            const v8bf v = *reinterpret_cast<const v8bf *>(stage + left_off[ks] + 2048 * op.idx);
+            lf[ks][op.idx][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+            lf[ks][op.idx][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+        } else {
+            const uint32_t off = (op.left ? left_off[op.idx] : kOperandBytes + right_off[op.idx]) +
+                                 512 * (16 * ks + 4 * op.half);
+            const v4bf v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                (__attribute__((address_space(3))) v4bf *)(stage + off));
+            if constexpr (op.left)
+                lf[ks][op.idx][op.half] = v;
+            else
+                rf[ks][op.idx][op.half] = v;
+        }
+    };
+    constexpr int kReads = TRANSPOSED ? 16 : 12;
+
+    // Ring of STAGES stages: while step s is multiplied out of stage s % STAGES, the transfers of
+    // steps s + 1 .. s + STAGES - 2 are in flight or done and, from the middle of the step on, those
+    // of step s + STAGES - 1 go into the stage that step s - 1 has left.
+    static_for<STAGES - 1>([&](auto sc) {
+        static_for<8>([&](auto pc) {
+            transfer(pc, smem_addr + decltype(sc)::value * kGStage, s_begin + decltype(sc)::value);
+        });
+    });
+    wait_vmcnt<8 * (STAGES - 2)>();
+    __builtin_amdgcn_s_barrier();
+    static_for<kReads>([&](auto nc) { load_frag(nc, smem, std::integral_constant<int, 0>{}); });
+
+    int cur = 0;   // stage of the current step
+    for (int step = s_begin; step < s_end; ++step) {
+        const uint8_t *cur_stage = smem + cur * kGStage;
+        const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+        const int prv = cur == 0 ? STAGES - 1 : cur - 1;
+        const uint8_t *nxt_stage = smem + nxt * kGStage;
+        const uint32_t refill = smem_addr + prv * kGStage;
+        // 32 matrix instructions; each is followed by one slice of the other work, pinned in place:
+        //    0..15  fragment reads of the step's second k-step
+        //   15      transfers of step + 1 have landed (all but the newest STAGES - 3 groups), barrier
+        //   16..31  fragment reads of the next step's first k-step
+        //   16..23  transfers of step + STAGES - 1
+        static_for<32>([&](auto kc) {
             constexpr int k = decltype(kc)::value;
             constexpr int ks = k >> 4, i = (k >> 2) & 3, j = k & 3;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf[ks & 1][j], lf[ks & 1][i], acc[i][j], 0, 0, 0);
-            if constexpr ((k & 15) < 8 && ks < 3)
-                load_frag(cur, ks + 1, k & 15);
-            if constexpr (k < 8 && TRANSPOSED)
-                stash_left_piece(std::integral_constant<int, k & 7>{}, nxt);
-            if constexpr (k < 32) {
-                dequant_pair(std::integral_constant<int, k & 31>{});
-                // after the slice's first use of the code registers: the wait for those (older)
-                // loads must not also cover the transfer just issued
-                if constexpr (k < 8 && !TRANSPOSED)
-                    dma_left_piece(std::integral_constant<int, k & 7>{}, nxt, c_one);
-            } else if constexpr (k < 40) {
-                stash_right_piece(std::integral_constant<int, (k - 32) & 7>{}, nxt);
-                if constexpr (!TRANSPOSED)
-                    fetch_piece(std::integral_constant<int, (k - 32) & 7>{}, c_two);
-            } else if constexpr (k >= 48 && k < 56) {
-                if constexpr (TRANSPOSED)
-                    fetch_piece(std::integral_constant<int, (k - 48) & 7>{}, c_two);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_shufflevector(rf[ks][j][0], rf[ks][j][1], 0, 1, 2, 3, 4, 5, 6, 7),
+                __builtin_shufflevector(lf[ks][i][0], lf[ks][i][1], 0, 1, 2, 3, 4, 5, 6, 7), acc[i][j], 0, 0, 0);
+            if constexpr (k < 16) {
+                if constexpr (k < kReads)
+                    load_frag(std::integral_constant<int, k>{}, cur_stage, std::integral_constant<int, 1>{});
+                if constexpr (k == 15) {
+                    wait_vmcnt<8 * (STAGES - 3)>();
+                    __builtin_amdgcn_s_barrier();
+                }
+            } else {
+                if constexpr (k - 16 < kReads)
+                    load_frag(std::integral_constant<int, k - 16>{}, nxt_stage, std::integral_constant<int, 0>{});
+                if constexpr (k < 24)
+                    transfer(std::integral_constant<int, k - 16>{}, refill, step + STAGES - 1);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
-        if constexpr (!TRANSPOSED)
-            wait_vmcnt<8>();   // the eight transfers (issued before this step's eight code fetches) landed
-        __syncthreads();
-#pragma unroll
-        for (int f = 0; f < 8; ++f)
-            load_frag(nxt, 0, f);
+        cur = nxt;
     }
+    wait_vmcnt<0>();   // the look-ahead transfers still write into the stages
 
-    // Epilogue.  Each accumulator tile is a transposed output tile: lane l holds output row l % 32
+    // Epilogue.  A segment that is not a whole tile leaves its accumulators as they are, in fp32.
+    __syncthreads();
+    if (s_begin != 0 || s_end != steps) {
+        float4 *slot = partial + ((int64_t)(2 * block + (s_begin == 0 ? 1 : 0)) * 4 + wave) * (64 * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    __builtin_nontemporal_store(
+                        v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]},
+                        reinterpret_cast<v4f *>(slot + ((i * 4 + j) * 4 + q) * 64));
+        continue;   // LDS untouched since the barrier
+    }
+    // Each accumulator tile is a transposed output tile: lane l holds output row l % 32
     // and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4.  Each wave parks its
     // 128 x 128 block as bf16 in its own 32 KiB of LDS (chunks swizzled by row) and writes it out as
     // 256-byte row segments.
-    __syncthreads();
     uint8_t *park = smem + wave * 32768;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -362,6 +454,101 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
         const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 256 + ((c ^ (row & 15)) << 4));
         *reinterpret_cast<uint4 *>(out_base + (int64_t)row * K + c * 8) = v;
     }
+    __syncthreads();   // the next segment's first stage overwrites the parked block
+    }
+}
+
+/*
+ * Adds up the partial tiles of every tile that more than one workgroup worked on (in workgroup
+ * order, so the sum does not depend on timing) and writes the bf16 result.  One workgroup per
+ * 128 x 128 quadrant of a tile (the block of one wave of the main kernel); its wave i takes the
+ * four accumulator tiles (i, 0..3).
+ */
+__global__ __launch_bounds__(256) void grad_gemm_fixup_kernel(const float4 *__restrict__ partial, int steps,
+                                                              int per_block, int phase_period, int K,
+                                                              int tiles_r, int tiles_k,
+                                                              uint16_t *__restrict__ out)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t park[32768];
+    const int tile = blockIdx.x >> 2, quadrant = blockIdx.x & 3;
+    const int64_t first_unit = (int64_t)tile * steps, last_unit = first_unit + steps - 1;
+    const int b_first = (int)(first_unit / per_block), b_last = (int)(last_unit / per_block);
+    if (b_first == b_last)
+        return;   // computed whole by one workgroup, already written
+    const int tid = threadIdx.x, lane = tid & 63, i = tid >> 6;
+    const int lm = lane & 31, lh = lane >> 5;
+    float4 sum[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            sum[j][q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int b = b_first; b <= b_last; ++b) {
+        const bool continues = (int64_t)b * per_block > first_unit;
+        const float4 *slot = partial + ((int64_t)(2 * b + (continues ? 0 : 1)) * 4 + quadrant) * (64 * 64) + lane;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = slot[((i * 4 + j) * 4 + q) * 64];
+                sum[j][q].x += v.x; sum[j][q].y += v.y; sum[j][q].z += v.z; sum[j][q].w += v.w;
+            }
+    }
+    const int row = i * 32 + lm;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = j * 32 + 8 * q + 4 * lh;
+            const int chunk = (col >> 3) ^ (row & 15);
+            *reinterpret_cast<uint2 *>(park + row * 256 + chunk * 16 + (col & 4) * 2) =
+                make_uint2(pack2_bf16(sum[j][q].x, sum[j][q].y), pack2_bf16(sum[j][q].z, sum[j][q].w));
+        }
+    __syncthreads();
+    int r0, k0;
+    tile_origin(tile, tiles_r, tiles_k, phase_period, r0, k0);
+    uint16_t *out_base = out + (int64_t)(r0 + (quadrant >> 1) * 128) * K + k0 + (quadrant & 1) * 128;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+        const int prow = pass * 16 + (tid >> 4);
+        const int c = tid & 15;
+        const uint4 v = *reinterpret_cast<const uint4 *>(park + prow * 256 + ((c ^ (prow & 15)) << 4));
+        *reinterpret_cast<uint4 *>(out_base + (int64_t)prow * K + c * 8) = v;
+    }
+}
+
+/*
+ * Device memory for the expanded operand and the partial tiles, one buffer per device, grown on
+ * demand and kept until the process ends.  All launches of the main path on a device share it, so
+ * they must not overlap (they do not when issued to one stream).  Growing frees the old buffer
+ * after a device synchronisation.
+ */
+hipError_t library_memory(int device, size_t bytes, char **out_ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void *buffer[kMaxDevices] = {};
+    static size_t capacity[kMaxDevices] = {};
+    if (device < 0 || device >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    if (capacity[device] < bytes) {
+        if (buffer[device] != nullptr) {
+            hipError_t err = hipDeviceSynchronize();
+            if (err == hipSuccess)
+                err = hipFree(buffer[device]);
+            if (err != hipSuccess)
+                return err;
+            buffer[device] = nullptr;
+            capacity[device] = 0;
+        }
+        hipError_t err = hipMalloc(&buffer[device], bytes);
+        if (err != hipSuccess)
+            return err;
+        capacity[device] = bytes;
+    }
+    *out_ptr = static_cast<char *>(buffer[device]);
+    return hipSuccess;
 }
 
 }  // namespace
@@ -374,30 +561,77 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
     const auto *dy = static_cast<const uint16_t *>(a.dy);
     auto *out = static_cast<uint16_t *>(a.out);
     const int64_t out_rows = a.which == 0 ? a.M : a.N, contraction = a.which == 0 ? a.N : a.M;
-    if (a.cb == 4 && (out_rows % GT) == 0 && (a.K % GT) == 0 && (contraction % GC) == 0) {
+    if ((out_rows % GT) == 0 && (a.K % GT) == 0 && (contraction % GC) == 0 &&
+        out_rows * a.K < ((int64_t)1 << 31) && contraction * std::max(a.K, a.N) < ((int64_t)1 << 30)) {
         const int tiles_r = (int)(out_rows / GT), tiles_k = (int)(a.K / GT);
-        const dim3 grid((unsigned)(((tiles_r * tiles_k + 7) / 8) * 8));
+        const int tiles = tiles_r * tiles_k, steps = (int)(contraction / GC);
+        constexpr int kStages = 5;
+        constexpr int kLds = kStages * kGStage;
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t err = hipFuncSetAttribute(
-                reinterpret_cast<const void *>(grad_gemm_tile_kernel<false>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, kGLds);
+                reinterpret_cast<const void *>(grad_gemm_tile_kernel<false, kStages>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
             if (err == hipSuccess)
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(grad_gemm_tile_kernel<true>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kGLds);
+                err = hipFuncSetAttribute(reinterpret_cast<const void *>(grad_gemm_tile_kernel<true, kStages>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
             if (err != hipSuccess)
                 return err;
             attr_set = true;
         }
+        // One workgroup per CU at a time.  When the last round of whole tiles would leave more than
+        // a tenth of the CU-rounds idle, every CU gets the same share of (tile, step) units instead
+        // and the split tiles are summed by a second, small kernel.
+        int device = 0, cus = 0;
+        hipError_t err = hipGetDevice(&device);
+        if (err == hipSuccess)
+            err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+        if (err != hipSuccess)
+            return err;
+        cus = cus / 8 * 8;
+        const int rounds = cus > 0 ? (tiles + cus - 1) / cus : 0;
+        const bool split = cus >= 8 && 10 * tiles < 9 * rounds * cus && (int64_t)tiles * steps >= 4 * (int64_t)cus;
+        int blocks = (tiles + 7) / 8 * 8, per_block = steps, phase_period = 0;
+        if (split) {
+            blocks = cus;
+            per_block = (int)(((int64_t)tiles * steps + blocks - 1) / blocks);
+            // workgroups b and b + period are at the same contraction position at all times
+            const int period = steps / std::gcd(per_block, steps);
+            phase_period = (period % 8 == 0 && blocks % period == 0) ? period : 8;
+            if (blocks % phase_period != 0)
+                phase_period = blocks;
+        }
+        // library-owned device memory: the expanded operand, then the partial tiles
+        const size_t expanded_bytes = ((size_t)contraction * a.K * 2 + 255) / 256 * 256;
+        const size_t partial_bytes = split ? (size_t)2 * blocks * kSlotQuads * sizeof(float4) : 0;
+        char *memory = nullptr;
+        err = library_memory(device, expanded_bytes + partial_bytes, &memory);
+        if (err != hipSuccess)
+            return err;
+        auto *qhat = reinterpret_cast<uint16_t *>(memory);
+        auto *partial = split ? reinterpret_cast<float4 *>(memory + expanded_bytes) : nullptr;
+
+        const int64_t groups = contraction * a.K / 8;
+        hipLaunchKernelGGL(expand_codes_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream,
+                           a.q_codes, a.q_scales, levels, a.cb, (int)a.K, groups, qhat);
+        err = hipGetLastError();
+        if (err != hipSuccess)
+            return err;
         if (a.which == 0)
-            hipLaunchKernelGGL(grad_gemm_tile_kernel<false>, grid, dim3(kGemmThreads), kGLds, stream, dy,
-                               a.N, a.q_codes, a.q_scales, levels, (int)contraction, (int)a.K, tiles_r,
-                               tiles_k, out);
+            hipLaunchKernelGGL((grad_gemm_tile_kernel<false, kStages>), dim3((unsigned)blocks),
+                               dim3(kGemmThreads), kLds, stream, dy, a.N, qhat, (int)contraction, (int)a.K,
+                               tiles_r, tiles_k, per_block, phase_period, out, partial);
         else
-            hipLaunchKernelGGL(grad_gemm_tile_kernel<true>, grid, dim3(kGemmThreads), kGLds, stream, dy,
-                               a.N, a.q_codes, a.q_scales, levels, (int)contraction, (int)a.K, tiles_r,
-                               tiles_k, out);
-        return hipGetLastError();
+            hipLaunchKernelGGL((grad_gemm_tile_kernel<true, kStages>), dim3((unsigned)blocks),
+                               dim3(kGemmThreads), kLds, stream, dy, a.N, qhat, (int)contraction, (int)a.K,
+                               tiles_r, tiles_k, per_block, phase_period, out, partial);
+        err = hipGetLastError();
+        if (err == hipSuccess && split) {
+            hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles * 4)), dim3(256), 0, stream, partial,
+                               steps, per_block, phase_period, (int)a.K, tiles_r, tiles_k, out);
+            err = hipGetLastError();
+        }
+        return err;
     }
     if (a.which == 0) {
         const dim3 grid((unsigned)(a.K / kTile), (unsigned)(a.M / kTile));

@@ -144,9 +144,18 @@ __device__ __forceinline__ void lds_butterfly_passes(float *row, int cols, int l
  */
 __device__ __forceinline__ void lds_dma16(const void *global_src, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :
                  : "v"(global_src), "s"(lds_base)
+                 : "memory");
+}
+
+// Same, the source given as a wave-uniform base plus a per-lane unsigned 32-bit byte offset.
+__device__ __forceinline__ void lds_dma16(const void *uniform_base, uint32_t lane_offset, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_base)
                  : "memory");
 }
 
@@ -156,11 +165,13 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
 }
 
-// wait until at most N vector-memory operations of this wave are outstanding (N <= 15)
+// wait until at most N vector-memory operations of this wave are outstanding (N <= 63; the
+// count's low four bits sit in bits 3:0 of the immediate, its high two in bits 15:14)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+    static_assert(N >= 0 && N <= 63, "vmcnt is a six-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 }  // namespace quest

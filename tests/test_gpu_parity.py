@@ -200,10 +200,16 @@ def test_trust_backward_full_size_headline_shape():
     assert np.all(np.abs(to_host_f64(out) - ref) <= BF16_HALF_ULP * np.abs(ref) + 1e-5 * scale + 1e-30)
 
 
-@pytest.mark.parametrize("M,N,K", [(192, 128, 256), (512, 256, 512), (768, 512, 256)])
+@pytest.mark.parametrize("M,N,K", [(192, 128, 256), (512, 256, 512), (768, 512, 256),
+                                   # few tiles, long contraction: tiles split between workgroups,
+                                   # evenly (12 steps over 4) and unevenly (128 steps in threes)
+                                   (768, 8192, 512), (8192, 768, 512),
+                                   # more tiles than CUs, two steps each: whole tiles and halves mixed
+                                   (5120, 128, 3840), (128, 5120, 3840)])
 @pytest.mark.parametrize("which", [0, 1])
 def test_grad_gemm_matches_oracle(which, M, N, K):
-    """Small shapes run the 64x64 kernel; shapes made of whole 256x256 tiles run the main kernel."""
+    """Small shapes run the 64x64 kernel; shapes made of whole 256x256 tiles run the main kernel,
+    which splits tiles between workgroups when whole tiles would leave CUs idle."""
     bits, n = 4, 256
     x = synth.gaussian(M, K, 1.0, 11, "bf16")
     w = synth.gaussian(N, K, 0.02, 12, "bf16")
