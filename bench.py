@@ -30,6 +30,23 @@ KERNELS = ("quantize_x", "quantize_w", "lowbit_gemm", "grad_gemm_x", "grad_gemm_
            "trust_backward_x", "trust_backward_w")
 
 
+# HBM-side traffic per launch on this workload, bytes, from rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE runs of this script (profiles/bench_step_mlp_up_1p6b_hbm_traffic.md): counter
+# value in KiB per dispatch times 1024, FETCH_SIZE also times 2.0 -- the factor by which it
+# under-reads the plain streaming kernel of --copy-calibration (2^30 bytes in, 2^30 out); WRITE_SIZE
+# reads that kernel exactly.  A gradient matmul is the sum over the kernels of its call.
+MIB = 1 << 20
+MEASURED_TRAFFIC = {
+    "quantize_x": (2 * 32.1 + 20.1) * MIB,
+    "quantize_w": (2 * 11.0 + 6.9) * MIB,
+    "lowbit_gemm": (2 * 64.0 + 176.0) * MIB,
+    "grad_gemm_x": (2 * (2.9 + 273.0) + 22.0 + 88.5) * MIB,
+    "grad_gemm_w": (2 * (8.3 + 441.0 + 52.0) + 64.0 + 120.4 + 22.0) * MIB,
+    "trust_backward_x": (2 * 34.1 + 64.0) * MIB,
+    "trust_backward_w": (2 * 11.8 + 22.0) * MIB,
+}
+
+
 def algorithmic_bytes_quantize(rows, cols, cb=4, in_bytes=2):
     """input + packed codes + mask bitmap + one fp32 scale per row."""
     return rows * cols * in_bytes + rows * cols * cb // 8 + rows * cols // 8 + 4 * rows
@@ -84,11 +101,6 @@ def step_kernels(q, b, cfg):
     ]
 
 
-def run_step(q, b, cfg):
-    for _, launch in step_kernels(q, b, cfg):
-        launch()
-
-
 def cpu_baseline(x_bits, w_bits, dy_bits, cfg):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same step."""
     import numpy as np
@@ -124,6 +136,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain streaming kernel of known size (reads and writes 1 GiB each), "
+                         "the yardstick for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (one MI355X per box); run with --gpus 1")
@@ -148,36 +163,40 @@ def main():
     sets = [BufferSet(torch, dev, x_bits, w_bits, dy_bits, cfg) for _ in range(n_sets)]
     torch.cuda.synchronize()
 
+    # Every kernel launch is bracketed by a pair of HIP events on the stream it is launched on
+    # (torch's current stream), in the warm-up and in the timed region alike, so that the per-kernel
+    # durations behind the rooflines come from the very steps that `value` is computed from.  An
+    # event pair around a single launch also counts the idle gaps at both ends, a few microseconds;
+    # half the duration of an empty pair (one is recorded per step) is subtracted, which brings the
+    # figures to within a few percent of the rocprofv3 kernel durations of this same command
+    # (profiles/).  The pairs cost the step about 2 % against launching the kernels back to back.
+    def event_pair():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    events = [{k: event_pair() for k in KERNELS} for _ in range(args.steps)]
+    empty = [event_pair() for _ in range(args.steps)]
+    scratch_pair = event_pair()
+
+    def timed_step(i, pairs, gap_pair):
+        for name, launch in step_kernels(q, sets[i % n_sets], cfg):
+            start, end = pairs[name] if pairs else scratch_pair
+            start.record()
+            launch()
+            end.record()
+        gap_pair[0].record()
+        gap_pair[1].record()
+
     for i in range(args.warmup):
-        run_step(q, sets[i % n_sets], cfg)
+        timed_step(i, None, scratch_pair)
     torch.cuda.synchronize()
 
     # Timed region: exactly `steps` whole steps, host clock, synchronised on both sides.
     t0 = time.perf_counter()
     for i in range(args.steps):
-        run_step(q, sets[i % n_sets], cfg)
+        timed_step(i, events[i], empty[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    # Per-kernel durations for the rooflines: the same `steps` steps again, each kernel bracketed
-    # by HIP events on the stream it is launched on (torch's current stream).  An event pair around
-    # a single launch also counts idle gaps at both ends, a few microseconds; half the duration of
-    # an empty pair is subtracted (calibrated against the rocprofv3 kernel durations of this same
-    # command, kept under profiles/).
-    events = [{k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for k in KERNELS} for _ in range(args.steps)]
-    empty = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    for i in range(args.steps):
-        for name, launch in step_kernels(q, sets[i % n_sets], cfg):
-            start, end = events[i][name]
-            start.record()
-            launch()
-            end.record()
-        empty[i][0].record()
-        empty[i][1].record()
-    torch.cuda.synchronize()
     gap_ms = 0.5 * float(np.median([a.elapsed_time(b) for a, b in empty]))
     ms = {k: max(float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in events])) - gap_ms, 1e-6)
           for k in KERNELS}
@@ -188,13 +207,14 @@ def main():
     def hbm(name, nbytes):
         gbs = nbytes / (ms[name] * 1e-3) / 1e9
         return {"kernel": name, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": gbs / HBM_PEAK_GBS, "traffic": None, "ms": ms[name]}
+                "frac": gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC[name], "algorithmic": nbytes,
+                "ms": ms[name]}
 
     def mfma(name, peak):
         t = gemm_ops / (ms[name] * 1e-3) / 1e12
         return {"kernel": name, "bound": "mfma", "achieved": t, "peak": peak,
                 "unit": "TOPS" if peak == INT8_PEAK_TOPS else "TFLOP/s", "frac": t / peak,
-                "traffic": None, "ms": ms[name]}
+                "traffic": MEASURED_TRAFFIC[name], "ms": ms[name]}
 
     rooflines = {
         "quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K)),
@@ -227,6 +247,12 @@ def main():
         "roofline": headline,
         "kernels": rooflines,
     }
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)   # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(x_bits, w_bits, dy_bits, cfg)
     print(json.dumps(result))

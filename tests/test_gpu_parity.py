@@ -98,8 +98,10 @@ def test_quantizer_full_size_headline_shape():
 
 GEMM_CASES = [(256, 512, 512, 4), (130, 200, 1024, 4), (1, 1, 64, 4), (257, 129, 2048, 4),
               (64, 640, 5632, 4), (96, 160, 256, 3), (96, 160, 256, 2), (96, 160, 256, 1),
-              # shapes that run the 256 x 256 tile kernel: whole tiles, ragged edges, several steps
-              (512, 512, 256, 4), (700, 600, 512, 4), (513, 1025, 1024, 4), (768, 512, 5632, 4)]
+              # shapes that run the 256 x 128 tile kernel: whole tiles, ragged edges, several steps
+              (512, 512, 256, 4), (700, 600, 512, 4), (513, 1025, 1024, 4), (768, 512, 5632, 4),
+              # more tiles than the chip holds at once, ragged last tile row and column, one step only
+              (4096, 4090, 256, 4), (4096, 4096, 128, 4), (4000, 4100, 384, 4)]
 
 
 @pytest.mark.parametrize("M,N,K,bits", GEMM_CASES)
@@ -237,6 +239,48 @@ def test_grad_gemm_matches_oracle(which, M, N, K):
     # against the exact oracle: the operand rounding adds about 2^-9 of the spread of the terms
     assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
     assert np.linalg.norm(got - ref) <= 4e-3 * np.linalg.norm(ref)
+
+
+def test_grad_gemm_full_size_sampled_rows():
+    """Both gradient matmuls at M=16384, N=5632, K=2048 (the launch shapes the benchmark times, the
+    weight gradient with its tiles split over the CUs); sampled output rows against the oracle."""
+    x, w, cfg = synth.make_config("mlp_up_1p6b", seed=0)
+    K, bits, n = cfg["K"], cfg["bits"], cfg["had_block"]
+    M, N = x.shape[0], w.shape[0]
+    dy = synth.upstream_gradient(M, N, 3, "bf16")
+    gx = gpu_quantize(x, n, bits, want_xh=False, want_mask=False)
+    gw = gpu_quantize(w, n, bits, want_xh=False, want_mask=False)
+    dyd = to_device(dy)
+    g_x = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
+    g_w = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
+    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x)
+    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w)
+    torch.cuda.synchronize()
+    assert torch.isfinite(g_x.float()).all() and torch.isfinite(g_w.float()).all()
+    rng = np.random.default_rng(1)
+    ux, uw = qo.unpack_odd(gx["codes"], K, bits), qo.unpack_odd(gw["codes"], K, bits)
+    sx, sw = gx["scales"].astype(np.float64), gw["scales"].astype(np.float64)
+    # G_x rows: one per 256-row tile band at the ends, the rest anywhere
+    rows = np.sort(rng.choice(M, size=24, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    d = qo.widen(dy[rows])
+    ref = qo.grad_input(d, uw, sw)
+    q16 = qo.widen(synth.to_bf16_bits(gw["scales"][:, None] * uw.astype(np.float32)))
+    spread = np.sqrt((d ** 2) @ (q16 ** 2))
+    got = to_host_f64(g_x[torch.from_numpy(rows).to(DEV)])
+    assert np.all(np.abs(got - d @ q16) <= BF16_HALF_ULP * 1.001 * np.abs(d @ q16) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+    # G_w rows (columns of dy), each a contraction over all 16384 tokens
+    cols = np.sort(rng.choice(N, size=12, replace=False))
+    cols[0], cols[-1] = 0, N - 1
+    d = qo.widen(np.ascontiguousarray(dy[:, cols]))
+    ref = qo.grad_weight(d, ux, sx)
+    q16 = qo.widen(synth.to_bf16_bits(gx["scales"][:, None] * ux.astype(np.float32)))
+    mirror = d.T @ q16
+    spread = np.sqrt((d.T ** 2) @ (q16 ** 2))
+    got = to_host_f64(g_w[torch.from_numpy(cols).to(DEV)])
+    assert np.all(np.abs(got - mirror) <= BF16_HALF_ULP * 1.001 * np.abs(mirror) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
 
 
 def test_full_linear_forward_backward_small():
