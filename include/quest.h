@@ -15,9 +15,10 @@
  *
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer unless the comment says "host".  The caller owns
- *     all buffers; the library allocates nothing, frees nothing and never synchronises: a call
- *     validates its arguments on the host and enqueues kernels on `stream` (a hipStream_t
- *     passed as void*, NULL = the default stream).
+ *     all buffers; the library allocates nothing, frees nothing and never synchronises (the one
+ *     exception, quest_grad_gemm's scratch memory, is described there): a call validates its
+ *     arguments on the host and enqueues kernels on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream).
  *   - Errors are return codes.  On any code other than QUEST_OK nothing was launched.
  *   - Outputs must not alias inputs.
  *   - "bf16" is the upper half of an IEEE binary32, stored as uint16_t.
@@ -118,6 +119,13 @@ quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint
  *   which = 1:  out[N, K] = dy[M, N]^T * xhat_h[M, K]    (q = activation codes [M, K*cb/8], scales [M])
  *   dy bf16 [M, N] row-major, out bf16, fp32 accumulation.  bits in {1,2,3,4}.
  *   M, N, K multiples of 64.
+ * Device memory: when the output is made of whole 256 x 256 tiles the call first expands the packed
+ * operand to bf16 and, if the tiles do not fill the GPU's compute units evenly, sums partial tiles
+ * in a second pass.  Both live in memory the library owns: one buffer per device, allocated
+ * (hipMalloc) or grown on the first call that needs the size and kept until the process ends.
+ * Consequences: calls on one device must not overlap (issue them to one stream); a call that has
+ * to grow the buffer synchronises the device and cannot be captured into a graph; an allocation
+ * failure is reported as QUEST_ERR_LAUNCH.  All other entry points allocate nothing.
  */
 quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_codes,
                              const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,
