@@ -212,6 +212,7 @@ constexpr int kRowBytes = TK / 2;                      // packed bytes per tile 
 constexpr int kStageBytes = (TM + TN) * kRowBytes;     // 24 KiB
 constexpr int kStages = 3;
 constexpr int kParkBytes = 4 * 128 * 64 * 2;           // epilogue: four waves x 128 x 64 bf16 (reuses the stages)
+static_assert(kParkBytes <= kStages * kStageBytes, "the epilogue parks in the stages");
 constexpr int kTileLds = kStages * kStageBytes + TN * 4;   // 72 KiB + the tile's weight scales
 
 // 16-byte chunk c (0..3) of tile row `row` lives at chunk c ^ swz(row).  The LDS serves 128-bit
@@ -298,6 +299,16 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
 
     static_for<6>([&](auto i) { QUEST_DMA(smem_addr, decltype(i)::value, 0); });
     static_for<6>([&](auto i) { QUEST_DMA(smem_addr + kStageBytes, decltype(i)::value, 1); });
+    // the epilogue's scales, fetched while the first stages are on their way: the weight scales of
+    // the tile's columns into their own corner of LDS, this lane's four activation scales into
+    // registers (float(64 acc) * (s_a / 64) rounds exactly like float(acc) * s_a)
+    float *scale_lds = reinterpret_cast<float *>(smem + kStages * kStageBytes);
+    if (tid < TN)
+        scale_lds[tid] = b_scales[min(n0 + tid, N - 1)];
+    float sa_reg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        sa_reg[i] = a_scales[min(m0 + wm * 128 + i * 32 + lm, M - 1)] * (1.0f / 64.0f);
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -316,13 +327,38 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     };
     static_for<6>([&](auto f) { load_frag(smem, 0, decltype(f)::value); });
 
-    // Main loop: 32 MFMAs per step and wave, everything else pinned between them.
-    //   MFMA k: pair p = k / 16, half e = (k / 8) % 2, A tile i = (k / 2) % 4, B tile j = k % 2
+    // Widened operands of the sub-step being multiplied: both B fragments, and two A fragments
+    // (A fragment i sits in wa[i % 2] while its two instructions run).  Sub-step g = 2 p + e takes
+    // words (x, y) (e = 0) or (z, w) (e = 1) of the packed fragments of pair p.
+    v4i wa[2], wb[2];
+    auto widen_a = [&](auto gc, auto ic) {
+        constexpr int g = decltype(gc)::value & 3, i = decltype(ic)::value;
+        constexpr int p = g >> 1, e = g & 1;
+        int w0, w1, w2, w3;
+        widen8(e ? af[p][i].z : af[p][i].x, nibble_mask, w0, w1);
+        widen8(e ? af[p][i].w : af[p][i].y, nibble_mask, w2, w3);
+        wa[i & 1] = v4i{w0, w1, w2, w3};
+    };
+    auto widen_b = [&](auto gc, auto jc) {
+        constexpr int g = decltype(gc)::value & 3, j = decltype(jc)::value;
+        constexpr int p = g >> 1, e = g & 1;
+        int w0, w1, w2, w3;
+        widen8(e ? bf[p][j].z : bf[p][j].x, nibble_mask, w0, w1);
+        widen8(e ? bf[p][j].w : bf[p][j].y, nibble_mask, w2, w3);
+        wb[j] = v4i{w0, w1, w2, w3};
+    };
+    widen_a(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    widen_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+
+    // Main loop: 32 MFMAs per step and wave, everything else pinned between them, at most one
+    // widening (six vector ops) per MFMA so that the vector unit never has a burst to work off.
+    //   MFMA k: sub-step g = k / 8, within it s = k % 8 multiplies A fragment s / 2 with B fragment s % 2
+    //   s = 0: widen B1   s = 1, 3, 5: widen A1, A2, A3   s = 6, 7: widen B0, A0 of the next sub-step
     //   k = 0..5    start the transfer of step + 2 into the stage that was read in step - 1
-    //   k = 0..5    load the fragments of pair 1 (needed from k = 16)
-    //   k = 23      wait for this wave's transfers of step + 1 (issued one step ago: all but the six
+    //   k = 2..7    load the packed fragments of pair 1 (first needed after k = 14)
+    //   k = 20      wait for this wave's transfers of step + 1 (issued one step ago: all but the six
     //               newest), then the workgroup barrier: step + 1 is complete in LDS
-    //   k = 24..29  load the fragments of pair 0 of step + 1
+    //   k = 21..26  load the packed fragments of pair 0 of step + 1 (first needed after k = 30)
     // Three stages: a transfer has almost two steps to land, and no wave waits on the barrier with
     // an empty MFMA queue.
     int stage_cur = 0;   // byte offsets of the stages holding step, step + 1, step + 2
@@ -330,38 +366,29 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     for (int step = 0; step < steps; ++step) {
         const uint8_t *cur = smem + stage_cur;
         const uint8_t *one = smem + stage_one;
-        v4i bw[2];
         static_for<32>([&](auto kc) {
             constexpr int k = decltype(kc)::value;
-            constexpr int p = k >> 4, e = (k >> 3) & 1, i = (k >> 1) & 3, j = k & 1;
-            if constexpr ((k & 7) == 0) {   // widen the two B fragments of this half
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    int w0, w1, w2, w3;
-                    widen8(e ? bf[p][jj].z : bf[p][jj].x, nibble_mask, w0, w1);
-                    widen8(e ? bf[p][jj].w : bf[p][jj].y, nibble_mask, w2, w3);
-                    bw[jj] = v4i{w0, w1, w2, w3};
-                }
-            }
-            v4i aw;
-            {
-                int w0, w1, w2, w3;
-                widen8(e ? af[p][i].z : af[p][i].x, nibble_mask, w0, w1);
-                widen8(e ? af[p][i].w : af[p][i].y, nibble_mask, w2, w3);
-                aw = v4i{w0, w1, w2, w3};
-            }
+            constexpr int g = k >> 3, s = k & 7, i = s >> 1, j = s & 1;
             // weight fragment as the row operand: transposed accumulator tiles
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bw[j], aw, acc[i][j], 0, 0, 0);
-            if constexpr (k < 6) {
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[j], wa[i & 1], acc[i][j], 0, 0, 0);
+            if constexpr (s == 0)
+                widen_b(std::integral_constant<int, g>{}, std::integral_constant<int, 1>{});
+            if constexpr (s == 1 || s == 3 || s == 5)
+                widen_a(std::integral_constant<int, g>{}, std::integral_constant<int, (s + 1) / 2>{});
+            if constexpr (s == 6)
+                widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
+            if constexpr (s == 7)
+                widen_a(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
+            if constexpr (k < 6)
                 QUEST_DMA(smem_addr + stage_two, k, step + 2);
-                load_frag(cur, 1, k);
-            }
-            if constexpr (k == 23) {
+            if constexpr (k >= 2 && k < 8)
+                load_frag(cur, 1, k - 2);
+            if constexpr (k == 20) {
                 wait_vmcnt<6>();
                 __builtin_amdgcn_s_barrier();
             }
-            if constexpr (k >= 24 && k < 30)
-                load_frag(one, 0, k - 24);
+            if constexpr (k >= 21 && k < 27)
+                load_frag(one, 0, k - 21);
             __builtin_amdgcn_sched_barrier(0);
         });
         const int t = stage_cur;
@@ -376,11 +403,7 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
     // consecutive columns.  Each wave converts its 128 x 64 block to bf16, parks it in its own
     // 16 KiB of LDS (16-byte chunks swizzled by row) and writes it out as 128-byte row segments.
-    float *scale_lds = reinterpret_cast<float *>(smem + kParkBytes);
     __syncthreads();   // every wave is done with the stages
-    if (tid < TN)
-        scale_lds[tid] = b_scales[min(n0 + tid, N - 1)];
-    __syncthreads();
 
     if (acc_out) {
 #pragma unroll
@@ -402,8 +425,7 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = i * 32 + lm;   // row within the wave's block
-        // float(64 acc) * (s_a / 64) rounds exactly like float(acc) * s_a
-        const float sa = a_scales[min(m0 + wm * 128 + row, M - 1)] * (1.0f / 64.0f);
+        const float sa = sa_reg[i];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
 #pragma unroll
@@ -461,6 +483,7 @@ constexpr int kWideThreads = 512;
 constexpr int kWideRowBytes = WTK / 2;                      // packed bytes per tile row and step: 128
 constexpr int kWideStageBytes = (WTM + WTN) * kWideRowBytes;     // 64 KiB
 constexpr int kWideParkBytes = 8 * 128 * 64 * 2;           // epilogue: eight waves x 128 x 64 bf16 (reuses the stages)
+static_assert(kWideParkBytes <= 2 * kWideStageBytes, "the epilogue parks in the stages");
 constexpr int kWideLds = 2 * kWideStageBytes + WTN * 4;     // 128 KiB + the tile's weight scales
 
 // 16-byte chunk c (0..7) of tile row `row` lives at chunk c ^ wide_swz(row).  The LDS serves 128-bit
@@ -536,6 +559,14 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
               (STAGE) + ((I) < 4 ? 0 : WTM * kWideRowBytes) + (64 * ((I)&3) + 8 * wave_u) * kWideRowBytes)
 
     static_for<8>([&](auto i) { QUEST_WIDE_DMA(smem_addr, decltype(i)::value, 0); });
+    // the epilogue's scales, fetched while the first stage is on its way (see the kernel above)
+    float *scale_lds = reinterpret_cast<float *>(smem + 2 * kWideStageBytes);
+    if (tid < WTN)
+        scale_lds[tid] = b_scales[min(n0 + tid, N - 1)];
+    float sa_reg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        sa_reg[i] = a_scales[min(m0 + wm * 128 + i * 32 + lm, M - 1)] * (1.0f / 64.0f);
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -606,11 +637,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
     // consecutive columns.  Each wave converts its 128 x 64 block to bf16, parks it in its own
     // 16 KiB of LDS (16-byte chunks swizzled by row) and writes it out as 128-byte row segments.
-    float *scale_lds = reinterpret_cast<float *>(smem + kWideParkBytes);
     __syncthreads();   // every wave is done with the stages
-    if (tid < WTN)
-        scale_lds[tid] = b_scales[min(n0 + tid, N - 1)];
-    __syncthreads();
 
     if (acc_out) {
 #pragma unroll
@@ -632,8 +659,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = i * 32 + lm;   // row within the wave's block
-        // float(64 acc) * (s_a / 64) rounds exactly like float(acc) * s_a
-        const float sa = a_scales[min(m0 + wm * 128 + row, M - 1)] * (1.0f / 64.0f);
+        const float sa = sa_reg[i];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
 #pragma unroll
