@@ -153,6 +153,8 @@ void hq_mfma_kernel(
     constexpr int NI = 8 * HT;             // elements per lane
     constexpr int cols = 512 * HT;
     constexpr bool kHalfTail = (HT & 1) != 0;
+    // tiles transformed together: all of them when the block spans tiles, else two (one mask word)
+    constexpr int G = (LOG2N > 10) ? T : (T >= 2 ? 2 : 1);
     constexpr int kLevels = 16;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -233,7 +235,7 @@ void hq_mfma_kernel(
         RawRow raw;
         load_row(row, raw);
 #endif
-        float acc[T][16];
+        // sum of squares from the packed inputs (the block transform is orthonormal)
         float sumsq = 0.0f;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -245,81 +247,8 @@ void hq_mfma_kernel(
                 __builtin_memcpy(&pair, &w[i], 4);
                 sumsq = __builtin_amdgcn_fdot2_f32_bf16(pair, pair, sumsq, false);
             }
-            v8bf f0, f1;
-            __builtin_memcpy(&f0, &a0, 16);
-            __builtin_memcpy(&f1, &a1, 16);
-            v16f z;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                z[r] = 0.0f;
-            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
-            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[t][r] = z[r];
         }
         sumsq = wave_sum(sumsq);
-
-        if (LOG2N > 5) {  // bit 5 = register bit 0
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2)
-                    bfly(acc[t][r], acc[t][r + 1]);
-        }
-        if (LOG2N > 6) {  // bit 6 = register bit 1
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!(r & 2))
-                        bfly(acc[t][r], acc[t][r + 2]);
-        }
-        // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][r]),
-                                                                 __float_as_uint(acc[t][r + 1]),
-                                                                 false, false);
-                acc[t][r] = __uint_as_float(sw[0]);
-                acc[t][r + 1] = __uint_as_float(sw[1]);
-            }
-        if (LOG2N > 7) {
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2)
-                    bfly(acc[t][r], acc[t][r + 1]);
-        }
-        if (LOG2N > 8) {  // bit 8 = register bit 2
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!(r & 4))
-                        bfly(acc[t][r], acc[t][r + 4]);
-        }
-        if (LOG2N > 9) {  // bit 9 = register bit 3
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-                for (int r = 0; r < 8; ++r)
-                    bfly(acc[t][r], acc[t][r + 8]);
-        }
-#pragma unroll
-        for (int k = 0; (1 << k) < T; ++k) {  // bits >= 10 pair whole tiles
-            if (LOG2N > 10 + k) {
-#pragma unroll
-                for (int t = 0; t < T; ++t)
-                    if (!(t & (1 << k)) && (t | (1 << k)) < T) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            bfly(acc[t][r], acc[t | (1 << k)][r]);
-                    }
-            }
-        }
 
         // Per-row constants in the un-normalised domain (x_h = raw / sqrt(n)).  The reciprocal and
         // the square root are the hardware approximations (1 ulp): the codes are decided on
@@ -332,53 +261,157 @@ void hq_mfma_kernel(
         const float trust_raw = trust_edge * rms * sqrt_n;
         if (lane == 0)
             scales[row] = clip * (1.0f / (float)(kLevels - 1));
-
-        if (xh_out) {
-            float *dst = xh_out + row * cols + lane;   // element = lane + 64 iota
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-                dst[64 * i] = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
-        }
-
-        // codes: byte = sat_u8(rne(16 cell + 128 - 1/2)); its high nibble is
-        // clamp(floor(cell) + 8, 0, 15) = c.  Eight per dword in iota order, then the transpose.
         uint32_t *code_row = reinterpret_cast<uint32_t *>(codes + row * (cols / 2));
-#pragma unroll
-        for (int d = 0; d < HT; ++d) {
-            uint32_t even = 0, odd = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float v = acc[(8 * d + i) >> 4][reg_of_iota((8 * d + i) & 15)];
-                const float t = __fmaf_rn(v, cell16, 127.5f);
-                if (i & 1)
-                    odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
-                else
-                    even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
-            }
-            const uint32_t packed = ((even >> 4) & 0x0f0f0f0fu) | (odd & 0xf0f0f0f0u);
-            store_word(code_row + code_word + 64 * d, nibble_plan.apply(packed));
-        }
+        uint32_t *mask_row = reinterpret_cast<uint32_t *>(mask + row * (cols / 8));
 
-        // trust mask: one bit per element in iota order (sign of trust_raw - |raw|), then the
-        // 32 x 32 bit transpose; lane m ends up with the bits of 32 consecutive elements
-        if (WITH_MASK) {
-            uint32_t *mask_row = reinterpret_cast<uint32_t *>(mask + row * (cols / 8));
+        // The transform couples whole tiles only for blocks above 1024.  Below that the tiles are
+        // worked off two at a time (the 32 elements per lane that one mask word transposes), so
+        // that a long row holds its packed inputs and 32 transformed values, not all of them.
 #pragma unroll
-            for (int c = 0; c * 32 < NI; ++c) {
-                const int count = (NI - 32 * c) < 32 ? (NI - 32 * c) : 32;
-                uint32_t untrusted = 0;
+        for (int g0 = 0; g0 < T; g0 += G) {
+            float acc[G][16];
 #pragma unroll
-                for (int i = count - 1; i >= 0; --i) {
-                    const float v = acc[(32 * c + i) >> 4][reg_of_iota((32 * c + i) & 15)];
-                    const float slack = trust_raw - fabsf(v);          // negative <=> untrusted
-                    untrusted = __builtin_amdgcn_alignbit(untrusted, __float_as_uint(slack), 31);
+            for (int u = 0; u < G; ++u) {
+                const int t = g0 + u;
+                if (t < T) {
+                    v8bf f0, f1;
+                    __builtin_memcpy(&f0, &raw.a[t][0], 16);
+                    __builtin_memcpy(&f1, &raw.a[t][1], 16);
+                    v16f z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        z[r] = 0.0f;
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[u][r] = z[r];
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[u][r] = 0.0f;
                 }
-                uint32_t trusted = ~untrusted;
-                if (count < 32)
-                    trusted &= (1u << count) - 1u;
-                trusted = bit_plan.apply(trusted);
-                if (m < count)
-                    store_word(mask_row + h + 2 * (m + 32 * c), trusted);
+            }
+
+            if (LOG2N > 5) {  // bit 5 = register bit 0
+#pragma unroll
+                for (int u = 0; u < G; ++u)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2)
+                        bfly(acc[u][r], acc[u][r + 1]);
+            }
+            if (LOG2N > 6) {  // bit 6 = register bit 1
+#pragma unroll
+                for (int u = 0; u < G; ++u)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (!(r & 2))
+                            bfly(acc[u][r], acc[u][r + 2]);
+            }
+            // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
+#pragma unroll
+            for (int u = 0; u < G; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[u][r]),
+                                                                     __float_as_uint(acc[u][r + 1]),
+                                                                     false, false);
+                    acc[u][r] = __uint_as_float(sw[0]);
+                    acc[u][r + 1] = __uint_as_float(sw[1]);
+                }
+            if (LOG2N > 7) {
+#pragma unroll
+                for (int u = 0; u < G; ++u)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2)
+                        bfly(acc[u][r], acc[u][r + 1]);
+            }
+            if (LOG2N > 8) {  // bit 8 = register bit 2
+#pragma unroll
+                for (int u = 0; u < G; ++u)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (!(r & 4))
+                            bfly(acc[u][r], acc[u][r + 4]);
+            }
+            if (LOG2N > 9) {  // bit 9 = register bit 3
+#pragma unroll
+                for (int u = 0; u < G; ++u)
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        bfly(acc[u][r], acc[u][r + 8]);
+            }
+#pragma unroll
+            for (int k = 0; (1 << k) < G; ++k) {  // bits >= 10 pair whole tiles (then G = T)
+                if (LOG2N > 10 + k) {
+#pragma unroll
+                    for (int u = 0; u < G; ++u)
+                        if (!(u & (1 << k)) && (u | (1 << k)) < G) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                bfly(acc[u][r], acc[u | (1 << k)][r]);
+                        }
+                }
+            }
+
+            // in-lane elements of this group: iota = 16 g0 .. , as far as the row goes
+            constexpr int kGroupI = 16 * G;
+            const int first = 16 * g0;
+            const int count_i = (NI - first) < kGroupI ? (NI - first) : kGroupI;
+
+            if (xh_out) {
+                float *dst = xh_out + row * cols + lane;   // element = lane + 64 iota
+#pragma unroll
+                for (int i = 0; i < kGroupI; ++i)
+                    if (i < count_i)
+                        dst[64 * (first + i)] = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
+            }
+
+            // codes: byte = sat_u8(rne(16 cell + 128 - 1/2)); its high nibble is
+            // clamp(floor(cell) + 8, 0, 15) = c.  Eight per dword in iota order, then the transpose.
+#pragma unroll
+            for (int dd = 0; dd < 2 * G; ++dd) {
+                if (8 * dd < count_i) {
+                    uint32_t even = 0, odd = 0;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float v = acc[(8 * dd + i) >> 4][reg_of_iota((8 * dd + i) & 15)];
+                        const float t = __fmaf_rn(v, cell16, 127.5f);
+                        if (i & 1)
+                            odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
+                        else
+                            even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+                    }
+                    const uint32_t packed = ((even >> 4) & 0x0f0f0f0fu) | (odd & 0xf0f0f0f0u);
+                    store_word(code_row + code_word + 64 * (2 * g0 + dd), nibble_plan.apply(packed));
+                }
+            }
+
+            // trust mask: one bit per element in iota order (sign of trust_raw - |raw|), then the
+            // 32 x 32 bit transpose; lane m ends up with the bits of 32 consecutive elements
+            if (WITH_MASK) {
+#pragma unroll
+                for (int cc = 0; cc * 32 < kGroupI; ++cc) {
+                    const int left = count_i - 32 * cc;
+                    if (left > 0) {
+                        const int count = left < 32 ? left : 32;
+                        uint32_t untrusted = 0;
+#pragma unroll
+                        for (int i = 31; i >= 0; --i) {
+                            if (i < count) {
+                                const float v = acc[(32 * cc + i) >> 4][reg_of_iota((32 * cc + i) & 15)];
+                                const float slack = trust_raw - fabsf(v);          // negative <=> untrusted
+                                untrusted = __builtin_amdgcn_alignbit(untrusted, __float_as_uint(slack), 31);
+                            }
+                        }
+                        uint32_t trusted = ~untrusted;
+                        if (count < 32)
+                            trusted &= (1u << count) - 1u;
+                        trusted = bit_plan.apply(trusted);
+                        if (m < count)
+                            store_word(mask_row + h + 2 * (m + 32 * (g0 / 2 + cc)), trusted);
+                    }
+                }
             }
         }
     }
