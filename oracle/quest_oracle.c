@@ -168,7 +168,6 @@ void qo_project(const double *xh, int64_t rows, int64_t cols, int bits, double a
 {
     const int64_t L = (int64_t)1 << bits;
     const double D = 2.0 * alpha / (double)(L - 1);
-    const double T = alpha / (double)(L - 1);
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
         const double *row = xh + r * cols;
@@ -194,8 +193,12 @@ void qo_project(const double *xh, int64_t rows, int64_t cols, int bits, double a
                 k = (int64_t)cell;
                 xhat = rms * alpha * (double)(2 * k + 1) / (double)(L - 1);
                 const double err = fabs(xhat - row[j]);
-                const double t_eff = (fabs(xn) <= alpha) ? T : outer_trust * T;
-                trusted = (err <= t_eff * rms) ? 1 : 0;
+                /* T_eff * rms, written with the operations of xhat in the same order: a value on
+                 * a cell boundary (x_h = 0 after exact cancellation is one) has error exactly T and
+                 * is trusted by the definition; two differently rounded products must not turn
+                 * that equality into "greater". */
+                const double t_factor = (fabs(xn) <= alpha) ? 1.0 : outer_trust;
+                trusted = (err <= rms * alpha * t_factor / (double)(L - 1)) ? 1 : 0;
             }
             if (k_out)
                 k_out[r * cols + j] = (int32_t)k;

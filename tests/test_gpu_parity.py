@@ -283,6 +283,63 @@ def test_grad_gemm_full_size_sampled_rows():
     assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
 
 
+def test_down_projection_full_size():
+    """The MLP down-projection (X 16384 x 5632 in blocks of 512, W 2048 x 5632; Sec. 5 singles this
+    layer out for its transform overhead): quantizer on the whole activation tensor, forward GEMM,
+    both gradient matmuls and the trust backward on sampled rows, all at the full launch shape."""
+    x, w, cfg = synth.make_config("mlp_down_1p6b", seed=0)
+    K, bits, n = cfg["K"], cfg["bits"], cfg["had_block"]
+    M, N = x.shape[0], w.shape[0]
+    gx = gpu_quantize(x, n, bits, want_xh=False)
+    gw = gpu_quantize(w, n, bits, want_xh=False)
+    ref = qo.hadamard_quantize(x, n, bits)
+    compare_quantizer(gx, ref, K, bits)
+    del ref
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    q.quest_lowbit_gemm(gx["dev"]["codes"], gx["dev"]["scales"], gw["dev"]["codes"], gw["dev"]["scales"],
+                        K, bits, y=y, acc_out=None)
+    dy = synth.upstream_gradient(M, N, 5, "bf16")
+    dyd = to_device(dy)
+    g_x = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
+    g_w = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
+    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x)
+    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w)
+    dx = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
+    q.quest_trust_backward(g_x, gx["dev"]["mask"], n, out=dx)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(2)
+    rows = np.sort(rng.choice(M, size=16, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    rows_d = torch.from_numpy(rows).to(DEV)
+    ux_all = qo.unpack_odd(gx["codes"], K, bits)
+    uw = qo.unpack_odd(gw["codes"], K, bits)
+    sx, sw = gx["scales"].astype(np.float64), gw["scales"].astype(np.float64)
+    # forward GEMM rows
+    check_gemm_output(y[rows_d], qo.gemm_odd(ux_all[rows], uw), gx["scales"][rows], gw["scales"])
+    # G_x rows, then the masked inverse transform of exactly what the GPU produced for them
+    d = qo.widen(dy[rows])
+    ref = qo.grad_input(d, uw, sw)
+    q16 = qo.widen(synth.to_bf16_bits(gw["scales"][:, None] * uw.astype(np.float32)))
+    spread = np.sqrt((d ** 2) @ (q16 ** 2))
+    got = to_host_f64(g_x[rows_d])
+    assert np.all(np.abs(got - d @ q16) <= BF16_HALF_ULP * 1.001 * np.abs(d @ q16) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+    ref_dx = qo.trust_backward(got, qo.unpack_mask(gx["mask"][rows], K), n)
+    scale = np.sqrt(np.mean(ref_dx * ref_dx, axis=1, keepdims=True))
+    assert np.all(np.abs(to_host_f64(dx[rows_d]) - ref_dx) <= BF16_HALF_ULP * np.abs(ref_dx) + 1e-5 * scale + 1e-30)
+    # G_w rows (columns of dy)
+    cols = np.sort(rng.choice(N, size=8, replace=False))
+    cols[0], cols[-1] = 0, N - 1
+    d = qo.widen(np.ascontiguousarray(dy[:, cols]))
+    ref = qo.grad_weight(d, ux_all, sx)
+    q16 = qo.widen(synth.to_bf16_bits(gx["scales"][:, None] * ux_all.astype(np.float32)))
+    mirror = d.T @ q16
+    spread = np.sqrt((d.T ** 2) @ (q16 ** 2))
+    got = to_host_f64(g_w[torch.from_numpy(cols).to(DEV)])
+    assert np.all(np.abs(got - mirror) <= BF16_HALF_ULP * 1.001 * np.abs(mirror) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+
+
 def test_full_linear_forward_backward_small():
     """Algorithm 1 + Algorithm 2 end to end through the C ABI on a small layer."""
     M, N, K, bits, n = 128, 192, 512, 4, 512

@@ -164,3 +164,21 @@ def test_packing_layouts_byte_by_byte():
     _load().qo_pack_mask(_ptr(trust), 1, 16, _ptr(bm))
     assert bm[0].tolist() == [0b10111001, 0b10000000]
     assert np.array_equal(qo.unpack_mask(bm, 16), trust)
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_exact_zero_is_trusted_at_any_scale(bits):
+    """Sec. 3.2: M = 1[|xhat - x_h| <= T].  x_h = 0 (exact cancellation in the transform) sits on
+    the boundary of cell 0; its error is exactly T, so it is trusted whatever the row's RMS is,
+    also where T rms and xhat would round differently if written as different products."""
+    rng = np.random.default_rng(bits)
+    xh = rng.standard_normal((4000, 16)) * np.exp(rng.uniform(-8, 8, size=(4000, 1)))
+    xh[:, 5] = 0.0
+    p = qo.project(xh, bits)
+    assert np.all(p.k[:, 5] == 0)
+    assert np.all(p.trust[:, 5] == 1)
+    # and through the transform: (1, 1) -> (sqrt 2, 0), (3, -3) -> (0, 3 sqrt 2), at random scales
+    x = np.tile(np.array([1.0, 1.0, 3.0, -3.0]), (500, 4)) * np.exp(rng.uniform(-8, 8, size=(500, 1)))
+    q = qo.hadamard_quantize(x.astype(np.float32), 2, bits)
+    assert np.all(q.xh[:, 1::4] == 0.0) and np.all(q.xh[:, 2::4] == 0.0)
+    assert np.all(q.trust[:, 1::4] == 1) and np.all(q.trust[:, 2::4] == 1)
