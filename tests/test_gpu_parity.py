@@ -1,4 +1,6 @@
 """GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -92,6 +94,52 @@ def test_quantizer_full_size_headline_shape():
     ref = qo.hadamard_quantize(x, cfg["had_block"], cfg["bits"])
     n_code, n_mask = compare_quantizer(got, ref, cfg["K"], cfg["bits"])
     print(f"full size: {n_code} codes and {n_mask} mask bits at a boundary out of {x.size}")
+
+
+@pytest.mark.parametrize("n", [128, 1024])
+def test_quantizer_and_gemm_100m_layer_full_size(n):
+    """X 8192 x 1024 with 1 % outlier channels x 20, W 4096 x 1024, Hadamard block 128 and 1024:
+    whole tensors against the oracle, the forward GEMM (68.7 GOP) on sampled rows.  The full-width
+    transform must also give the smaller quantization error (why Sec. 3.1 transforms whole rows)."""
+    x, w, cfg = synth.make_config("mlp_up_100m", seed=0)
+    K, bits = cfg["K"], cfg["bits"]
+    gx = gpu_quantize(x, n, bits, want_xh=False)
+    gw = gpu_quantize(w, n, bits, want_xh=False)
+    rx, rw = qo.hadamard_quantize(x, n, bits), qo.hadamard_quantize(w, n, bits)
+    compare_quantizer(gx, rx, K, bits)
+    compare_quantizer(gw, rw, K, bits)
+    M, N = x.shape[0], w.shape[0]
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    q.quest_lowbit_gemm(gx["dev"]["codes"], gx["dev"]["scales"], gw["dev"]["codes"], gw["dev"]["scales"],
+                        K, bits, y=y)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(n).choice(M, size=64, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    ux, uw = qo.unpack_odd(gx["codes"][rows], K, bits), qo.unpack_odd(gw["codes"], K, bits)
+    check_gemm_output(y[torch.from_numpy(rows).to(DEV)], qo.gemm_odd(ux, uw), gx["scales"][rows], gw["scales"])
+    # relative quantization error of the GPU's own codes, in the Hadamard domain
+    xhat = gx["scales"][:, None].astype(np.float64) * qo.unpack_odd(gx["codes"], K, bits)
+    err = np.linalg.norm(xhat - rx.xh) / np.linalg.norm(rx.xh)
+    print(f"block {n}: relative error of xhat_h {err:.4f}")
+    assert err < (0.16 if n == 1024 else 0.30)
+
+
+@pytest.mark.parametrize("bits,outer_trust", [(1, 1.0), (1, 0.30), (2, 1.0), (3, 1.0), (4, 1.0), (8, 1.0)])
+def test_bit_sweep_student_t_full_size(bits, outer_trust, alpha_table):
+    """X 16384 x 2048, Student-t with 3 degrees of freedom at unit RMS, block 2048, every bit width:
+    whole tensor against the oracle.  After the transform the rows are close to Gaussian, so the
+    share of untrusted elements must be close to the Gaussian tail beyond the trust edge."""
+    x, _, cfg = synth.make_config("bit_sweep_1p6b", seed=0)
+    K, n = cfg["K"], cfg["had_block"]
+    got = gpu_quantize(x, n, bits, outer_trust=outer_trust, want_xh=False)
+    ref = qo.hadamard_quantize(x, n, bits, outer_trust=outer_trust)
+    compare_quantizer(got, ref, K, bits, outer_trust=outer_trust)
+    untrusted = 1.0 - qo.unpack_mask(got["mask"], K).mean()
+    levels = 1 << bits
+    edge = alpha_table[bits] * (1.0 + outer_trust / (levels - 1))
+    gaussian_tail = math.erfc(edge / math.sqrt(2.0))
+    print(f"b={bits} outer_trust={outer_trust}: untrusted {untrusted:.5f}, Gaussian tail {gaussian_tail:.5f}")
+    assert abs(untrusted - gaussian_tail) < 0.1 * gaussian_tail + 2e-4
 
 
 # ------------------------------------------------------------------ GEMM
