@@ -210,6 +210,59 @@ void qo_project(const double *xh, int64_t rows, int64_t cols, int bits, double a
     }
 }
 
+/*
+ * AbsMax projection: the comparison quantizer of Sec. 4.1 (the QAT extension of a rotation-based
+ * PTQ method, "AbsMax scaling instead of proper distribution matching").  The paper gives no
+ * formula; the reading taken here keeps everything of the projection above and replaces the
+ * clip alpha * rms by the row's largest magnitude a = max_j |x_h[j]|:
+ *   D    = 2 a / (L - 1),  k = clamp(floor(x_h / D), -L/2, L/2 - 1)
+ *   xhat = a (2k + 1) / (L - 1),  scale = a / (L - 1)
+ *   M    = 1 iff |xhat - x_h| <= a / (L - 1)   (nothing is clipped, so every element is trusted)
+ * A zero row (a = 0) maps to k = 0 everywhere with xhat = 0 and M = 1.
+ * Outputs as for qo_project; amax_out[rows] takes the place of rms_out.
+ */
+void qo_project_absmax(const double *xh, int64_t rows, int64_t cols, int bits, double *amax_out,
+                       double *scale_out, int32_t *k_out, double *xhat_out, uint8_t *trust_out)
+{
+    const int64_t L = (int64_t)1 << bits;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *row = xh + r * cols;
+        double a = 0.0;
+        for (int64_t j = 0; j < cols; ++j)
+            if (fabs(row[j]) > a)
+                a = fabs(row[j]);
+        if (amax_out)
+            amax_out[r] = a;
+        if (scale_out)
+            scale_out[r] = a / (double)(L - 1);
+        const double D = 2.0 * a / (double)(L - 1);
+        for (int64_t j = 0; j < cols; ++j) {
+            int64_t k = 0;
+            double xhat = 0.0;
+            int trusted = 1;
+            if (a > 0.0) {
+                double cell = floor(row[j] / D);
+                if (cell < (double)(-L / 2))
+                    cell = (double)(-L / 2);
+                if (cell > (double)(L / 2 - 1))
+                    cell = (double)(L / 2 - 1);
+                k = (int64_t)cell;
+                xhat = a * (double)(2 * k + 1) / (double)(L - 1);
+                /* mathematically |xhat - x_h| <= a / (L - 1) always; the factor absorbs the
+                 * separate roundings of the two sides for a value on a cell boundary */
+                trusted = (fabs(xhat - row[j]) <= a / (double)(L - 1) * (1.0 + 4e-16)) ? 1 : 0;
+            }
+            if (k_out)
+                k_out[r * cols + j] = (int32_t)k;
+            if (xhat_out)
+                xhat_out[r * cols + j] = xhat;
+            if (trust_out)
+                trust_out[r * cols + j] = (uint8_t)trusted;
+        }
+    }
+}
+
 /* ------------------------------------------------------------------ storage formats */
 
 /* Container width in bits for a b-bit code: 3-bit codes sit in a nibble. */

@@ -55,6 +55,7 @@ def _load():
             getattr(lib, name).argtypes = [_p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_row_rms.argtypes = [_p, _c_i64, _c_i64, _p]
         lib.qo_project.argtypes = [_p, _c_i64, _c_i64, _c_int, _c_dbl, _c_dbl, _p, _p, _p, _p, _p]
+        lib.qo_project_absmax.argtypes = [_p, _c_i64, _c_i64, _c_int, _p, _p, _p, _p, _p]
         lib.qo_container_bits.argtypes = [_c_int]
         lib.qo_container_bits.restype = _c_int
         lib.qo_pack_codes.argtypes = [_p, _c_i64, _c_i64, _c_int, _p]
@@ -170,10 +171,36 @@ def project(xh: np.ndarray, bits: int, alpha: float | None = None,
     return Projection(xh, rms, scale, k, xhat, trust, codes, mask, float(alpha), bits)
 
 
+def project_absmax(xh: np.ndarray, bits: int) -> Projection:
+    """The AbsMax comparison quantizer (Sec. 4.1): the grid spans the row's largest magnitude.
+    In the result `rms` holds that magnitude and `alpha` is 1 (clip = alpha * rms still holds)."""
+    xh = _c(xh, np.float64)
+    rows, cols = xh.shape
+    cb = container_bits(bits)
+    amax = np.empty(rows, dtype=np.float64)
+    scale = np.empty(rows, dtype=np.float64)
+    k = np.empty((rows, cols), dtype=np.int32)
+    xhat = np.empty((rows, cols), dtype=np.float64)
+    trust = np.empty((rows, cols), dtype=np.uint8)
+    lib = _load()
+    lib.qo_project_absmax(_ptr(xh), rows, cols, bits, _ptr(amax), _ptr(scale), _ptr(k), _ptr(xhat),
+                          _ptr(trust))
+    codes = np.empty((rows, cols * cb // 8), dtype=np.uint8)
+    lib.qo_pack_codes(_ptr(k), rows, cols, bits, _ptr(codes))
+    mask = np.empty((rows, cols // 8), dtype=np.uint8)
+    lib.qo_pack_mask(_ptr(trust), rows, cols, _ptr(mask))
+    return Projection(xh, amax, scale, k, xhat, trust, codes, mask, 1.0, bits)
+
+
 def hadamard_quantize(x: np.ndarray, n: int, bits: int, alpha: float | None = None,
                       outer_trust: float = 1.0, dense: bool = False) -> Projection:
     """Algorithm 1 for one operand: x_h = HT(x), then the projection and the mask."""
     return project(hadamard(widen(x), n, dense=dense), bits, alpha, outer_trust)
+
+
+def hadamard_quantize_absmax(x: np.ndarray, n: int, bits: int, dense: bool = False) -> Projection:
+    """x_h = HT(x) (n = 1: no transform), then the AbsMax projection."""
+    return project_absmax(hadamard(widen(x), n, dense=dense), bits)
 
 
 def unpack_odd(codes: np.ndarray, cols: int, bits: int) -> np.ndarray:
