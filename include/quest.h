@@ -82,6 +82,19 @@ quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t r
                                      uint8_t *mask, float *xh_out, void *stream);
 
 /*
+ * The comparison quantizer of Sec. 4.1 ("AbsMax scaling instead of proper distribution
+ * matching"), and with had_block = 1 the no-transform ablation of Sec. 4.3: everything as in
+ * quest_hadamard_quantize, except that the grid spans the row's largest magnitude,
+ *   a = max_j |x_h[j]|,  k = clamp(floor(x_h (L - 1) / (2 a)), -L/2, L/2 - 1),  scales[r] = a / (L - 1).
+ * Nothing is clipped, so every mask bit is 1 (the mask is still written when given).  A zero row
+ * gives c = L/2, scale 0.  Same arguments, layouts, limits and errors as quest_hadamard_quantize.
+ */
+quest_status quest_hadamard_quantize_absmax(const void *x, quest_dtype dtype, int64_t rows,
+                                            int64_t cols, int64_t ld, int32_t had_block, int32_t bits,
+                                            uint8_t *codes, float *scales, uint8_t *mask,
+                                            float *xh_out, void *stream);
+
+/*
  * Algorithm 1, the matmul y = xhat_h what_h^T, run on the integer codes (Sec. 5 "Kernel
  * Overview", stage 3): acc[m, n] = sum_k u_a[m, k] u_b[n, k] exactly in int32, then
  * y[m, n] = bf16(float(acc[m, n]) * a_scales[m] * b_scales[n]).

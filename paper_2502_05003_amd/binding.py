@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
-EXPORTS = ("quest_hadamard_quantize", "quest_lowbit_gemm", "quest_trust_backward",
+EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_lowbit_gemm", "quest_trust_backward",
            "quest_grad_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
 
 _i64, _i32, _f32, _p = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
@@ -39,11 +39,13 @@ def load():
         lib = ctypes.CDLL(LIB_PATH)
         lib.quest_hadamard_quantize.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _i32, _f32, _f32,
                                                 _p, _p, _p, _p, _p]
+        lib.quest_hadamard_quantize_absmax.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _i32,
+                                                       _p, _p, _p, _p, _p]
         lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p]
         lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
         lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
-        for name in ("quest_hadamard_quantize", "quest_lowbit_gemm", "quest_trust_backward",
-                     "quest_grad_gemm"):
+        for name in ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_lowbit_gemm",
+                     "quest_trust_backward", "quest_grad_gemm"):
             getattr(lib, name).restype = ctypes.c_int
         lib.quest_alpha_star.argtypes = [_i32]
         lib.quest_alpha_star.restype = _f32
@@ -98,6 +100,17 @@ def quest_hadamard_quantize(x: torch.Tensor, had_block: int, bits: int, alpha: f
                                           had_block, bits, alpha, outer_trust, _ptr(codes),
                                           _ptr(scales), _ptr(mask), _ptr(xh_out), _stream()),
            "quest_hadamard_quantize")
+
+
+def quest_hadamard_quantize_absmax(x: torch.Tensor, had_block: int, bits: int, *, codes: torch.Tensor,
+                                   scales: torch.Tensor, mask: torch.Tensor | None = None,
+                                   xh_out: torch.Tensor | None = None) -> None:
+    """As quest_hadamard_quantize, with the grid spanning each row's largest |x_h|."""
+    rows, cols = x.shape
+    _check(load().quest_hadamard_quantize_absmax(_ptr(x), _dtype_code(x), rows, cols, x.stride(0),
+                                                 had_block, bits, _ptr(codes), _ptr(scales), _ptr(mask),
+                                                 _ptr(xh_out), _stream()),
+           "quest_hadamard_quantize_absmax")
 
 
 def quest_lowbit_gemm(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: torch.Tensor,

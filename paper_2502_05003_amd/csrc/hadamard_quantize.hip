@@ -31,6 +31,18 @@ __device__ __forceinline__ RowQuant row_quant(float sumsq, int cols, int levels,
     return q;
 }
 
+// AbsMax variant (the comparison quantizer of Sec. 4.1): the clip is the row's largest magnitude,
+// nothing is clipped and every element is trusted.
+__device__ __forceinline__ RowQuant row_quant_absmax(float amax, int levels)
+{
+    RowQuant q;
+    q.zero = !(amax > 0.0f);
+    q.inv_step = q.zero ? 0.0f : __fdiv_rn((float)(levels - 1), __fmul_rn(2.0f, amax));
+    q.trust_abs = amax;
+    q.scale = __fdiv_rn(amax, (float)(levels - 1));
+    return q;
+}
+
 // Code c = clamp(floor(x_h * inv_step), -L/2, L/2 - 1) + L/2 for one element.
 __device__ __forceinline__ uint32_t quantize_one(float xh, const RowQuant &q, int levels)
 {
@@ -49,12 +61,13 @@ __device__ __forceinline__ uint32_t quantize_one(float xh, const RowQuant &q, in
 template <typename In>
 __global__ __launch_bounds__(kGenericThreads) void hq_generic_kernel(
     const In *__restrict__ x, int64_t rows, int cols, int64_t ld, int log2n, int bits, int cb,
-    float alpha, float trust_edge, uint8_t *__restrict__ codes, float *__restrict__ scales,
-    uint8_t *__restrict__ mask, float *__restrict__ xh_out)
+    float alpha, float trust_edge, bool absmax, uint8_t *__restrict__ codes,
+    float *__restrict__ scales, uint8_t *__restrict__ mask, float *__restrict__ xh_out)
 {
     extern __shared__ float lds[];
     float *row = lds;
     __shared__ float partial[kGenericThreads / kWave];
+    __shared__ float partial_max[kGenericThreads / kWave];
 
     const int levels = 1 << bits;
     const int groups = cols >> 3;
@@ -74,25 +87,34 @@ __global__ __launch_bounds__(kGenericThreads) void hq_generic_kernel(
         }
         lds_butterfly_passes(row, cols, log2n);
 
-        // x_h = raw / sqrt(n); row sum of squares
-        float sumsq = 0.0f;
+        // x_h = raw / sqrt(n); row sum of squares and largest magnitude
+        float sumsq = 0.0f, amax = 0.0f;
         for (int g = threadIdx.x; g < groups; g += blockDim.x) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const float xh = __fmul_rn(row[lds_pad(8 * g + i)], inv_sqrt_n);
                 row[lds_pad(8 * g + i)] = xh;
                 sumsq = __fmaf_rn(xh, xh, sumsq);
+                amax = fmaxf(amax, fabsf(xh));
             }
         }
         sumsq = wave_sum(sumsq);
-        if ((threadIdx.x & (kWave - 1)) == 0)
-            partial[threadIdx.x / kWave] = sumsq;
-        __syncthreads();
-        float total = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kGenericThreads / kWave; ++w)
+        for (int off = 32; off > 0; off >>= 1)
+            amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
+        if ((threadIdx.x & (kWave - 1)) == 0) {
+            partial[threadIdx.x / kWave] = sumsq;
+            partial_max[threadIdx.x / kWave] = amax;
+        }
+        __syncthreads();
+        float total = 0.0f, total_max = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kGenericThreads / kWave; ++w) {
             total += partial[w];
-        const RowQuant q = row_quant(total, cols, levels, alpha, trust_edge);
+            total_max = fmaxf(total_max, partial_max[w]);
+        }
+        const RowQuant q = absmax ? row_quant_absmax(total_max, levels)
+                                  : row_quant(total, cols, levels, alpha, trust_edge);
         if (threadIdx.x == 0)
             scales[r] = q.scale;
 
@@ -133,7 +155,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
 {
     if (a.rows == 0)
         return hipSuccess;
-    if (launch_hadamard_quantize_mfma(a, stream))
+    if (!a.absmax && launch_hadamard_quantize_mfma(a, stream))
         return hipGetLastError();
     const int cols = (int)a.cols;
     const size_t lds_bytes = (size_t)(cols + (cols >> 5) + 1) * sizeof(float);
@@ -150,7 +172,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
             return err;
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream,
                            static_cast<const uint16_t *>(a.x), a.rows, cols, a.ld, a.log2n, a.bits,
-                           a.cb, a.alpha, a.trust_edge, a.codes, a.scales, a.mask, a.xh_out);
+                           a.cb, a.alpha, a.trust_edge, a.absmax, a.codes, a.scales, a.mask, a.xh_out);
     } else {
         auto kernel = hq_generic_kernel<float>;
         if (lds_bytes > 48 * 1024)
@@ -160,7 +182,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
             return err;
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream,
                            static_cast<const float *>(a.x), a.rows, cols, a.ld, a.log2n, a.bits,
-                           a.cb, a.alpha, a.trust_edge, a.codes, a.scales, a.mask, a.xh_out);
+                           a.cb, a.alpha, a.trust_edge, a.absmax, a.codes, a.scales, a.mask, a.xh_out);
     }
     return hipGetLastError();
 }

@@ -97,10 +97,12 @@ const char *quest_status_string(quest_status status)
     }
 }
 
-quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
-                                     int64_t ld, int32_t had_block, int32_t bits, float alpha,
-                                     float outer_trust, uint8_t *codes, float *scales,
-                                     uint8_t *mask, float *xh_out, void *stream)
+namespace {
+
+// Shared by the two quantizer entry points; absmax ignores alpha and outer_trust.
+quest_status quantize_entry(const void *x, quest_dtype dtype, int64_t rows, int64_t cols, int64_t ld,
+                            int32_t had_block, int32_t bits, float alpha, float outer_trust, bool absmax,
+                            uint8_t *codes, float *scales, uint8_t *mask, float *xh_out, void *stream)
 {
     if (!x || !codes || !scales)
         return QUEST_ERR_NULL;
@@ -142,9 +144,30 @@ quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t r
     args.scales = scales;
     args.mask = mask;
     args.xh_out = xh_out;
+    args.absmax = absmax;
     return quest::launch_hadamard_quantize(args, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUEST_OK
                : QUEST_ERR_LAUNCH;
+}
+
+}  // namespace
+
+quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
+                                     int64_t ld, int32_t had_block, int32_t bits, float alpha,
+                                     float outer_trust, uint8_t *codes, float *scales,
+                                     uint8_t *mask, float *xh_out, void *stream)
+{
+    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, alpha, outer_trust, false, codes,
+                          scales, mask, xh_out, stream);
+}
+
+quest_status quest_hadamard_quantize_absmax(const void *x, quest_dtype dtype, int64_t rows,
+                                            int64_t cols, int64_t ld, int32_t had_block, int32_t bits,
+                                            uint8_t *codes, float *scales, uint8_t *mask,
+                                            float *xh_out, void *stream)
+{
+    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, 0.0f, -1.0f, true, codes, scales,
+                          mask, xh_out, stream);
 }
 
 quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,

@@ -22,6 +22,7 @@ struct QuantizeArgs {
     float *scales;
     uint8_t *mask;     // may be null
     float *xh_out;     // may be null
+    bool absmax;       // clip at the row's largest |x_h| instead of alpha * rms (alpha, trust_edge unused)
 };
 
 hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream);

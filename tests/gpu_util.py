@@ -23,7 +23,8 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
 
 
 def gpu_quantize(x_host: np.ndarray, had_block: int, bits: int, alpha: float = 0.0,
-                 outer_trust: float = -1.0, want_xh: bool = True, want_mask: bool = True, ld=None):
+                 outer_trust: float = -1.0, want_xh: bool = True, want_mask: bool = True, ld=None,
+                 absmax: bool = False):
     """Run quest_hadamard_quantize on a host array; returns host arrays."""
     rows, cols = x_host.shape
     cb = q.quest_container_bits(bits)
@@ -37,8 +38,11 @@ def gpu_quantize(x_host: np.ndarray, had_block: int, bits: int, alpha: float = 0
     scales = torch.full((rows,), -1.0, dtype=torch.float32, device=DEV)
     mask = torch.full((rows, cols // 8), 0x55, dtype=torch.uint8, device=DEV) if want_mask else None
     xh = torch.full((rows, cols), float("nan"), dtype=torch.float32, device=DEV) if want_xh else None
-    q.quest_hadamard_quantize(x, had_block, bits, alpha, outer_trust, codes=codes, scales=scales,
-                              mask=mask, xh_out=xh)
+    if absmax:
+        q.quest_hadamard_quantize_absmax(x, had_block, bits, codes=codes, scales=scales, mask=mask, xh_out=xh)
+    else:
+        q.quest_hadamard_quantize(x, had_block, bits, alpha, outer_trust, codes=codes, scales=scales,
+                                  mask=mask, xh_out=xh)
     torch.cuda.synchronize()
     return dict(codes=codes.cpu().numpy(), scales=scales.cpu().numpy(),
                 mask=None if mask is None else mask.cpu().numpy(),

@@ -65,6 +65,44 @@ def test_quantizer_matches_oracle(rows, cols, n, bits, dtype):
     compare_quantizer(got, ref, cols, bits)
 
 
+ABSMAX_CASES = [(37, 1024, 128, 4, "bf16"), (130, 2048, 2048, 4, "bf16"), (70, 5632, 512, 4, "bf16"),
+                (33, 2048, 1, 4, "bf16"), (33, 2048, 2048, 2, "bf16"), (33, 2048, 2048, 8, "f32"),
+                (19, 512, 1, 3, "f32"), (21, 1536, 512, 1, "f32"), (4100, 256, 256, 4, "bf16")]
+
+
+@pytest.mark.parametrize("rows,cols,n,bits,dtype", ABSMAX_CASES)
+def test_absmax_quantizer_matches_oracle(rows, cols, n, bits, dtype):
+    """The AbsMax comparison quantizer (Sec. 4.1), with and without the transform (block 1 is the
+    no-transform ablation); an all-zero row among the inputs."""
+    x = synth.outlier_activations(rows, cols, 0.01, 20.0, seed=rows + cols + bits, dtype=dtype)
+    x[2] = 0
+    got = gpu_quantize(x, n, bits, absmax=True)
+    ref = qo.hadamard_quantize_absmax(x, n, bits, dense=(1 < n <= 512))
+    compare_quantizer(got, ref, cols, bits)
+    assert np.all(got["mask"] == 0xFF)
+    assert got["scales"][2] == 0.0
+    assert np.all(qo.unpack_odd(got["codes"][2:3], cols, bits) == 1)
+
+
+def test_transform_and_gaussian_clip_each_reduce_the_error():
+    """The mechanisms behind Sec. 4.3 (Hadamard ablation) and the AbsMax baseline of Sec. 4.1, on the
+    headline activations (outlier channels): relative error of the 4-bit reconstruction from the
+    GPU's own codes, for the four combinations of {transform, none} x {Gaussian-fitted clip, AbsMax}."""
+    x, _, cfg = synth.make_config("mlp_up_1p6b", seed=0, rows=2048)
+    K, bits = cfg["K"], cfg["bits"]
+    xd = qo.widen(x)
+    err = {}
+    for n in (2048, 1):
+        target = qo.hadamard(xd, n)
+        for absmax in (False, True):
+            got = gpu_quantize(x, n, bits, want_xh=False, want_mask=False, absmax=absmax)
+            xhat = got["scales"][:, None].astype(np.float64) * qo.unpack_odd(got["codes"], K, bits)
+            err[(n, absmax)] = np.linalg.norm(xhat - target) / np.linalg.norm(target)
+    print({f"block {n}, {'absmax' if a else 'rms clip'}": round(v, 4) for (n, a), v in err.items()})
+    assert err[(2048, False)] < err[(2048, True)] < err[(1, True)]
+    assert err[(2048, False)] < err[(1, False)]
+
+
 def test_quantizer_options_and_degenerate_rows():
     rows, cols, n = 16, 1024, 256
     x = synth.student_t_activations(rows, cols, 3.0, seed=4, dtype="bf16")
