@@ -385,7 +385,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
         //    0..15  fragment reads of the step's second k-step
         //   15      transfers of step + 1 have landed (all but the newest STAGES - 3 groups), barrier
         //   16..31  fragment reads of the next step's first k-step
-        //   16..23  transfers of step + STAGES - 1
+        //   16, 18, .. 30  transfers of step + STAGES - 1 (spread out: a wave issues in order, and a
+        //           transfer that finds the memory pipeline's queue full holds up the MFMAs behind it)
         static_for<32>([&](auto kc) {
             constexpr int k = decltype(kc)::value;
             constexpr int ks = k >> 4, i = (k >> 2) & 3, j = k & 3;
@@ -402,8 +403,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
             } else {
                 if constexpr (k - 16 < kReads)
                     load_frag(std::integral_constant<int, k - 16>{}, nxt_stage, std::integral_constant<int, 0>{});
-                if constexpr (k < 24)
-                    transfer(std::integral_constant<int, k - 16>{}, refill, step + STAGES - 1);
+                if constexpr ((k & 1) == 0)
+                    transfer(std::integral_constant<int, (k - 16) / 2>{}, refill, step + STAGES - 1);
             }
             __builtin_amdgcn_sched_barrier(0);
         });

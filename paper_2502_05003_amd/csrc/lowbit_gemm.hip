@@ -354,7 +354,8 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     // widening (six vector ops) per MFMA so that the vector unit never has a burst to work off.
     //   MFMA k: sub-step g = k / 8, within it s = k % 8 multiplies A fragment s / 2 with B fragment s % 2
     //   s = 0: widen B1   s = 1, 3, 5: widen A1, A2, A3   s = 6, 7: widen B0, A0 of the next sub-step
-    //   k = 0..5    start the transfer of step + 2 into the stage that was read in step - 1
+    //   k = 0, 3, .. 15  start the transfers of step + 2 into the stage that was read in step - 1
+    //               (spread out: a transfer that finds the memory queue full holds up the MFMAs)
     //   k = 2..7    load the packed fragments of pair 1 (first needed after k = 14)
     //   k = 20      wait for this wave's transfers of step + 1 (issued one step ago: all but the six
     //               newest), then the workgroup barrier: step + 1 is complete in LDS
@@ -379,8 +380,8 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
                 widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
             if constexpr (s == 7)
                 widen_a(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
-            if constexpr (k < 6)
-                QUEST_DMA(smem_addr + stage_two, k, step + 2);
+            if constexpr (k < 18 && k % 3 == 0)
+                QUEST_DMA(smem_addr + stage_two, k / 3, step + 2);
             if constexpr (k >= 2 && k < 8)
                 load_frag(cur, 1, k - 2);
             if constexpr (k == 20) {
