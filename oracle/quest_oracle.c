@@ -405,6 +405,24 @@ void qo_grad_input(const double *dy, const int32_t *uw, const double *sw, int64_
 }
 
 /*
+ * Weight-only forward product (Sec. 4.4 "Weight-only quantization": activations stay in 16 bits,
+ * only the weights go through the projection):  y[M, N] = x[M, K] * what^T,
+ * what[n, k] = s_w[n] * u_w[n, k].
+ */
+void qo_weight_only_gemm(const double *x, const int32_t *uw, const double *sw, int64_t M, int64_t N,
+                         int64_t K, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double sum = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                sum += x[m * K + k] * (sw[n] * (double)uw[n * K + k]);
+            y[m * N + n] = sum;
+        }
+}
+
+/*
  * G_w[N, K] = dY^T[N, M] * xhat[M, K], xhat[m, k] = s_x[m] * u_x[m, k]  (Alg. 2, second
  * matmul, written with the shape of the row-major weight w[N, K]).
  */

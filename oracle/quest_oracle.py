@@ -67,6 +67,7 @@ def _load():
         lib.qo_dequant.argtypes = [_p, _p, _p, _c_i64, _c_i64, _p]
         lib.qo_trust_backward.argtypes = [_p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_grad_input.argtypes = [_p, _p, _p, _c_i64, _c_i64, _c_i64, _p]
+        lib.qo_weight_only_gemm.argtypes = [_p, _p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_grad_weight.argtypes = [_p, _p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_threads.restype = _c_int
         _lib = lib
@@ -266,6 +267,18 @@ def grad_input(dy: np.ndarray, uw: np.ndarray, sw: np.ndarray) -> np.ndarray:
     gx = np.empty((M, K), dtype=np.float64)
     _load().qo_grad_input(_ptr(dy), _ptr(uw), _ptr(sw), M, N, K, _ptr(gx))
     return gx
+
+
+def weight_only_gemm(x: np.ndarray, uw: np.ndarray, sw: np.ndarray) -> np.ndarray:
+    """y = x what^T, what = s_w u_w: the forward product with 16-bit activations (Sec. 4.4)."""
+    x = _c(x, np.float64)
+    uw = _c(uw, np.int32)
+    sw = _c(sw, np.float64)
+    M, K = x.shape
+    N = uw.shape[0]
+    y = np.empty((M, N), dtype=np.float64)
+    _load().qo_weight_only_gemm(_ptr(x), _ptr(uw), _ptr(sw), M, N, K, _ptr(y))
+    return y
 
 
 def grad_weight(dy: np.ndarray, ux: np.ndarray, sx: np.ndarray) -> np.ndarray:

@@ -134,6 +134,8 @@ constexpr ReadOp kReadsTransposed[16] = {{false, 0, 0}, {false, 0, 1}, {true, 0,
                                          {false, 1, 0}, {false, 1, 1}, {false, 2, 0}, {false, 2, 1},
                                          {false, 3, 0}, {false, 3, 1}, {true, 1, 0},  {true, 1, 1},
                                          {true, 2, 0},  {true, 2, 1},  {true, 3, 0},  {true, 3, 1}};
+constexpr ReadOp kReadsRows[8] = {{false, 0, -1}, {true, 0, -1}, {false, 1, -1}, {false, 2, -1},
+                                  {false, 3, -1}, {true, 1, -1},  {true, 2, -1},  {true, 3, -1}};
 constexpr ReadOp kReadsPlain[12] = {{false, 0, 0}, {false, 0, 1}, {true, 0, -1}, {false, 1, 0},
                                     {false, 1, 1}, {false, 2, 0}, {false, 2, 1}, {false, 3, 0},
                                     {false, 3, 1}, {true, 1, -1}, {true, 2, -1}, {true, 3, -1}};
@@ -234,12 +236,21 @@ __device__ __forceinline__ void tile_origin(int tile, int tiles_r, int tiles_k, 
  * A transfer instruction moves 1 KiB (lane l to offset 16 l): sixteen rows of the row form, two
  * contraction rows of the column form; each lane fetches the chunk that belongs in its slot.
  */
-template <bool TRANSPOSED, int STAGES>
+/*
+ * MODE 0: out[M, K] = dy[M, N] what[N, K]        left = dy rows (row form),     right = expanded [c][k]
+ * MODE 1: out[N, K] = dy[M, N]^T xhat[M, K]      left = dy columns (column form), right = expanded [c][k]
+ * MODE 2: out[M, N] = x[M, K] what[N, K]^T       left = x rows (row form),       right = expanded rows
+ *         (row form: the weight-only forward product, contraction over the expanded matrix's columns)
+ * `left` has row pitch ld_left elements, the expanded operand ld_right, `out` has K columns.
+ */
+template <int MODE, int STAGES>
 __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
-    const uint16_t *__restrict__ dy, int64_t ld_dy, const uint16_t *__restrict__ qhat, int C, int K,
-    int tiles_r, int tiles_k, int per_block, int phase_period, uint16_t *__restrict__ out,
+    const uint16_t *__restrict__ dy, int64_t ld_dy, const uint16_t *__restrict__ qhat, int64_t ld_right,
+    int C, int K, int tiles_r, int tiles_k, int per_block, int phase_period, uint16_t *__restrict__ out,
     float4 *__restrict__ partial)
 {
+    constexpr bool TRANSPOSED = MODE == 1;   // left operand in column form
+    constexpr bool RIGHT_ROWS = MODE == 2;   // right operand in row form
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     static_assert(STAGES * kGStage >= kParkBytes, "the epilogue reuses the stages");
 
@@ -273,16 +284,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
         const int piece = 4 * q + wave;
         const int crow = 2 * piece + lh;
         const uint32_t column_form = (uint32_t)(((lane & 31) ^ ((crow & 3) << 2)) << 4);
-        right_voff[q] = (uint32_t)crow * (uint32_t)K * 2u + column_form;
-        if (TRANSPOSED)
-            left_voff[q] = (uint32_t)crow * (uint32_t)ld_dy * 2u + column_form;
-        else
-            left_voff[q] = (uint32_t)(16 * piece + (lane >> 2)) * (uint32_t)ld_dy * 2u +
-                           (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+        const uint32_t row_form_row = (uint32_t)(16 * piece + (lane >> 2));
+        const uint32_t row_form_chunk = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+        right_voff[q] = RIGHT_ROWS ? row_form_row * (uint32_t)ld_right * 2u + row_form_chunk
+                                   : (uint32_t)crow * (uint32_t)ld_right * 2u + column_form;
+        left_voff[q] = TRANSPOSED ? (uint32_t)crow * (uint32_t)ld_dy * 2u + column_form
+                                  : row_form_row * (uint32_t)ld_dy * 2u + row_form_chunk;
     }
     // byte advance per step
     const int64_t left_step = TRANSPOSED ? (int64_t)GC * ld_dy * 2 : (int64_t)GC * 2;
-    const int64_t right_step = (int64_t)GC * K * 2;
+    const int64_t right_step = RIGHT_ROWS ? (int64_t)GC * 2 : (int64_t)GC * ld_right * 2;
 
     // Fragment reads, byte offsets from the operand's place in a stage.
     //   row form, fragment i, k-step ks:      row_off[ks] + 2048 i
@@ -297,16 +308,21 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
             off[j] = (uint32_t)(crow * 512 + chunk * 16 + 8 * (l16 & 1));
         }
     };
-    uint32_t left_off[4], right_off[4];
-    column_offsets(wc, right_off);
-    if (TRANSPOSED) {
-        column_offsets(wr, left_off);
-    } else {
+    auto row_offsets = [&](int w, uint32_t (&off)[4]) {
         const int x = (lm >> 2) & 3;
-        left_off[0] = (uint32_t)((wr * 128 + lm) * 64 + ((lh ^ x) << 4));
-        left_off[1] = (uint32_t)((wr * 128 + lm) * 64 + (((2 + lh) ^ x) << 4));
-        left_off[2] = left_off[3] = 0;
-    }
+        off[0] = (uint32_t)((w * 128 + lm) * 64 + ((lh ^ x) << 4));
+        off[1] = (uint32_t)((w * 128 + lm) * 64 + (((2 + lh) ^ x) << 4));
+        off[2] = off[3] = 0;
+    };
+    uint32_t left_off[4], right_off[4];
+    if (RIGHT_ROWS)
+        row_offsets(wc, right_off);
+    else
+        column_offsets(wc, right_off);
+    if (TRANSPOSED)
+        column_offsets(wr, left_off);
+    else
+        row_offsets(wr, left_off);
 
     for (int64_t unit = unit_begin; unit < unit_end;) {
     const int tile = (int)(unit / steps);
@@ -317,7 +333,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     tile_origin(tile, tiles_r, tiles_k, phase_period, r0, k0);
     // operand positions of contraction step 0 (wave-uniform)
     const char *left_base = reinterpret_cast<const char *>(TRANSPOSED ? dy + r0 : dy + (int64_t)r0 * ld_dy);
-    const char *right_base = reinterpret_cast<const char *>(qhat + k0);
+    const char *right_base = reinterpret_cast<const char *>(RIGHT_ROWS ? qhat + (int64_t)k0 * ld_right : qhat + k0);
 
     v16f acc[4][4];
 #pragma unroll
@@ -344,11 +360,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     // read number n of k-step ks out of `stage`, in the order the matrix instructions want them
     auto load_frag = [&](auto nc, const uint8_t *stage, auto ksc) {
         constexpr int ks = decltype(ksc)::value;
-        constexpr ReadOp op = (TRANSPOSED ? kReadsTransposed : kReadsPlain)[decltype(nc)::value];
+        constexpr ReadOp op = (MODE == 1 ? kReadsTransposed : MODE == 0 ? kReadsPlain : kReadsRows)[decltype(nc)::value];
         if constexpr (op.half < 0) {
-            const v8bf v = *reinterpret_cast<const v8bf *>(stage + left_off[ks] + 2048 * op.idx);
-            lf[ks][op.idx][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
-            lf[ks][op.idx][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+            const uint32_t off = (op.left ? left_off[ks] : kOperandBytes + right_off[ks]) + 2048 * op.idx;
+            const v8bf v = *reinterpret_cast<const v8bf *>(stage + off);
+            if constexpr (op.left) {
+                lf[ks][op.idx][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+                lf[ks][op.idx][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+            } else {
+                rf[ks][op.idx][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+                rf[ks][op.idx][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+            }
         } else {
             const uint32_t off = (op.left ? left_off[op.idx] : kOperandBytes + right_off[op.idx]) +
                                  512 * (16 * ks + 4 * op.half);
@@ -360,7 +382,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
                 rf[ks][op.idx][op.half] = v;
         }
     };
-    constexpr int kReads = TRANSPOSED ? 16 : 12;
+    constexpr int kReads = MODE == 1 ? 16 : MODE == 0 ? 12 : 8;
 
     // Ring of STAGES stages: while step s is multiplied out of stage s % STAGES, the transfers of
     // steps s + 1 .. s + STAGES - 2 are in flight or done and, from the middle of the step on, those
@@ -561,20 +583,31 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
     const int levels = 1 << a.bits;
     const auto *dy = static_cast<const uint16_t *>(a.dy);
     auto *out = static_cast<uint16_t *>(a.out);
-    const int64_t out_rows = a.which == 0 ? a.M : a.N, contraction = a.which == 0 ? a.N : a.M;
-    if ((out_rows % GT) == 0 && (a.K % GT) == 0 && (contraction % GC) == 0 &&
-        out_rows * a.K < ((int64_t)1 << 31) && contraction * std::max(a.K, a.N) < ((int64_t)1 << 30)) {
-        const int tiles_r = (int)(out_rows / GT), tiles_k = (int)(a.K / GT);
+    // which = 0: out[M, K] = dy what;  1: out[N, K] = dy^T xhat;  2: out[M, N] = x what^T (weight-only)
+    const int64_t out_rows = a.which == 1 ? a.N : a.M, out_cols = a.which == 2 ? a.N : a.K;
+    const int64_t contraction = a.which == 0 ? a.N : a.which == 1 ? a.M : a.K;
+    const int64_t q_rows = a.which == 1 ? a.M : a.N;          // rows of the code-packed operand [q_rows, K]
+    const int64_t ld_left = a.which == 2 ? a.K : a.N;
+    const bool whole_tiles = (out_rows % GT) == 0 && (out_cols % GT) == 0 && (contraction % GC) == 0 &&
+                             out_rows * out_cols < ((int64_t)1 << 31) &&
+                             std::max(a.M, a.N) * std::max(a.K, a.N) < ((int64_t)1 << 30);
+    if (a.which == 2 && !whole_tiles)
+        return hipErrorInvalidValue;
+    if (whole_tiles) {
+        const int tiles_r = (int)(out_rows / GT), tiles_k = (int)(out_cols / GT);
         const int tiles = tiles_r * tiles_k, steps = (int)(contraction / GC);
         constexpr int kStages = 5;
         constexpr int kLds = kStages * kGStage;
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t err = hipFuncSetAttribute(
-                reinterpret_cast<const void *>(grad_gemm_tile_kernel<false, kStages>),
+                reinterpret_cast<const void *>(grad_gemm_tile_kernel<0, kStages>),
                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
             if (err == hipSuccess)
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(grad_gemm_tile_kernel<true, kStages>),
+                err = hipFuncSetAttribute(reinterpret_cast<const void *>(grad_gemm_tile_kernel<1, kStages>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+            if (err == hipSuccess)
+                err = hipFuncSetAttribute(reinterpret_cast<const void *>(grad_gemm_tile_kernel<2, kStages>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
             if (err != hipSuccess)
                 return err;
@@ -603,7 +636,7 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
                 phase_period = blocks;
         }
         // library-owned device memory: the expanded operand, then the partial tiles
-        const size_t expanded_bytes = ((size_t)contraction * a.K * 2 + 255) / 256 * 256;
+        const size_t expanded_bytes = ((size_t)q_rows * a.K * 2 + 255) / 256 * 256;
         const size_t partial_bytes = split ? (size_t)2 * blocks * kSlotQuads * sizeof(float4) : 0;
         char *memory = nullptr;
         err = library_memory(device, expanded_bytes + partial_bytes, &memory);
@@ -612,24 +645,29 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
         auto *qhat = reinterpret_cast<uint16_t *>(memory);
         auto *partial = split ? reinterpret_cast<float4 *>(memory + expanded_bytes) : nullptr;
 
-        const int64_t groups = contraction * a.K / 8;
+        const int64_t groups = q_rows * a.K / 8;
         hipLaunchKernelGGL(expand_codes_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream,
                            a.q_codes, a.q_scales, levels, a.cb, (int)a.K, groups, qhat);
         err = hipGetLastError();
         if (err != hipSuccess)
             return err;
+        const dim3 grid((unsigned)blocks), block(kGemmThreads);
         if (a.which == 0)
-            hipLaunchKernelGGL((grad_gemm_tile_kernel<false, kStages>), dim3((unsigned)blocks),
-                               dim3(kGemmThreads), kLds, stream, dy, a.N, qhat, (int)contraction, (int)a.K,
-                               tiles_r, tiles_k, per_block, phase_period, out, partial);
+            hipLaunchKernelGGL((grad_gemm_tile_kernel<0, kStages>), grid, block, kLds, stream, dy, ld_left, qhat,
+                               a.K, (int)contraction, (int)out_cols, tiles_r, tiles_k, per_block,
+                               phase_period, out, partial);
+        else if (a.which == 1)
+            hipLaunchKernelGGL((grad_gemm_tile_kernel<1, kStages>), grid, block, kLds, stream, dy, ld_left, qhat,
+                               a.K, (int)contraction, (int)out_cols, tiles_r, tiles_k, per_block,
+                               phase_period, out, partial);
         else
-            hipLaunchKernelGGL((grad_gemm_tile_kernel<true, kStages>), dim3((unsigned)blocks),
-                               dim3(kGemmThreads), kLds, stream, dy, a.N, qhat, (int)contraction, (int)a.K,
-                               tiles_r, tiles_k, per_block, phase_period, out, partial);
+            hipLaunchKernelGGL((grad_gemm_tile_kernel<2, kStages>), grid, block, kLds, stream, dy, ld_left, qhat,
+                               a.K, (int)contraction, (int)out_cols, tiles_r, tiles_k, per_block,
+                               phase_period, out, partial);
         err = hipGetLastError();
         if (err == hipSuccess && split) {
             hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles * 4)), dim3(256), 0, stream, partial,
-                               steps, per_block, phase_period, (int)a.K, tiles_r, tiles_k, out);
+                               steps, per_block, phase_period, (int)out_cols, tiles_r, tiles_k, out);
             err = hipGetLastError();
         }
         return err;

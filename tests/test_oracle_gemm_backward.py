@@ -106,3 +106,28 @@ def test_unquantised_unmasked_backward_is_the_true_gradient():
     dx = qo.trust_backward(dy @ wh, None, n)
     dw = qo.trust_backward(dy.T @ xh, None, n)
     assert np.allclose(dx, dy @ w, atol=1e-11) and np.allclose(dw, dy.T @ x, atol=1e-11)
+
+
+def test_weight_only_product_against_loops_and_the_other_matmuls():
+    """y = x what^T (Sec. 4.4): brute force on a tiny case; with unit scales it is the input-gradient
+    product of the transposed integer matrix; a column's scale multiplies that column only."""
+    rng = np.random.default_rng(7)
+    M, N, K = 5, 4, 6
+    x = rng.standard_normal((M, K))
+    u = (2 * rng.integers(-8, 8, size=(N, K)) + 1).astype(np.int32)
+    s = rng.random(N) + 0.5
+    y = qo.weight_only_gemm(x, u, s)
+    for m in range(M):
+        for n in range(N):
+            assert y[m, n] == pytest.approx(sum(x[m, k] * s[n] * u[n, k] for k in range(K)), rel=1e-13)
+    ones_n, ones_k = np.ones(N), np.ones(K)
+    assert np.allclose(qo.weight_only_gemm(x, u, ones_n), qo.grad_input(x, np.ascontiguousarray(u.T), ones_k),
+                       rtol=1e-13)
+    s2 = s.copy()
+    s2[2] *= 4.0
+    y2 = qo.weight_only_gemm(x, u, s2)
+    assert np.array_equal(y2[:, [0, 1, 3]], y[:, [0, 1, 3]]) and np.allclose(y2[:, 2], 4.0 * y[:, 2], rtol=1e-15)
+    # with both operands quantized it agrees with the integer path: (s_x u_x) what^T = s_x s_w acc
+    ux = (2 * rng.integers(-8, 8, size=(M, K)) + 1).astype(np.int32)
+    sx = rng.random(M) + 0.5
+    assert np.allclose(qo.weight_only_gemm(sx[:, None] * ux, u, s), qo.dequant(qo.gemm_odd(ux, u), sx, s), rtol=1e-13)
