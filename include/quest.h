@@ -144,6 +144,21 @@ quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_cod
                              const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,
                              void *out, void *stream);
 
+/*
+ * Weight-only forward product (Sec. 4.4 "Weight-only quantization": 16-bit activations against
+ * 1..4-bit weights):  y[M, N] = x[M, K] * what_h^T,  what_h[n, k] = bf16(s_w[n] * u_w[n, k]).
+ *   x        bf16 [M, K] row-major (the activations in the domain the weights were quantized in:
+ *            for Hadamard-domain weight codes, x_h = HT(x), which quest_trust_backward computes
+ *            when called without a mask)
+ *   w_codes  [N, K*cb/8], w_scales [N] from either quantizer entry point;  bits in {1,2,3,4}
+ *   y        out bf16 [M, N] row-major, fp32 accumulation on the bf16 matrix cores
+ * M and N multiples of 256, K a multiple of 64, M*N < 2^31 (QUEST_ERR_SHAPE otherwise).
+ * Uses the same library-owned device memory as quest_grad_gemm, with the same consequences.
+ */
+quest_status quest_weight_only_gemm(const void *x, const uint8_t *w_codes, const float *w_scales,
+                                    int32_t bits, int64_t M, int64_t N, int64_t K, void *y,
+                                    void *stream);
+
 /* Host: the built-in Gaussian-MSE-optimal clip alpha*(bits) (Sec. 3.1); 0 for unsupported bits. */
 float quest_alpha_star(int32_t bits);
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
 EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_lowbit_gemm", "quest_trust_backward",
-           "quest_grad_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
+           "quest_grad_gemm", "quest_weight_only_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
 
 _i64, _i32, _f32, _p = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 _lib = None
@@ -44,8 +44,9 @@ def load():
         lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p]
         lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
         lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
+        lib.quest_weight_only_gemm.argtypes = [_p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
         for name in ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_lowbit_gemm",
-                     "quest_trust_backward", "quest_grad_gemm"):
+                     "quest_trust_backward", "quest_grad_gemm", "quest_weight_only_gemm"):
             getattr(lib, name).restype = ctypes.c_int
         lib.quest_alpha_star.argtypes = [_i32]
         lib.quest_alpha_star.restype = _f32
@@ -139,3 +140,13 @@ def quest_grad_gemm(which: int, dy: torch.Tensor, q_codes: torch.Tensor, q_scale
     _check(load().quest_grad_gemm(which, _ptr(dy), _ptr(q_codes), _ptr(q_scales), bits, M, N, K,
                                   _ptr(out), _stream()),
            "quest_grad_gemm")
+
+
+def quest_weight_only_gemm(x: torch.Tensor, w_codes: torch.Tensor, w_scales: torch.Tensor, bits: int,
+                           *, y: torch.Tensor) -> None:
+    """y[M, N] (bf16) = x[M, K] (bf16) times the transposed weights given as packed codes [N, K*cb/8]."""
+    M, K = x.shape
+    N = w_codes.shape[0]
+    _check(load().quest_weight_only_gemm(_ptr(x), _ptr(w_codes), _ptr(w_scales), bits, M, N, K, _ptr(y),
+                                         _stream()),
+           "quest_weight_only_gemm")

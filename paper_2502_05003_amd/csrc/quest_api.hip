@@ -268,4 +268,35 @@ quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_cod
                : QUEST_ERR_LAUNCH;
 }
 
+quest_status quest_weight_only_gemm(const void *x, const uint8_t *w_codes, const float *w_scales,
+                                    int32_t bits, int64_t M, int64_t N, int64_t K, void *y,
+                                    void *stream)
+{
+    if (!x || !w_codes || !w_scales || !y)
+        return QUEST_ERR_NULL;
+    if (bits < 1 || bits > 4)
+        return QUEST_ERR_BITS;
+    if (M < 0 || N < 0 || K < 0 || (M & 255) || (N & 255) || (K & 63) || M > (int64_t(1) << 22) ||
+        N > (int64_t(1) << 22) || K > (int64_t(1) << 22) || M * N >= (int64_t(1) << 31) ||
+        (M > N ? M : N) * (K > N ? K : N) >= (int64_t(1) << 30))
+        return QUEST_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w_codes) || !aligned16(y))
+        return QUEST_ERR_ALIGN;
+
+    quest::GradGemmArgs args;
+    args.which = 2;
+    args.dy = x;
+    args.q_codes = w_codes;
+    args.q_scales = w_scales;
+    args.bits = bits;
+    args.cb = container_bits(bits);
+    args.M = M;
+    args.N = N;
+    args.K = K;
+    args.out = y;
+    return quest::launch_grad_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUEST_OK
+               : QUEST_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -426,6 +426,39 @@ def test_down_projection_full_size():
     assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
 
 
+@pytest.mark.parametrize("M,N,K,bits", [(256, 256, 64, 4), (512, 256, 2048, 4), (256, 768, 320, 2),
+                                        (768, 512, 1024, 1), (256, 256, 5632, 3),
+                                        (4096, 2304, 128, 4)])   # 144 tiles: split over the CUs
+def test_weight_only_gemm_matches_oracle(M, N, K, bits):
+    """Sec. 4.4: bf16 activations in the Hadamard domain (the transform alone is the trust
+    backward without a mask) against 1..4-bit weights expanded on the fly."""
+    n = 64
+    x = synth.outlier_activations(M, K, 0.01, 20.0, seed=M + K, dtype="bf16")
+    w = synth.gaussian(N, K, 0.02, 12, "bf16")
+    gw = gpu_quantize(w, n, bits, want_xh=False, want_mask=False)
+    xh = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
+    q.quest_trust_backward(to_device(x), None, n, out=xh)
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    q.quest_weight_only_gemm(xh, gw["dev"]["codes"], gw["dev"]["scales"], bits, y=y)
+    torch.cuda.synchronize()
+    xh_host = to_host_f64(xh)
+    ref_xh = qo.hadamard(qo.widen(x), n)
+    scale = np.sqrt(np.mean(ref_xh * ref_xh, axis=1, keepdims=True))
+    assert np.all(np.abs(xh_host - ref_xh) <= BF16_HALF_ULP * np.abs(ref_xh) + 1e-5 * scale)
+    u = qo.unpack_odd(gw["codes"], K, bits)
+    ref = qo.weight_only_gemm(xh_host, u, gw["scales"].astype(np.float64))
+    w16 = qo.widen(synth.to_bf16_bits(gw["scales"][:, None] * u.astype(np.float32)))   # the 16-bit operand
+    mirror = xh_host @ w16.T
+    spread = np.sqrt((xh_host ** 2) @ (w16.T ** 2))
+    got = to_host_f64(y)
+    assert np.all(np.abs(got - mirror) <= BF16_HALF_ULP * 1.001 * np.abs(mirror) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+    assert np.linalg.norm(got - ref) <= 4e-3 * np.linalg.norm(ref)
+    # and the product approximates x w^T (the transform is orthogonal)
+    exact = qo.widen(x) @ qo.widen(w).T
+    print(f"b={bits}: relative error against x w^T {np.linalg.norm(got - exact) / np.linalg.norm(exact):.3f}")
+
+
 def test_full_linear_forward_backward_small():
     """Algorithm 1 + Algorithm 2 end to end through the C ABI on a small layer."""
     M, N, K, bits, n = 128, 192, 512, 4, 512
