@@ -67,3 +67,38 @@ def untrusted_fraction(alpha: float, bits: int, outer_trust: float = 1.0) -> flo
     levels = 1 << bits
     edge = alpha * (1.0 + outer_trust / (levels - 1))
     return 2.0 * float(ndtr(-edge))
+
+
+# ------------------------------------------------------------------ FP4 grid (Sec. 4.4, "The FP4 Format")
+
+# Magnitudes of the 4-bit floating-point format with 2 exponent and 1 mantissa bit (E2M1),
+# in code order; the grid "scaled to fit the same [-1, 1] interval" is FP4_MAGNITUDES / 6.
+FP4_MAGNITUDES = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)
+
+
+def fp4_grid() -> list[float]:
+    """The 15 distinct points of the scaled grid, ascending."""
+    pos = [m / 6.0 for m in FP4_MAGNITUDES]
+    return [-p for p in reversed(pos[1:])] + pos
+
+
+def gaussian_mse_fp4(alpha: float) -> float:
+    """E (xi - alpha * round_FP4(clip(xi, alpha) / alpha))^2 for xi ~ N(0, 1): each grid point
+    owns the interval between the midpoints to its neighbours, the outer ones run to infinity."""
+    grid = [alpha * g for g in fp4_grid()]
+    total = 0.0
+    for i, q in enumerate(grid):
+        lo = -math.inf if i == 0 else 0.5 * (grid[i - 1] + q)
+        hi = math.inf if i == len(grid) - 1 else 0.5 * (q + grid[i + 1])
+        total += _cell_error(lo, hi, q)
+    return total
+
+
+def alpha_star_fp4() -> float:
+    """argmin over alpha of gaussian_mse_fp4: the paper's alpha*_FP4 ("replacing the rounding
+    operation in the original definition")."""
+    result = minimize_scalar(gaussian_mse_fp4, bounds=(0.05, 8.0), method="bounded", options={"xatol": 1e-10})
+    return float(result.x)
+
+
+FP4_TRUST = 1.0 / 6.0   # largest half-interval of the scaled grid: (1 - 2/3) / 2, in units of alpha

@@ -263,6 +263,84 @@ void qo_project_absmax(const double *xh, int64_t rows, int64_t cols, int bits, d
     }
 }
 
+/*
+ * FP4 variant of the projection (Sec. 4.4, "The FP4 Format"): the rounding of Eq. 1 is replaced
+ * by rounding to the grid of the 4-bit floating-point format E2M1, magnitudes
+ * {0, 0.5, 1, 1.5, 2, 3, 4, 6}, scaled to fit [-1, 1]:
+ *   t     = 6 x_n / alpha, clipped to [-6, 6]
+ *   m     = nearest E2M1 magnitude to |t| (a tie goes to the magnitude with the even code, the
+ *           format's own round-to-nearest-even), code = sign bit (8, set iff x_h < 0) + index of m
+ *   xhat  = sign * m * alpha * rms / 6,  scale = alpha * rms / 6
+ *   M     = 1 iff |xhat - x_h| <= T rms, T = alpha / 6 (the largest half-interval of the grid)
+ * The paper states the variant in two sentences; ties, the sign of a negative value that rounds to
+ * zero (kept, as the format does) and the per-row scale are this build's reading of them.
+ * Outputs (any may be NULL): rms, scale [rows]; code [rows*cols] (0..15); xhat, trust [rows*cols].
+ */
+static const double kFp4Magnitude[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+void qo_project_fp4(const double *xh, int64_t rows, int64_t cols, double alpha, double *rms_out,
+                    double *scale_out, uint8_t *code_out, double *xhat_out, uint8_t *trust_out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *row = xh + r * cols;
+        double sumsq = 0.0;
+        for (int64_t j = 0; j < cols; ++j)
+            sumsq += row[j] * row[j];
+        const double rms = sqrt(sumsq / (double)cols);
+        if (rms_out)
+            rms_out[r] = rms;
+        if (scale_out)
+            scale_out[r] = alpha * rms / 6.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            int code = 0;
+            double xhat = 0.0;
+            int trusted = 1;
+            if (rms > 0.0) {
+                const double xn = row[j] / rms;
+                double t = fabs(6.0 * xn / alpha);
+                if (t > 6.0)
+                    t = 6.0;
+                int best = 0;
+                for (int i = 1; i < 8; ++i) {
+                    const double mid = 0.5 * (kFp4Magnitude[i - 1] + kFp4Magnitude[i]);
+                    /* above the midpoint, or on it when the upper code is the even one */
+                    if (t > mid || (t == mid && (i & 1) == 0))
+                        best = i;
+                }
+                code = best + (row[j] < 0.0 ? 8 : 0);
+                xhat = (row[j] < 0.0 ? -1.0 : 1.0) * (rms * alpha * kFp4Magnitude[best] / 6.0);
+                trusted = (fabs(xhat - row[j]) <= rms * alpha * 1.0 / 6.0) ? 1 : 0;
+            }
+            if (code_out)
+                code_out[r * cols + j] = (uint8_t)code;
+            if (xhat_out)
+                xhat_out[r * cols + j] = xhat;
+            if (trust_out)
+                trust_out[r * cols + j] = (uint8_t)trusted;
+        }
+    }
+}
+
+/* Two E2M1 codes per byte, element 2i in the low nibble (the 4-bit container of the integer codes). */
+void qo_pack_fp4(const uint8_t *code, int64_t rows, int64_t cols, uint8_t *packed)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t j = 0; j < cols; j += 2)
+            packed[r * (cols / 2) + j / 2] =
+                (uint8_t)((code[r * cols + j] & 15) | ((code[r * cols + j + 1] & 15) << 4));
+}
+
+/* Signed E2M1 values (multiples of 0.5, |v| <= 6) of packed codes. */
+void qo_unpack_fp4(const uint8_t *packed, int64_t rows, int64_t cols, double *value)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t j = 0; j < cols; ++j) {
+            const int c = (packed[r * (cols / 2) + j / 2] >> (4 * (j & 1))) & 15;
+            value[r * cols + j] = ((c & 8) ? -1.0 : 1.0) * kFp4Magnitude[c & 7];
+        }
+}
+
 /* ------------------------------------------------------------------ storage formats */
 
 /* Container width in bits for a b-bit code: 3-bit codes sit in a nibble. */

@@ -56,6 +56,9 @@ def _load():
         lib.qo_row_rms.argtypes = [_p, _c_i64, _c_i64, _p]
         lib.qo_project.argtypes = [_p, _c_i64, _c_i64, _c_int, _c_dbl, _c_dbl, _p, _p, _p, _p, _p]
         lib.qo_project_absmax.argtypes = [_p, _c_i64, _c_i64, _c_int, _p, _p, _p, _p, _p]
+        lib.qo_project_fp4.argtypes = [_p, _c_i64, _c_i64, _c_dbl, _p, _p, _p, _p, _p]
+        lib.qo_pack_fp4.argtypes = [_p, _c_i64, _c_i64, _p]
+        lib.qo_unpack_fp4.argtypes = [_p, _c_i64, _c_i64, _p]
         lib.qo_container_bits.argtypes = [_c_int]
         lib.qo_container_bits.restype = _c_int
         lib.qo_pack_codes.argtypes = [_p, _c_i64, _c_i64, _c_int, _p]
@@ -191,6 +194,60 @@ def project_absmax(xh: np.ndarray, bits: int) -> Projection:
     mask = np.empty((rows, cols // 8), dtype=np.uint8)
     lib.qo_pack_mask(_ptr(trust), rows, cols, _ptr(mask))
     return Projection(xh, amax, scale, k, xhat, trust, codes, mask, 1.0, bits)
+
+
+@dataclass
+class Fp4Projection:
+    """What the FP4 variant (Sec. 4.4) derives from one operand."""
+    xh: np.ndarray        # [rows, cols] double
+    rms: np.ndarray       # [rows]
+    scale: np.ndarray     # [rows]  alpha rms / 6: xhat = scale * value
+    code: np.ndarray      # [rows, cols] uint8 E2M1 code, bit 3 = sign
+    value: np.ndarray     # [rows, cols] double signed E2M1 value of the code
+    xhat: np.ndarray      # [rows, cols] double
+    trust: np.ndarray     # [rows, cols] uint8
+    codes: np.ndarray     # [rows, cols/2] uint8, two codes per byte, low nibble first
+    mask: np.ndarray      # [rows, cols/8] uint8 bitmap
+    alpha: float
+
+
+def unpack_fp4(codes: np.ndarray, cols: int) -> np.ndarray:
+    codes = _c(codes, np.uint8)
+    rows = codes.shape[0]
+    value = np.empty((rows, cols), dtype=np.float64)
+    _load().qo_unpack_fp4(_ptr(codes), rows, cols, _ptr(value))
+    return value
+
+
+def project_fp4(xh: np.ndarray, alpha: float | None = None) -> Fp4Projection:
+    """RMS-normalise, clip at alpha (default alpha*_FP4), round to the scaled E2M1 grid, trust mask."""
+    xh = _c(xh, np.float64)
+    rows, cols = xh.shape
+    if alpha is None:
+        alpha = _alpha.alpha_star_fp4()
+    rms = np.empty(rows, dtype=np.float64)
+    scale = np.empty(rows, dtype=np.float64)
+    code = np.empty((rows, cols), dtype=np.uint8)
+    xhat = np.empty((rows, cols), dtype=np.float64)
+    trust = np.empty((rows, cols), dtype=np.uint8)
+    lib = _load()
+    lib.qo_project_fp4(_ptr(xh), rows, cols, float(alpha), _ptr(rms), _ptr(scale), _ptr(code), _ptr(xhat),
+                       _ptr(trust))
+    codes = np.empty((rows, cols // 2), dtype=np.uint8)
+    lib.qo_pack_fp4(_ptr(code), rows, cols, _ptr(codes))
+    mask = np.empty((rows, cols // 8), dtype=np.uint8)
+    lib.qo_pack_mask(_ptr(trust), rows, cols, _ptr(mask))
+    return Fp4Projection(xh, rms, scale, code, unpack_fp4(codes, cols), xhat, trust, codes, mask, float(alpha))
+
+
+def hadamard_quantize_fp4(x: np.ndarray, n: int, alpha: float | None = None, dense: bool = False) -> Fp4Projection:
+    """x_h = HT(x), then the FP4 projection."""
+    return project_fp4(hadamard(widen(x), n, dense=dense), alpha)
+
+
+def gemm_fp4(va: np.ndarray, vb: np.ndarray) -> np.ndarray:
+    """acc[m, n] = sum_k v_a[m, k] v_b[n, k] of signed E2M1 values: multiples of 1/4, exact in double."""
+    return _c(va, np.float64) @ _c(vb, np.float64).T
 
 
 def hadamard_quantize(x: np.ndarray, n: int, bits: int, alpha: float | None = None,

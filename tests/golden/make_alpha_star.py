@@ -16,3 +16,7 @@ with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "alpha_star.t
         alpha = a.alpha_star(bits)
         f.write(f"{bits} {alpha:.7f} {a.gaussian_mse(alpha, bits):.9e} "
                 f"{a.untrusted_fraction(alpha, bits):.6e}\n")
+    alpha = a.alpha_star_fp4()
+    f.write("# FP4 grid (Sec. 4.4): alpha_star_fp4 gaussian_mse untrusted_fraction at T = alpha / 6\n")
+    f.write(f"fp4 {alpha:.7f} {a.gaussian_mse_fp4(alpha):.9e} "
+            f"{2.0 * float(a.ndtr(-alpha * (1.0 + a.FP4_TRUST))):.6e}\n")

@@ -73,6 +73,10 @@ def test_stored_table_is_what_the_oracle_derives(alpha_table):
     import os
     path = os.path.join(os.path.dirname(__file__), "golden", "alpha_star.txt")
     rows = [line.split() for line in open(path) if line.strip() and not line.startswith("#")]
+    fp4 = [r for r in rows if r[0] == "fp4"]
+    rows = [r for r in rows if r[0] != "fp4"]
+    assert len(fp4) == 1 and float(fp4[0][1]) == pytest.approx(a.alpha_star_fp4(), abs=2e-6)
+    assert float(fp4[0][2]) == pytest.approx(a.gaussian_mse_fp4(a.alpha_star_fp4()), rel=1e-6)
     assert [int(r[0]) for r in rows] == [1, 2, 3, 4, 8]
     for r in rows:
         assert float(r[1]) == pytest.approx(alpha_table[int(r[0])], abs=2e-6)
