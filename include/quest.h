@@ -95,6 +95,25 @@ quest_status quest_hadamard_quantize_absmax(const void *x, quest_dtype dtype, in
                                             float *xh_out, void *stream);
 
 /*
+ * FP4 variant of the quantizer (Sec. 4.4 "The FP4 Format"): the rounding of Eq. 1 is replaced by
+ * rounding to the value set of the 4-bit floating-point format E2M1, {0, .5, 1, 1.5, 2, 3, 4, 6}
+ * with a sign, scaled so that 6 sits on the clip alpha * rms:
+ *   t = 6 x_h / (alpha rms) clipped to [-6, 6];  code = E2M1(t), nearest value, ties to the even
+ *   code, bit 3 = sign of x_h (kept when the magnitude rounds to zero);  scales[r] = alpha rms / 6,
+ *   so that xhat_h = scales[r] * value(code);  mask bit = 1 iff |x_h| <= alpha (1 + 1/6) rms
+ *   (T = alpha / 6 is the largest half-interval of the grid).
+ * alpha <= 0 selects the built-in alpha*_FP4.  Codes are packed two per byte, low nibble first:
+ * the operand layout of the FP4 matrix instructions.  A zero row gives code 0, scale 0, mask 1.
+ * Other arguments, layouts, limits and errors as quest_hadamard_quantize.
+ */
+quest_status quest_hadamard_quantize_fp4(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
+                                         int64_t ld, int32_t had_block, float alpha, uint8_t *codes,
+                                         float *scales, uint8_t *mask, float *xh_out, void *stream);
+
+/* Host: the built-in Gaussian-MSE-optimal clip for the scaled E2M1 grid (Sec. 4.4). */
+float quest_alpha_star_fp4(void);
+
+/*
  * Algorithm 1, the matmul y = xhat_h what_h^T, run on the integer codes (Sec. 5 "Kernel
  * Overview", stage 3): acc[m, n] = sum_k u_a[m, k] u_b[n, k] exactly in int32, then
  * y[m, n] = bf16(float(acc[m, n]) * a_scales[m] * b_scales[n]).

@@ -16,7 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
-EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_lowbit_gemm", "quest_trust_backward",
+EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
+           "quest_lowbit_gemm", "quest_trust_backward",
            "quest_grad_gemm", "quest_weight_only_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
 
 _i64, _i32, _f32, _p = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
@@ -41,6 +42,10 @@ def load():
                                                 _p, _p, _p, _p, _p]
         lib.quest_hadamard_quantize_absmax.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _i32,
                                                        _p, _p, _p, _p, _p]
+        lib.quest_hadamard_quantize_fp4.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _f32, _p, _p, _p, _p, _p]
+        lib.quest_hadamard_quantize_fp4.restype = ctypes.c_int
+        lib.quest_alpha_star_fp4.argtypes = []
+        lib.quest_alpha_star_fp4.restype = _f32
         lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p]
         lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
         lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
@@ -112,6 +117,21 @@ def quest_hadamard_quantize_absmax(x: torch.Tensor, had_block: int, bits: int, *
                                                  had_block, bits, _ptr(codes), _ptr(scales), _ptr(mask),
                                                  _ptr(xh_out), _stream()),
            "quest_hadamard_quantize_absmax")
+
+
+def quest_hadamard_quantize_fp4(x: torch.Tensor, had_block: int, alpha: float = 0.0, *, codes: torch.Tensor,
+                                scales: torch.Tensor, mask: torch.Tensor | None = None,
+                                xh_out: torch.Tensor | None = None) -> None:
+    """As quest_hadamard_quantize, rounding to the scaled E2M1 grid; codes are E2M1 nibbles."""
+    rows, cols = x.shape
+    _check(load().quest_hadamard_quantize_fp4(_ptr(x), _dtype_code(x), rows, cols, x.stride(0), had_block,
+                                              alpha, _ptr(codes), _ptr(scales), _ptr(mask), _ptr(xh_out),
+                                              _stream()),
+           "quest_hadamard_quantize_fp4")
+
+
+def quest_alpha_star_fp4() -> float:
+    return float(load().quest_alpha_star_fp4())
 
 
 def quest_lowbit_gemm(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: torch.Tensor,

@@ -43,6 +43,29 @@ __device__ __forceinline__ RowQuant row_quant_absmax(float amax, int levels)
     return q;
 }
 
+// FP4 variant (Sec. 4.4): the grid is the E2M1 value set {0, .5, 1, 1.5, 2, 3, 4, 6} scaled so that 6
+// sits on the clip; inv_step = 6 / (alpha rms) maps x_h to E2M1 units, scale = alpha rms / 6.
+__device__ __forceinline__ RowQuant row_quant_fp4(float sumsq, int cols, float alpha, float trust_edge)
+{
+    RowQuant q;
+    const float rms = __fsqrt_rn(__fdiv_rn(sumsq, (float)cols));
+    const float clip = __fmul_rn(alpha, rms);
+    q.zero = !(rms > 0.0f);
+    q.inv_step = q.zero ? 0.0f : __fdiv_rn(6.0f, clip);
+    q.trust_abs = __fmul_rn(trust_edge, rms);
+    q.scale = __fdiv_rn(clip, 6.0f);
+    return q;
+}
+
+// E2M1 code of one element: nearest magnitude (a tie goes to the even code), sign in bit 3.
+__device__ __forceinline__ uint32_t quantize_fp4(float xh, const RowQuant &q)
+{
+    const float t = fminf(__fmul_rn(fabsf(xh), q.inv_step), 6.0f);
+    const uint32_t index = (t > 0.25f) + (t >= 0.75f) + (t > 1.25f) + (t >= 1.75f) + (t > 2.5f) +
+                           (t >= 3.5f) + (t > 5.0f);
+    return index | (xh < 0.0f ? 8u : 0u);
+}
+
 // Code c = clamp(floor(x_h * inv_step), -L/2, L/2 - 1) + L/2 for one element.
 __device__ __forceinline__ uint32_t quantize_one(float xh, const RowQuant &q, int levels)
 {
@@ -61,7 +84,7 @@ __device__ __forceinline__ uint32_t quantize_one(float xh, const RowQuant &q, in
 template <typename In>
 __global__ __launch_bounds__(kGenericThreads) void hq_generic_kernel(
     const In *__restrict__ x, int64_t rows, int cols, int64_t ld, int log2n, int bits, int cb,
-    float alpha, float trust_edge, bool absmax, uint8_t *__restrict__ codes,
+    float alpha, float trust_edge, int mode, uint8_t *__restrict__ codes,
     float *__restrict__ scales, uint8_t *__restrict__ mask, float *__restrict__ xh_out)
 {
     extern __shared__ float lds[];
@@ -113,8 +136,9 @@ __global__ __launch_bounds__(kGenericThreads) void hq_generic_kernel(
             total += partial[w];
             total_max = fmaxf(total_max, partial_max[w]);
         }
-        const RowQuant q = absmax ? row_quant_absmax(total_max, levels)
-                                  : row_quant(total, cols, levels, alpha, trust_edge);
+        const RowQuant q = mode == kQuantAbsMax ? row_quant_absmax(total_max, levels)
+                           : mode == kQuantFp4  ? row_quant_fp4(total, cols, alpha, trust_edge)
+                                                : row_quant(total, cols, levels, alpha, trust_edge);
         if (threadIdx.x == 0)
             scales[r] = q.scale;
 
@@ -128,7 +152,9 @@ __global__ __launch_bounds__(kGenericThreads) void hq_generic_kernel(
             uint32_t trusted = 0;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const uint32_t c = q.zero ? (uint32_t)(levels >> 1) : quantize_one(v[i], q, levels);
+                const uint32_t c = mode == kQuantFp4 ? (q.zero ? 0u : quantize_fp4(v[i], q))
+                                   : q.zero         ? (uint32_t)(levels >> 1)
+                                                    : quantize_one(v[i], q, levels);
                 packed |= (uint64_t)c << (i * cb);
                 trusted |= ((q.zero || fabsf(v[i]) <= q.trust_abs) ? 1u : 0u) << i;
             }
@@ -155,7 +181,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
 {
     if (a.rows == 0)
         return hipSuccess;
-    if (!a.absmax && launch_hadamard_quantize_mfma(a, stream))
+    if (a.mode == kQuantRms && launch_hadamard_quantize_mfma(a, stream))
         return hipGetLastError();
     const int cols = (int)a.cols;
     const size_t lds_bytes = (size_t)(cols + (cols >> 5) + 1) * sizeof(float);
@@ -172,7 +198,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
             return err;
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream,
                            static_cast<const uint16_t *>(a.x), a.rows, cols, a.ld, a.log2n, a.bits,
-                           a.cb, a.alpha, a.trust_edge, a.absmax, a.codes, a.scales, a.mask, a.xh_out);
+                           a.cb, a.alpha, a.trust_edge, a.mode, a.codes, a.scales, a.mask, a.xh_out);
     } else {
         auto kernel = hq_generic_kernel<float>;
         if (lds_bytes > 48 * 1024)
@@ -182,7 +208,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
             return err;
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream,
                            static_cast<const float *>(a.x), a.rows, cols, a.ld, a.log2n, a.bits,
-                           a.cb, a.alpha, a.trust_edge, a.absmax, a.codes, a.scales, a.mask, a.xh_out);
+                           a.cb, a.alpha, a.trust_edge, a.mode, a.codes, a.scales, a.mask, a.xh_out);
     }
     return hipGetLastError();
 }

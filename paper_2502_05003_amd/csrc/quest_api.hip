@@ -15,6 +15,9 @@ constexpr double kAlphaStar2 = 1.4935300066;
 constexpr double kAlphaStar3 = 2.0510680577;
 constexpr double kAlphaStar4 = 2.5140046071;
 constexpr double kAlphaStar8 = 3.9221998115;
+// Same definition with the rounding to the E2M1 grid scaled to [-1, 1] (Sec. 4.4 "The FP4 Format"):
+// ternary search on a piecewise Simpson integral of the error; the minimum is flat to 1e-7.
+constexpr double kAlphaStarFp4 = 2.9224752;
 
 double alpha_star(int bits)
 {
@@ -101,7 +104,7 @@ namespace {
 
 // Shared by the two quantizer entry points; absmax ignores alpha and outer_trust.
 quest_status quantize_entry(const void *x, quest_dtype dtype, int64_t rows, int64_t cols, int64_t ld,
-                            int32_t had_block, int32_t bits, float alpha, float outer_trust, bool absmax,
+                            int32_t had_block, int32_t bits, float alpha, float outer_trust, int mode,
                             uint8_t *codes, float *scales, uint8_t *mask, float *xh_out, void *stream)
 {
     if (!x || !codes || !scales)
@@ -126,8 +129,11 @@ quest_status quantize_entry(const void *x, quest_dtype dtype, int64_t rows, int6
         return QUEST_ERR_ARG;
 
     const int levels = 1 << bits;
-    const double a = alpha > 0.0f ? (double)alpha : alpha_star(bits);
+    const double a = alpha > 0.0f ? (double)alpha : mode == quest::kQuantFp4 ? kAlphaStarFp4 : alpha_star(bits);
     const double ot = outer_trust < 0.0f ? 1.0 : (double)outer_trust;
+    // trusted iff |x_h| <= edge * rms: the clip plus one trust width T (times outer_trust);
+    // T = alpha / (L - 1) on the Eq. 1 grid, alpha / 6 (largest half-interval) on the FP4 grid
+    const double width = mode == quest::kQuantFp4 ? 1.0 / 6.0 : 1.0 / (double)(levels - 1);
 
     quest::QuantizeArgs args;
     args.x = x;
@@ -139,12 +145,12 @@ quest_status quantize_entry(const void *x, quest_dtype dtype, int64_t rows, int6
     args.bits = bits;
     args.cb = cb;
     args.alpha = (float)a;
-    args.trust_edge = (float)(a * (1.0 + ot / (double)(levels - 1)));
+    args.trust_edge = (float)(a * (1.0 + ot * width));
     args.codes = codes;
     args.scales = scales;
     args.mask = mask;
     args.xh_out = xh_out;
-    args.absmax = absmax;
+    args.mode = mode;
     return quest::launch_hadamard_quantize(args, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUEST_OK
                : QUEST_ERR_LAUNCH;
@@ -157,7 +163,7 @@ quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t r
                                      float outer_trust, uint8_t *codes, float *scales,
                                      uint8_t *mask, float *xh_out, void *stream)
 {
-    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, alpha, outer_trust, false, codes,
+    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, alpha, outer_trust, quest::kQuantRms, codes,
                           scales, mask, xh_out, stream);
 }
 
@@ -166,8 +172,21 @@ quest_status quest_hadamard_quantize_absmax(const void *x, quest_dtype dtype, in
                                             uint8_t *codes, float *scales, uint8_t *mask,
                                             float *xh_out, void *stream)
 {
-    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, 0.0f, -1.0f, true, codes, scales,
-                          mask, xh_out, stream);
+    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, 0.0f, -1.0f, quest::kQuantAbsMax, codes,
+                          scales, mask, xh_out, stream);
+}
+
+quest_status quest_hadamard_quantize_fp4(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
+                                         int64_t ld, int32_t had_block, float alpha, uint8_t *codes,
+                                         float *scales, uint8_t *mask, float *xh_out, void *stream)
+{
+    return quantize_entry(x, dtype, rows, cols, ld, had_block, 4, alpha, -1.0f, quest::kQuantFp4, codes,
+                          scales, mask, xh_out, stream);
+}
+
+float quest_alpha_star_fp4(void)
+{
+    return (float)kAlphaStarFp4;
 }
 
 quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,

@@ -9,6 +9,8 @@
 
 namespace quest {
 
+enum { kQuantRms = 0, kQuantAbsMax = 1, kQuantFp4 = 2 };
+
 struct QuantizeArgs {
     const void *x;
     quest_dtype dtype;
@@ -22,7 +24,8 @@ struct QuantizeArgs {
     float *scales;
     uint8_t *mask;     // may be null
     float *xh_out;     // may be null
-    bool absmax;       // clip at the row's largest |x_h| instead of alpha * rms (alpha, trust_edge unused)
+    int mode;          // kQuantRms: Eq. 1 grid, clip alpha * rms;  kQuantAbsMax: Eq. 1 grid, clip = largest
+                       // |x_h| of the row (alpha, trust_edge unused);  kQuantFp4: E2M1 grid, clip alpha * rms
 };
 
 hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream);

@@ -24,7 +24,7 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
 
 def gpu_quantize(x_host: np.ndarray, had_block: int, bits: int, alpha: float = 0.0,
                  outer_trust: float = -1.0, want_xh: bool = True, want_mask: bool = True, ld=None,
-                 absmax: bool = False):
+                 absmax: bool = False, fp4: bool = False):
     """Run quest_hadamard_quantize on a host array; returns host arrays."""
     rows, cols = x_host.shape
     cb = q.quest_container_bits(bits)
@@ -38,7 +38,9 @@ def gpu_quantize(x_host: np.ndarray, had_block: int, bits: int, alpha: float = 0
     scales = torch.full((rows,), -1.0, dtype=torch.float32, device=DEV)
     mask = torch.full((rows, cols // 8), 0x55, dtype=torch.uint8, device=DEV) if want_mask else None
     xh = torch.full((rows, cols), float("nan"), dtype=torch.float32, device=DEV) if want_xh else None
-    if absmax:
+    if fp4:
+        q.quest_hadamard_quantize_fp4(x, had_block, alpha, codes=codes, scales=scales, mask=mask, xh_out=xh)
+    elif absmax:
         q.quest_hadamard_quantize_absmax(x, had_block, bits, codes=codes, scales=scales, mask=mask, xh_out=xh)
     else:
         q.quest_hadamard_quantize(x, had_block, bits, alpha, outer_trust, codes=codes, scales=scales,
@@ -90,6 +92,39 @@ def compare_quantizer(got: dict, ref: qo.Projection, cols: int, bits: int, outer
             edge = ref.alpha * (1.0 + outer_trust / (levels - 1))
             assert np.all(np.abs(np.abs(xn[mdiff]) - edge) <= 1e-6 * edge), "mask differs away from the edge"
         assert n_mask < 1e-5 * mdiff.size + 1, f"{n_mask} mask bits differ"
+    return n_code, n_mask
+
+
+def compare_quantizer_fp4(got: dict, ref, cols: int):
+    """Parity bar for the FP4 variant: as compare_quantizer, the rounding boundaries being the
+    midpoints between neighbouring E2M1 magnitudes (in units of alpha rms / 6) and zero (the sign bit)."""
+    rms = ref.rms[:, None]
+    safe = np.where(rms > 0, rms, 1.0)
+    if got["xh"] is not None:
+        bound = 1e-5 * np.maximum(np.abs(ref.xh), rms) + 1e-30
+        assert np.all(np.abs(got["xh"].astype(np.float64) - ref.xh) <= bound), "Hadamard outputs differ"
+    assert np.allclose(got["scales"].astype(np.float64), ref.scale, rtol=2e-6, atol=0), "scales differ"
+    v_got = qo.unpack_fp4(got["codes"], cols)
+    diff = (v_got != ref.value) | (np.signbit(v_got) != np.signbit(ref.value))
+    n_code = int(diff.sum())
+    if n_code:
+        t = np.abs(6.0 * ref.xh / safe / ref.alpha)[diff]
+        mids = np.array([0.0, 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+        near = np.min(np.abs(t[:, None] - mids[None, :]), axis=1) <= 1e-6 * np.maximum(t, 1.0)
+        assert np.all(near), "a code differs away from any rounding boundary"
+        mag = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+        step = np.abs(np.searchsorted(mag, np.abs(v_got[diff])) - np.searchsorted(mag, np.abs(ref.value[diff])))
+        assert np.all(step <= 1), "a code differs by more than one level"
+    assert n_code < 1e-5 * diff.size + 1, f"{n_code} codes differ"
+    n_mask = 0
+    if got["mask"] is not None:
+        mdiff = qo.unpack_mask(got["mask"], cols) != ref.trust
+        n_mask = int(mdiff.sum())
+        if n_mask:
+            edge = ref.alpha * (1.0 + 1.0 / 6.0)
+            xn = ref.xh / safe
+            assert np.all(np.abs(np.abs(xn[mdiff]) - edge) <= 1e-6 * edge), "mask differs away from the edge"
+        assert n_mask < 1e-5 * mdiff.size + 1
     return n_code, n_mask
 
 

@@ -9,8 +9,8 @@ from oracle import quest_oracle as qo
 from paper_2502_05003_amd import binding as q
 from paper_2502_05003_amd import synth
 
-from gpu_util import (BF16_HALF_ULP, DEV, check_gemm_output, compare_quantizer, gpu_quantize, to_device,
-                      to_host_f64)
+from gpu_util import (BF16_HALF_ULP, DEV, check_gemm_output, compare_quantizer, compare_quantizer_fp4, gpu_quantize,
+                      to_device, to_host_f64)
 
 pytestmark = pytest.mark.gpu
 
@@ -101,6 +101,21 @@ def test_transform_and_gaussian_clip_each_reduce_the_error():
     print({f"block {n}, {'absmax' if a else 'rms clip'}": round(v, 4) for (n, a), v in err.items()})
     assert err[(2048, False)] < err[(2048, True)] < err[(1, True)]
     assert err[(2048, False)] < err[(1, False)]
+
+
+FP4_CASES = [(37, 1024, 128, "bf16", 0.0), (130, 2048, 2048, "bf16", 0.0), (70, 5632, 512, "bf16", 0.0),
+             (33, 2048, 1, "bf16", 2.0), (19, 512, 64, "f32", 0.0), (4100, 256, 256, "bf16", 3.5)]
+
+
+@pytest.mark.parametrize("rows,cols,n,dtype,alpha", FP4_CASES)
+def test_fp4_quantizer_matches_oracle(rows, cols, n, dtype, alpha):
+    """The FP4 variant of the projection (Sec. 4.4): E2M1 codes, scale alpha rms / 6, trust mask."""
+    x = synth.outlier_activations(rows, cols, 0.01, 20.0, seed=rows + cols, dtype=dtype)
+    x[2] = 0
+    got = gpu_quantize(x, n, 4, alpha=alpha, fp4=True)
+    ref = qo.hadamard_quantize_fp4(x, n, alpha=(alpha if alpha > 0 else None), dense=(1 < n <= 512))
+    compare_quantizer_fp4(got, ref, cols)
+    assert got["scales"][2] == 0.0 and np.all(got["codes"][2] == 0) and np.all(got["mask"][2] == 0xFF)
 
 
 def test_quantizer_options_and_degenerate_rows():

@@ -33,6 +33,8 @@ def test_builtin_alpha_table_matches_the_oracle(lib, alpha_table):
     for bits, alpha in alpha_table.items():
         assert q.quest_alpha_star(bits) == pytest.approx(alpha, rel=3e-7)
     assert q.quest_alpha_star(5) == 0.0
+    from oracle import alpha_star
+    assert q.quest_alpha_star_fp4() == pytest.approx(alpha_star.alpha_star_fp4(), rel=3e-7)
     assert [q.quest_container_bits(b) for b in (1, 2, 3, 4, 8, 5)] == [1, 2, 4, 4, 8, 0]
     from oracle import quest_oracle as qo
     assert all(q.quest_container_bits(b) == qo.container_bits(b) for b in (1, 2, 3, 4, 8))
