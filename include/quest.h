@@ -132,6 +132,19 @@ quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, in
                                void *stream);
 
 /*
+ * The matmul of Algorithm 1 for the FP4 variant (Sec. 4.4), run on the E2M1 codes by the FP4 matrix
+ * instructions:  acc[m, n] = sum_k v_a[m, k] v_b[n, k] (v = signed E2M1 value of a code; the sum is
+ * a multiple of 1/4 and exact in fp32 for K <= 65536),  y = bf16((acc * a_scales[m]) * b_scales[n]).
+ *   a_codes [M, K/2], b_codes [N, K/2], scales from quest_hadamard_quantize_fp4
+ *   y        out bf16 [M, ld_y], ld_y >= N;  may be NULL if acc_out is given
+ *   acc_out  out fp32 [M, N] raw accumulators, or NULL (NULL in production)
+ * K a multiple of 128, 128 <= K <= 65536; M = 0 or N = 0 is a no-op; code pointers 16-byte aligned.
+ */
+quest_status quest_lowbit_gemm_fp4(const uint8_t *a_codes, const float *a_scales, int64_t M,
+                                   const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
+                                   void *y, int64_t ld_y, float *acc_out, void *stream);
+
+/*
  * Algorithm 2, the two masked inverse transforms: out = IHT(M (.) g) (Sec. 3.2 "Trust Estimators
  * for the Hadamard Projection").  The normalised Sylvester transform is its own inverse.
  *

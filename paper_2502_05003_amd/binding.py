@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
 EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
-           "quest_lowbit_gemm", "quest_trust_backward",
+           "quest_lowbit_gemm", "quest_lowbit_gemm_fp4", "quest_trust_backward",
            "quest_grad_gemm", "quest_weight_only_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
 
 _i64, _i32, _f32, _p = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
@@ -47,6 +47,8 @@ def load():
         lib.quest_alpha_star_fp4.argtypes = []
         lib.quest_alpha_star_fp4.restype = _f32
         lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p]
+        lib.quest_lowbit_gemm_fp4.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _p, _i64, _p, _p]
+        lib.quest_lowbit_gemm_fp4.restype = ctypes.c_int
         lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
         lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
         lib.quest_weight_only_gemm.argtypes = [_p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
@@ -143,6 +145,17 @@ def quest_lowbit_gemm(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: to
     _check(load().quest_lowbit_gemm(_ptr(a_codes), _ptr(a_scales), M, _ptr(b_codes), _ptr(b_scales),
                                     N, K, bits, _ptr(y), ld_y, _ptr(acc_out), _stream()),
            "quest_lowbit_gemm")
+
+
+def quest_lowbit_gemm_fp4(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: torch.Tensor,
+                          b_scales: torch.Tensor, K: int, *, y: torch.Tensor | None,
+                          acc_out: torch.Tensor | None = None) -> None:
+    """y[M, N] (bf16) and/or acc_out[M, N] (fp32) from packed E2M1 codes [M, K/2] and [N, K/2]."""
+    M, N = a_codes.shape[0], b_codes.shape[0]
+    ld_y = y.stride(0) if y is not None else N
+    _check(load().quest_lowbit_gemm_fp4(_ptr(a_codes), _ptr(a_scales), M, _ptr(b_codes), _ptr(b_scales),
+                                        N, K, _ptr(y), ld_y, _ptr(acc_out), _stream()),
+           "quest_lowbit_gemm_fp4")
 
 
 def quest_trust_backward(g: torch.Tensor, mask: torch.Tensor | None, had_block: int, *,

@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libquest.so")
 SOURCES = ["quest_api.hip", "hadamard_quantize.hip", "hadamard_quantize_mfma.hip",
-           "lowbit_gemm.hip", "trust_backward.hip", "trust_backward_mfma.hip", "grad_gemm.hip"]
+           "lowbit_gemm.hip", "fp4_gemm.hip", "trust_backward.hip", "trust_backward_mfma.hip", "grad_gemm.hip"]
 # per-source extra flags: kernels whose MFMA results are consumed by vector code keep them in VGPRs
 EXTRA_FLAGS = {"hadamard_quantize_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
                "trust_backward_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}

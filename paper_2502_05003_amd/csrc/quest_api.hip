@@ -225,6 +225,35 @@ quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, in
                : QUEST_ERR_LAUNCH;
 }
 
+quest_status quest_lowbit_gemm_fp4(const uint8_t *a_codes, const float *a_scales, int64_t M,
+                                   const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
+                                   void *y, int64_t ld_y, float *acc_out, void *stream)
+{
+    if (!a_codes || !a_scales || !b_codes || !b_scales || (!y && !acc_out))
+        return QUEST_ERR_NULL;
+    if (M < 0 || N < 0 || M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K < 128 || K > 65536 ||
+        (K & 127) || (M > N ? M : N) * (K / 2) >= (int64_t(1) << 32))
+        return QUEST_ERR_SHAPE;
+    if (y && ld_y < N)
+        return QUEST_ERR_SHAPE;
+    if (!aligned16(a_codes) || !aligned16(b_codes) || (reinterpret_cast<uintptr_t>(y) & 1u) ||
+        (reinterpret_cast<uintptr_t>(acc_out) & 3u))
+        return QUEST_ERR_ALIGN;
+    quest::Fp4GemmArgs args;
+    args.a_codes = a_codes;
+    args.a_scales = a_scales;
+    args.b_codes = b_codes;
+    args.b_scales = b_scales;
+    args.M = M;
+    args.N = N;
+    args.K = K;
+    args.y = y;
+    args.ld_y = ld_y;
+    args.acc_out = acc_out;
+    return quest::launch_fp4_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess ? QUEST_OK
+                                                                                       : QUEST_ERR_LAUNCH;
+}
+
 quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint8_t *mask,
                                   int64_t rows, int64_t cols, int32_t had_block, void *out,
                                   quest_dtype out_dtype, void *stream)

@@ -46,6 +46,19 @@ struct GemmArgs {
 
 hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream);
 
+struct Fp4GemmArgs {
+    const uint8_t *a_codes;
+    const float *a_scales;
+    const uint8_t *b_codes;
+    const float *b_scales;
+    int64_t M, N, K;
+    void *y;          // bf16, may be null
+    int64_t ld_y;
+    float *acc_out;   // may be null
+};
+
+hipError_t launch_fp4_gemm(const Fp4GemmArgs &a, hipStream_t stream);
+
 struct BackwardArgs {
     const void *g;
     quest_dtype g_dtype;

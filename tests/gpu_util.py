@@ -145,7 +145,10 @@ def check_gemm_output(y: torch.Tensor, ref_acc: np.ndarray, sa: np.ndarray, sb: 
     from paper_2502_05003_amd import synth
     mirror = (ref_acc.astype(np.float32) * sa.astype(np.float32)[:, None]) * sb.astype(np.float32)[None, :]
     assert np.array_equal(bf16_bits(y), synth.to_bf16_bits(mirror)), "bf16 output bits differ from the fp32 mirror"
-    ref = qo.dequant(ref_acc, sa.astype(np.float64), sb.astype(np.float64))
+    if np.issubdtype(ref_acc.dtype, np.integer):
+        ref = qo.dequant(ref_acc, sa.astype(np.float64), sb.astype(np.float64))
+    else:   # FP4 accumulators: multiples of 1/4, held in double
+        ref = ref_acc * sa.astype(np.float64)[:, None] * sb.astype(np.float64)[None, :]
     got = to_host_f64(y)
     assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * (1 + 1e-5) * np.abs(ref) + 1e-38)
     assert np.linalg.norm(got - ref) <= 2e-3 * np.linalg.norm(ref)

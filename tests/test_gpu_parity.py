@@ -259,6 +259,63 @@ def test_gemm_full_size_sampled_rows():
     assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.25
 
 
+FP4_GEMM_CASES = [(256, 512, 512), (130, 200, 1024), (1, 1, 128), (257, 129, 2048), (64, 640, 5632),
+                  (700, 600, 512), (513, 1025, 1024), (4000, 4100, 384)]
+
+
+@pytest.mark.parametrize("M,N,K", FP4_GEMM_CASES)
+def test_fp4_gemm_accumulators_exact_and_output_close(M, N, K):
+    """E2M1 codes on the FP4 matrix instructions (Sec. 4.4): accumulators equal the exact sums."""
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    a_codes = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    b_codes = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    a_codes[0] = 0x77                       # extreme rows: +6 everywhere, largest |acc| = 36 K
+    b_codes[0] = 0x77
+    if N > 1:
+        b_codes[1] = 0xFF                   # -6 everywhere
+    sa = (rng.random(M) + 0.5).astype(np.float32)
+    sb = ((rng.random(N) + 0.5) * 0.01).astype(np.float32)
+    y = torch.full((M, N + 2), 7.0, dtype=torch.bfloat16, device=DEV)   # ld_y > N
+    acc = torch.empty(M, N, dtype=torch.float32, device=DEV)
+    q.quest_lowbit_gemm_fp4(to_device(a_codes), to_device(sa), to_device(b_codes), to_device(sb), K,
+                            y=y[:, :N], acc_out=acc)
+    torch.cuda.synchronize()
+    ref_acc = qo.gemm_fp4(qo.unpack_fp4(a_codes, K), qo.unpack_fp4(b_codes, K))
+    got_acc = acc.cpu().numpy().astype(np.float64)
+    assert np.array_equal(got_acc, ref_acc)
+    assert got_acc[0, 0] == 36.0 * K
+    check_gemm_output(y[:, :N], ref_acc, sa, sb)
+    assert torch.all(y[:, N:] == 7.0)       # padding columns untouched
+
+
+def test_fp4_forward_full_size_sampled_rows():
+    """FP4 forward at M=16384, N=5632, K=2048: quantizer against the oracle on whole tensors, GEMM on
+    sampled rows; and FP4 reconstructs these activations slightly worse than INT4 (Sec. 4.4)."""
+    x, w, cfg = synth.make_config("mlp_up_1p6b", seed=0)
+    K, n = cfg["K"], cfg["had_block"]
+    M, N = x.shape[0], w.shape[0]
+    gx = gpu_quantize(x, n, 4, want_xh=False, fp4=True)
+    gw = gpu_quantize(w, n, 4, want_xh=False, fp4=True)
+    rx = qo.hadamard_quantize_fp4(x, n)
+    compare_quantizer_fp4(gx, rx, K)
+    compare_quantizer_fp4(gw, qo.hadamard_quantize_fp4(w, n), K)
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    q.quest_lowbit_gemm_fp4(gx["dev"]["codes"], gx["dev"]["scales"], gw["dev"]["codes"], gw["dev"]["scales"],
+                            K, y=y)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(4).choice(M, size=32, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    va, vb = qo.unpack_fp4(gx["codes"][rows], K), qo.unpack_fp4(gw["codes"], K)
+    got = check_gemm_output(y[torch.from_numpy(rows).to(DEV)], qo.gemm_fp4(va, vb), gx["scales"][rows], gw["scales"])
+    exact = qo.widen(x[rows]) @ qo.widen(w).T
+    assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.25
+    err_fp4 = np.linalg.norm(gx["scales"][:, None] * qo.unpack_fp4(gx["codes"], K) - rx.xh) / np.linalg.norm(rx.xh)
+    gi = gpu_quantize(x, n, 4, want_xh=False, want_mask=False)
+    err_int4 = np.linalg.norm(gi["scales"][:, None].astype(np.float64) * qo.unpack_odd(gi["codes"], K, 4) - rx.xh) / np.linalg.norm(rx.xh)
+    print(f"relative error of xhat_h: FP4 {err_fp4:.4f}, INT4 {err_int4:.4f}")
+    assert err_int4 < err_fp4 < 1.2 * err_int4
+
+
 # ------------------------------------------------------------------ backward
 
 BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16"), (70, 5632, 512, "bf16", "f32"),
