@@ -181,7 +181,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
 {
     if (a.rows == 0)
         return hipSuccess;
-    if (a.mode == kQuantRms && launch_hadamard_quantize_mfma(a, stream))
+    if (launch_hadamard_quantize_mfma(a, stream))
         return hipGetLastError();
     const int cols = (int)a.cols;
     const size_t lds_bytes = (size_t)(cols + (cols >> 5) + 1) * sizeof(float);

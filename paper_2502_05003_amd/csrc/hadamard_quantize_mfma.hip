@@ -141,8 +141,11 @@ struct TransposePlan {
 /*
  * HT: row length / 512.  LOG2N: log2 of the Hadamard block when it is >= 32; 5 also stands for
  * every smaller block (then only the MFMA operand differs, and `log2n` carries the true value).
+ * FP4: the codes are E2M1 values of 6 x_h / (alpha rms) (Sec. 4.4 "The FP4 Format"), made by the
+ * hardware conversion (nearest, ties to even, saturating, sign kept on underflow), and the scale
+ * is alpha rms / 6; everything else is shared.
  */
-template <int HT, int LOG2N, bool WITH_MASK>
+template <int HT, int LOG2N, bool WITH_MASK, bool FP4 = false>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(QUEST_HQ_WAVES_PER_EU)))
 void hq_mfma_kernel(
     const uint16_t *__restrict__ x, int64_t rows, int64_t ld, int log2n, float alpha,
@@ -258,9 +261,10 @@ void hq_mfma_kernel(
         const bool zero_row = !(rms > 0.0f);
         const float inv_step = zero_row ? 0.0f : (float)(kLevels - 1) * 0.5f * __builtin_amdgcn_rcpf(clip);
         const float cell16 = inv_step * inv_sqrt_n * 16.0f;     // raw -> 16 * (position in grid cells)
+        const float to_e2m1 = zero_row ? 0.0f : 6.0f * __builtin_amdgcn_rcpf(clip) * inv_sqrt_n;   // raw -> E2M1 units
         const float trust_raw = trust_edge * rms * sqrt_n;
         if (lane == 0)
-            scales[row] = clip * (1.0f / (float)(kLevels - 1));
+            scales[row] = clip * (FP4 ? 1.0f / 6.0f : 1.0f / (float)(kLevels - 1));
         uint32_t *code_row = reinterpret_cast<uint32_t *>(codes + row * (cols / 2));
         uint32_t *mask_row = reinterpret_cast<uint32_t *>(mask + row * (cols / 8));
 
@@ -372,17 +376,29 @@ void hq_mfma_kernel(
 #pragma unroll
             for (int dd = 0; dd < 2 * G; ++dd) {
                 if (8 * dd < count_i) {
-                    uint32_t even = 0, odd = 0;
+                    uint32_t packed;
+                    if (FP4) {
+                        // byte i / 2 = E2M1(element i + 1) << 4 | E2M1(element i), converted in pairs
+                        auto scaled = [&](int i) {
+                            return __fmul_rn(acc[(8 * dd + i) >> 4][reg_of_iota((8 * dd + i) & 15)], to_e2m1);
+                        };
+                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, scaled(0), scaled(1), 1.0f, 0);
+                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(2), scaled(3), 1.0f, 1);
+                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(4), scaled(5), 1.0f, 2);
+                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(6), scaled(7), 1.0f, 3);
+                    } else {
+                        uint32_t even = 0, odd = 0;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const float v = acc[(8 * dd + i) >> 4][reg_of_iota((8 * dd + i) & 15)];
-                        const float t = __fmaf_rn(v, cell16, 127.5f);
-                        if (i & 1)
-                            odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
-                        else
-                            even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+                        for (int i = 0; i < 8; ++i) {
+                            const float v = acc[(8 * dd + i) >> 4][reg_of_iota((8 * dd + i) & 15)];
+                            const float t = __fmaf_rn(v, cell16, 127.5f);
+                            if (i & 1)
+                                odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
+                            else
+                                even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+                        }
+                        packed = ((even >> 4) & 0x0f0f0f0fu) | (odd & 0xf0f0f0f0u);
                     }
-                    const uint32_t packed = ((even >> 4) & 0x0f0f0f0fu) | (odd & 0xf0f0f0f0u);
                     store_word(code_row + code_word + 64 * (2 * g0 + dd), nibble_plan.apply(packed));
                 }
             }
@@ -417,7 +433,7 @@ void hq_mfma_kernel(
     }
 }
 
-template <int HT, int LOG2N>
+template <int HT, int LOG2N, bool FP4 = false>
 void launch(const QuantizeArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -425,11 +441,11 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *x = static_cast<const uint16_t *>(a.x);
     if (a.mask)
-        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, true>), grid, dim3(kThreads), 0, stream, x,
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, true, FP4>), grid, dim3(kThreads), 0, stream, x,
                            a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
     else
-        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, false>), grid, dim3(kThreads), 0, stream, x,
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, false, FP4>), grid, dim3(kThreads), 0, stream, x,
                            a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
 }
@@ -441,10 +457,20 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
 // block of at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row.
 bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream)
 {
-    if (a.dtype != QUEST_BF16 || a.bits != 4 || (a.cols % 512) != 0)
+    if (a.dtype != QUEST_BF16 || a.bits != 4 || (a.cols % 512) != 0 || a.mode == kQuantAbsMax)
         return false;
     const int ht = (int)(a.cols / 512);
     const int l = a.log2n <= 5 ? 5 : a.log2n;
+    if (a.mode == kQuantFp4) {   // the E2M1 grid: rows of 1024 .. 5632 with their full-width block
+#define QUEST_FP4_CASE(HT_, L_)                   \
+    if (ht == HT_ && l == L_) {                   \
+        launch<HT_, L_, true>(a, stream);         \
+        return true;                              \
+    }
+        QUEST_FP4_CASE(2, 10) QUEST_FP4_CASE(4, 11) QUEST_FP4_CASE(8, 12) QUEST_FP4_CASE(11, 9)
+#undef QUEST_FP4_CASE
+        return false;
+    }
 #define QUEST_CASE(HT_, L_)                       \
     if (ht == HT_ && l == L_) {                   \
         launch<HT_, L_>(a, stream);               \
