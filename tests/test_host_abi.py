@@ -81,6 +81,32 @@ def test_gemm_backward_and_grad_gemm_reject_bad_arguments(lib):
     assert grad(which=2) == 8 and grad(dy=None) == 1 and grad(bits=8) == 3 and grad(M=32) == 2
 
 
+def test_variant_entry_points_reject_bad_arguments(lib):
+    def absmax(x=FAKE, dtype=1, rows=0, cols=512, ld=512, n=512, bits=4, codes=FAKE, scales=FAKE, mask=None):
+        return lib.quest_hadamard_quantize_absmax(x, dtype, rows, cols, ld, n, bits, codes, scales, mask, None, None)
+    assert absmax() == 0 and absmax(n=1) == 0
+    assert absmax(x=None) == 1 and absmax(bits=5) == 3 and absmax(n=48) == 4 and absmax(cols=20) == 2
+
+    def fp4(x=FAKE, dtype=1, rows=0, cols=512, ld=512, n=512, alpha=0.0, codes=FAKE, scales=FAKE, mask=None):
+        return lib.quest_hadamard_quantize_fp4(x, dtype, rows, cols, ld, n, alpha, codes, scales, mask, None, None)
+    assert fp4() == 0 and fp4(alpha=3.0) == 0
+    assert fp4(codes=None) == 1 and fp4(dtype=9) == 6 and fp4(alpha=float("nan")) == 8 and fp4(ld=100) == 2
+
+    def gemm4(a=FAKE, sa=FAKE, M=0, b=FAKE, sb=FAKE, N=0, K=512, y=FAKE, ld=0, acc=None):
+        return lib.quest_lowbit_gemm_fp4(a, sa, M, b, sb, N, K, y, ld, acc, None)
+    assert gemm4() == 0 and gemm4(y=None, acc=FAKE) == 0
+    assert gemm4(b=None) == 1 and gemm4(y=None) == 1
+    assert gemm4(K=64) == 2 and gemm4(K=192) == 2 and gemm4(K=131072) == 2 and gemm4(N=8, ld=4) == 2
+    assert gemm4(b=ctypes.c_void_p(0x10004)) == 5
+
+    def wonly(x=FAKE, wc=FAKE, ws=FAKE, bits=4, M=0, N=0, K=0, y=FAKE):
+        return lib.quest_weight_only_gemm(x, wc, ws, bits, M, N, K, y, None)
+    assert wonly() == 0
+    assert wonly(x=None) == 1 and wonly(bits=8) == 3
+    assert wonly(M=128, N=256, K=64) == 2 and wonly(M=256, N=256, K=32) == 2
+    assert wonly(y=ctypes.c_void_p(0x10002)) == 5
+
+
 def test_status_strings(lib):
     assert q.status_string(0) == "ok"
     assert len({q.status_string(s) for s in range(9)}) == 9
