@@ -29,6 +29,7 @@ WORKLOAD = "mlp_up_1p6b"     # the headline: X 16384x2048, W 5632x2048, Hadamard
 WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b")   # down: X 16384x5632, W 2048x5632, block 512
 KERNELS = ("quantize_x", "quantize_w", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w",
            "trust_backward_x", "trust_backward_w")
+FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the forward (--only)
 
 
 # HBM-side traffic per launch on this workload, bytes, from rocprofv3 --pmc FETCH_SIZE and
@@ -139,6 +140,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=WORKLOADS, default=WORKLOAD,
                     help="layer shape; the default is the one the headline metric is quoted on")
+    ap.add_argument("--only", choices=KERNELS + FP4_KERNELS, default=None,
+                    help="profiling aid: launch just this kernel --warmup + --steps times back to back "
+                         "(outputs of a whole step prepared once) and print its mean time; no benchmark line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain streaming kernel of known size (reads and writes 1 GiB each), "
                          "the yardstick for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -165,6 +169,39 @@ def main():
     n_sets = 3   # ~0.7 GiB per set: > 1 GiB of other traffic between two uses of any buffer
     sets = [BufferSet(torch, dev, x_bits, w_bits, dy_bits, cfg) for _ in range(n_sets)]
     torch.cuda.synchronize()
+
+    if args.only:
+        # one whole step first, so that every input of the chosen kernel exists
+        for b in sets:
+            for _, launch in step_kernels(q, b, cfg):
+                launch()
+        if args.only in FP4_KERNELS:
+            n, bits = cfg["had_block"], cfg["bits"]
+            for b in sets:
+                q.quest_hadamard_quantize_fp4(b.x, n, codes=b.x_codes, scales=b.x_scales, mask=b.x_mask)
+                q.quest_hadamard_quantize_fp4(b.w, n, codes=b.w_codes, scales=b.w_scales, mask=b.w_mask)
+        torch.cuda.synchronize()
+
+        def chosen(b):
+            if args.only == "quantize_x_fp4":
+                return lambda: q.quest_hadamard_quantize_fp4(b.x, cfg["had_block"], codes=b.x_codes,
+                                                             scales=b.x_scales, mask=b.x_mask)
+            if args.only == "lowbit_gemm_fp4":
+                return lambda: q.quest_lowbit_gemm_fp4(b.x_codes, b.x_scales, b.w_codes, b.w_scales, K, y=b.y)
+            return dict(step_kernels(q, b, cfg))[args.only]
+
+        launches = [chosen(b) for b in sets]
+        for i in range(args.warmup):
+            launches[i % n_sets]()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            launches[i % n_sets]()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / args.steps
+        print(json.dumps({"only": args.only, "workload": args.workload, "launches": args.steps,
+                          "us_per_launch_back_to_back": us}))
+        return
 
     # Every kernel launch is bracketed by a pair of HIP events on the stream it is launched on
     # (torch's current stream), in the warm-up and in the timed region alike, so that the per-kernel
