@@ -144,8 +144,12 @@ struct TransposePlan {
  * FP4: the codes are E2M1 values of 6 x_h / (alpha rms) (Sec. 4.4 "The FP4 Format"), made by the
  * hardware conversion (nearest, ties to even, saturating, sign kept on underflow), and the scale
  * is alpha rms / 6; everything else is shared.
+ * BITS: b of the Eq. 1 grid (1, 2, 3, 4 or 8; containers of 1, 2, 4, 4, 8 bits).  For b >= 2 the
+ * code is the top b bits of the byte sat_u8(rne(2^(8-b) cell + 127.5)) = clamp(floor(cell) + L/2,
+ * 0, L - 1); for b = 1 it is the complement of the sign bit.  What differs is how many codes make
+ * a dword and hence over how many lanes the fields are transposed before the store.
  */
-template <int HT, int LOG2N, bool WITH_MASK, bool FP4 = false>
+template <int HT, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(QUEST_HQ_WAVES_PER_EU)))
 void hq_mfma_kernel(
     const uint16_t *__restrict__ x, int64_t rows, int64_t ld, int log2n, float alpha,
@@ -158,7 +162,9 @@ void hq_mfma_kernel(
     constexpr bool kHalfTail = (HT & 1) != 0;
     // tiles transformed together: all of them when the block spans tiles, else two (one mask word)
     constexpr int G = (LOG2N > 10) ? T : (T >= 2 ? 2 : 1);
-    constexpr int kLevels = 16;
+    constexpr int kLevels = 1 << BITS;
+    constexpr int CB = BITS == 3 ? 4 : BITS;   // container bits
+    static_assert(!FP4 || BITS == 4, "the E2M1 grid has 4-bit codes");
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
@@ -185,9 +191,18 @@ void hq_mfma_kernel(
             __builtin_memcpy(&bmat[s], w, 16);
         }
     }
-    TransposePlan<3, 4> nibble_plan;
-    nibble_plan.init(lane);
-    TransposePlan<5, 1> bit_plan;
+    TransposePlan<3, 4> nibble_plan;   // 8 codes of 4 bits per dword
+    TransposePlan<2, 8> byte_plan;     // 4 codes of 8 bits
+    TransposePlan<4, 2> pair_plan;     // 16 codes of 2 bits
+    if (CB == 4)
+        nibble_plan.init(lane);
+    if (CB == 8)
+        byte_plan.init(lane);
+    if (CB == 2)
+        pair_plan.init(lane);
+    TransposePlan<5, 1> bit_plan;      // 32 mask bits, or 32 codes of 1 bit
+    if (CB == 1)
+        bit_plan.init(lane);
     if (WITH_MASK)
         bit_plan.init(lane);
 
@@ -260,12 +275,13 @@ void hq_mfma_kernel(
         const float clip = alpha * rms;
         const bool zero_row = !(rms > 0.0f);
         const float inv_step = zero_row ? 0.0f : (float)(kLevels - 1) * 0.5f * __builtin_amdgcn_rcpf(clip);
-        const float cell16 = inv_step * inv_sqrt_n * 16.0f;     // raw -> 16 * (position in grid cells)
+        // raw -> 2^(8-b) * (position in grid cells): the code ends up in the top b bits of a byte
+        const float cell16 = inv_step * inv_sqrt_n * (float)(256 >> BITS);
         const float to_e2m1 = zero_row ? 0.0f : 6.0f * __builtin_amdgcn_rcpf(clip) * inv_sqrt_n;   // raw -> E2M1 units
         const float trust_raw = trust_edge * rms * sqrt_n;
         if (lane == 0)
             scales[row] = clip * (FP4 ? 1.0f / 6.0f : 1.0f / (float)(kLevels - 1));
-        uint32_t *code_row = reinterpret_cast<uint32_t *>(codes + row * (cols / 2));
+        uint32_t *code_row = reinterpret_cast<uint32_t *>(codes + row * (cols * CB / 8));
         uint32_t *mask_row = reinterpret_cast<uint32_t *>(mask + row * (cols / 8));
 
         // The transform couples whole tiles only for blocks above 1024.  Below that the tiles are
@@ -371,35 +387,92 @@ void hq_mfma_kernel(
                         dst[64 * (first + i)] = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
             }
 
-            // codes: byte = sat_u8(rne(16 cell + 128 - 1/2)); its high nibble is
-            // clamp(floor(cell) + 8, 0, 15) = c.  Eight per dword in iota order, then the transpose.
+            // value of in-lane element i of this group
+            auto elem = [&](int i) { return acc[i >> 4][reg_of_iota(i & 15)]; };
+            if constexpr (CB == 4) {
+                // byte = sat_u8(rne(2^(8-b) cell + 128 - 1/2)); its top b bits are
+                // clamp(floor(cell) + L/2, 0, L - 1) = c.  Eight per dword in iota order, then the transpose.
 #pragma unroll
-            for (int dd = 0; dd < 2 * G; ++dd) {
-                if (8 * dd < count_i) {
-                    uint32_t packed;
-                    if (FP4) {
-                        // byte i / 2 = E2M1(element i + 1) << 4 | E2M1(element i), converted in pairs
-                        auto scaled = [&](int i) {
-                            return __fmul_rn(acc[(8 * dd + i) >> 4][reg_of_iota((8 * dd + i) & 15)], to_e2m1);
-                        };
-                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, scaled(0), scaled(1), 1.0f, 0);
-                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(2), scaled(3), 1.0f, 1);
-                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(4), scaled(5), 1.0f, 2);
-                        packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(6), scaled(7), 1.0f, 3);
-                    } else {
-                        uint32_t even = 0, odd = 0;
+                for (int dd = 0; dd < 2 * G; ++dd) {
+                    if (8 * dd < count_i) {
+                        uint32_t packed;
+                        if (FP4) {
+                            // byte i / 2 = E2M1(element i + 1) << 4 | E2M1(element i), converted in pairs
+                            auto scaled = [&](int i) { return __fmul_rn(elem(8 * dd + i), to_e2m1); };
+                            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, scaled(0), scaled(1), 1.0f, 0);
+                            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(2), scaled(3), 1.0f, 1);
+                            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(4), scaled(5), 1.0f, 2);
+                            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, scaled(6), scaled(7), 1.0f, 3);
+                        } else {
+                            uint32_t even = 0, odd = 0;
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            const float v = acc[(8 * dd + i) >> 4][reg_of_iota((8 * dd + i) & 15)];
-                            const float t = __fmaf_rn(v, cell16, 127.5f);
-                            if (i & 1)
-                                odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
-                            else
-                                even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+                            for (int i = 0; i < 8; ++i) {
+                                const float t = __fmaf_rn(elem(8 * dd + i), cell16, 127.5f);
+                                if (i & 1)
+                                    odd = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, odd);
+                                else
+                                    even = __builtin_amdgcn_cvt_pk_u8_f32(t, i >> 1, even);
+                            }
+                            packed = BITS == 4 ? ((even >> 4) & 0x0f0f0f0fu) | (odd & 0xf0f0f0f0u)
+                                               : ((even >> 5) & 0x07070707u) | ((odd >> 1) & 0x70707070u);
                         }
-                        packed = ((even >> 4) & 0x0f0f0f0fu) | (odd & 0xf0f0f0f0u);
+                        store_word(code_row + code_word + 64 * (2 * g0 + dd), nibble_plan.apply(packed));
                     }
-                    store_word(code_row + code_word + 64 * (2 * g0 + dd), nibble_plan.apply(packed));
+                }
+            } else if constexpr (CB == 8) {
+                // four codes per dword; lane 4 q + a ends up with elements 4 q .. 4 q + 3 of iota 4 w + a
+#pragma unroll
+                for (int w = 0; w < 4 * G; ++w) {
+                    if (4 * w < count_i) {
+                        uint32_t packed = 0;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            packed = __builtin_amdgcn_cvt_pk_u8_f32(__fmaf_rn(elem(4 * w + i), cell16, 127.5f), i, packed);
+                        store_word(code_row + (lane >> 2) + 16 * (lane & 3) + 64 * (4 * g0 + w),
+                                   byte_plan.apply(packed));
+                    }
+                }
+            } else if constexpr (CB == 2) {
+                // sixteen codes per dword.  Byte j of e[k] takes element k + 4 j, so that its code (top
+                // two bits) shifted down by 6 and up by 2 k lands at bit 2 (k + 4 j) of the dword.
+#pragma unroll
+                for (int t16 = 0; t16 < G; ++t16) {
+                    const int left = count_i - 16 * t16;
+                    if (left > 0) {
+                        uint32_t packed = 0;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            uint32_t e = 0;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                e = __builtin_amdgcn_cvt_pk_u8_f32(__fmaf_rn(elem(16 * t16 + k + 4 * j), cell16, 127.5f), j, e);
+                            packed |= ((e >> 6) & 0x03030303u) << (2 * k);
+                        }
+                        packed = pair_plan.apply(packed);
+                        if ((lane & 15) < left)   // a half tile at the end of the row has 8 elements per lane
+                            store_word(code_row + (lane >> 4) + 4 * (lane & 15) + 64 * (g0 + t16), packed);
+                    }
+                }
+            } else {
+                // one bit per code: c = 1 iff x_h >= 0, the complement of the sign bit; 32 per dword,
+                // transposed and stored like the mask
+#pragma unroll
+                for (int cc = 0; cc * 32 < kGroupI; ++cc) {
+                    const int left = count_i - 32 * cc;
+                    if (left > 0) {
+                        const int count = left < 32 ? left : 32;
+                        uint32_t negative = 0;
+#pragma unroll
+                        for (int i = 31; i >= 0; --i)
+                            if (i < count)
+                                negative = __builtin_amdgcn_alignbit(negative, __float_as_uint(elem(32 * cc + i)), 31);
+                        uint32_t code = ~negative;
+                        if (count < 32)
+                            code &= (1u << count) - 1u;
+                        code = bit_plan.apply(code);
+                        if (m < count)
+                            store_word(code_row + h + 2 * (m + 32 * (g0 / 2 + cc)), code);
+                    }
                 }
             }
 
@@ -433,7 +506,7 @@ void hq_mfma_kernel(
     }
 }
 
-template <int HT, int LOG2N, bool FP4 = false>
+template <int HT, int LOG2N, bool FP4 = false, int BITS = 4>
 void launch(const QuantizeArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -441,11 +514,11 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *x = static_cast<const uint16_t *>(a.x);
     if (a.mask)
-        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, true, FP4>), grid, dim3(kThreads), 0, stream, x,
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, true, FP4, BITS>), grid, dim3(kThreads), 0, stream, x,
                            a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
     else
-        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, false, FP4>), grid, dim3(kThreads), 0, stream, x,
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, false, FP4, BITS>), grid, dim3(kThreads), 0, stream, x,
                            a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
 }
@@ -457,10 +530,25 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
 // block of at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row.
 bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream)
 {
-    if (a.dtype != QUEST_BF16 || a.bits != 4 || (a.cols % 512) != 0 || a.mode == kQuantAbsMax)
+    if (a.dtype != QUEST_BF16 || (a.cols % 512) != 0 || a.mode == kQuantAbsMax)
         return false;
     const int ht = (int)(a.cols / 512);
     const int l = a.log2n <= 5 ? 5 : a.log2n;
+    if (a.bits != 4) {   // the other widths of the Eq. 1 grid: rows of 1024 .. 5632 with their full-width block
+        if (a.mode != kQuantRms)
+            return false;
+#define QUEST_BITS_CASE(HT_, L_, B_)                   \
+    if (ht == HT_ && l == L_ && a.bits == B_) {        \
+        launch<HT_, L_, false, B_>(a, stream);         \
+        return true;                                   \
+    }
+#define QUEST_BITS_CASES(HT_, L_) \
+    QUEST_BITS_CASE(HT_, L_, 1) QUEST_BITS_CASE(HT_, L_, 2) QUEST_BITS_CASE(HT_, L_, 3) QUEST_BITS_CASE(HT_, L_, 8)
+        QUEST_BITS_CASES(2, 10) QUEST_BITS_CASES(4, 11) QUEST_BITS_CASES(8, 12) QUEST_BITS_CASES(11, 9)
+#undef QUEST_BITS_CASES
+#undef QUEST_BITS_CASE
+        return false;
+    }
     if (a.mode == kQuantFp4) {   // the E2M1 grid: rows of 1024 .. 5632 with their full-width block
 #define QUEST_FP4_CASE(HT_, L_)                   \
     if (ht == HT_ && l == L_) {                   \

@@ -54,6 +54,10 @@ QUANT_CASES = [
     (33, 2048, 2048, 8, "bf16"), (19, 512, 1, 4, "bf16"), (19, 512, 2, 4, "f32"),
     (19, 512, 4, 2, "f32"), (19, 24, 8, 4, "f32"), (1, 8, 8, 4, "bf16"), (300, 64, 64, 8, "f32"),
     (21, 1536, 512, 3, "f32"), (9, 11008, 256, 4, "bf16"),
+    # every bit width on the matrix-core path: rows of 1024, 4096 and 5632 (ends in half a tile)
+    (70, 5632, 512, 1, "bf16"), (70, 5632, 512, 2, "bf16"), (70, 5632, 512, 3, "bf16"), (70, 5632, 512, 8, "bf16"),
+    (9, 1024, 1024, 1, "bf16"), (9, 1024, 1024, 2, "bf16"), (9, 1024, 1024, 3, "bf16"), (9, 1024, 1024, 8, "bf16"),
+    (5, 4096, 4096, 1, "bf16"), (5, 4096, 4096, 2, "bf16"), (5, 4096, 4096, 3, "bf16"), (5, 4096, 4096, 8, "bf16"),
 ]
 
 
