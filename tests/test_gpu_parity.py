@@ -535,6 +535,26 @@ def test_weight_only_gemm_matches_oracle(M, N, K, bits):
     print(f"b={bits}: relative error against x w^T {np.linalg.norm(got - exact) / np.linalg.norm(exact):.3f}")
 
 
+def test_split_tiles_are_summed_in_a_fixed_order():
+    """The weight gradient at the headline shape has its tiles split over the CUs; the partial tiles
+    are added in workgroup order, so two runs (with other work in between) agree bit for bit."""
+    M, N, K, bits = 8192, 768, 512, 4
+    x = synth.gaussian(M, K, 1.0, 1, "bf16")
+    dy = to_device(synth.upstream_gradient(M, N, 2, "bf16"))
+    gx = gpu_quantize(x, 512, bits, want_xh=False, want_mask=False)
+    outs = []
+    for rep in range(3):
+        out = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
+        q.quest_grad_gemm(1, dy, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=out)
+        if rep == 0:   # a call of another shape in between re-uses (and here regrows) the library's memory
+            other = torch.empty(256, 256, dtype=torch.bfloat16, device=DEV)
+            q.quest_grad_gemm(0, dy[:256, :256].contiguous(), gx["dev"]["codes"][:256, :128].contiguous(),
+                              gx["dev"]["scales"][:256].contiguous(), bits, 256, 256, 256, out=other)
+        outs.append(out)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[1], outs[2])
+
+
 def test_full_linear_forward_backward_small():
     """Algorithm 1 + Algorithm 2 end to end through the C ABI on a small layer."""
     M, N, K, bits, n = 128, 192, 512, 4, 512
