@@ -227,12 +227,19 @@ __device__ __forceinline__ int swz(int row)
 // odd and of the even elements.  With the nibble in the top half of its byte this is one
 // three-input bit function of (word, 0xf0f0f0f0, 0x88888888): keep bits 4..6, invert bit 7 (the
 // offset-binary -> two's-complement flip), force bit 3, clear bits 0..2.
-__device__ __forceinline__ void widen8(uint32_t w, uint32_t nibble_mask, int &even, int &odd)
+// For b = 3 (codes 0..7 in the same nibbles, u = 2c - 7) one more shift puts the three bits at the
+// top of the byte: (c << 5) with bit 7 inverted and bit 4 forced is 32 (c - 4) + 16 = 16 u; the
+// function is the same with (0xe0e0e0e0, 0x90909090), and the products carry 256 instead of 64.
+template <int BITS>
+__device__ __forceinline__ void widen8(uint32_t w, uint32_t field_mask, int &even, int &odd)
 {
-    odd = (int)__builtin_amdgcn_bitop3_b32(w, nibble_mask, 0x88888888u, 0x6A);
-    even = (int)__builtin_amdgcn_bitop3_b32(w << 4, nibble_mask, 0x88888888u, 0x6A);
+    static_assert(BITS == 3 || BITS == 4, "nibble containers only");
+    constexpr uint32_t forced = BITS == 4 ? 0x88888888u : 0x90909090u;
+    odd = (int)__builtin_amdgcn_bitop3_b32(w << (4 - BITS), field_mask, forced, 0x6A);
+    even = (int)__builtin_amdgcn_bitop3_b32(w << (8 - BITS), field_mask, forced, 0x6A);
 }
 
+template <int BITS>
 __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     const uint8_t *__restrict__ a_codes, const float *__restrict__ a_scales,
     const uint8_t *__restrict__ b_codes, const float *__restrict__ b_scales, int M, int N, int K,
@@ -285,7 +292,8 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
                 acc[i][j][r] = 0;
 
     // kept in a vector register (opaque to constant folding) so that widen8 is one instruction
-    uint32_t nibble_mask = 0xf0f0f0f0u;
+    constexpr int kCarry = BITS == 4 ? 6 : 8;   // log2 of the factor the products carry (8 u or 16 u per operand)
+    uint32_t nibble_mask = BITS == 4 ? 0xf0f0f0f0u : 0xe0e0e0e0u;
     asm volatile("" : "+v"(nibble_mask));
 
     const int steps = K / TK;
@@ -308,7 +316,7 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     float sa_reg[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        sa_reg[i] = a_scales[min(m0 + wm * 128 + i * 32 + lm, M - 1)] * (1.0f / 64.0f);
+        sa_reg[i] = a_scales[min(m0 + wm * 128 + i * 32 + lm, M - 1)] * (1.0f / (float)(1 << kCarry));
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -335,16 +343,16 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
         constexpr int g = decltype(gc)::value & 3, i = decltype(ic)::value;
         constexpr int p = g >> 1, e = g & 1;
         int w0, w1, w2, w3;
-        widen8(e ? af[p][i].z : af[p][i].x, nibble_mask, w0, w1);
-        widen8(e ? af[p][i].w : af[p][i].y, nibble_mask, w2, w3);
+        widen8<BITS>(e ? af[p][i].z : af[p][i].x, nibble_mask, w0, w1);
+        widen8<BITS>(e ? af[p][i].w : af[p][i].y, nibble_mask, w2, w3);
         wa[i & 1] = v4i{w0, w1, w2, w3};
     };
     auto widen_b = [&](auto gc, auto jc) {
         constexpr int g = decltype(gc)::value & 3, j = decltype(jc)::value;
         constexpr int p = g >> 1, e = g & 1;
         int w0, w1, w2, w3;
-        widen8(e ? bf[p][j].z : bf[p][j].x, nibble_mask, w0, w1);
-        widen8(e ? bf[p][j].w : bf[p][j].y, nibble_mask, w2, w3);
+        widen8<BITS>(e ? bf[p][j].z : bf[p][j].x, nibble_mask, w0, w1);
+        widen8<BITS>(e ? bf[p][j].w : bf[p][j].y, nibble_mask, w2, w3);
         wb[j] = v4i{w0, w1, w2, w3};
     };
     widen_a(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
@@ -416,7 +424,7 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
                     const int m = m0 + wm * 128 + i * 32 + lm;
                     const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                     if (m < M && n < N)
-                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> 6;   // exact: a multiple of 64
+                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> kCarry;   // exact: a multiple of 2^kCarry
                 }
     }
     if (!y)
@@ -496,6 +504,7 @@ __device__ __forceinline__ int wide_swz(int row)
     return (row >> 1) & 7;
 }
 
+template <int BITS>
 __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     const uint8_t *__restrict__ a_codes, const float *__restrict__ a_scales,
     const uint8_t *__restrict__ b_codes, const float *__restrict__ b_scales, int M, int N, int K,
@@ -548,7 +557,8 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
                 acc[i][j][r] = 0;
 
     // kept in a vector register (opaque to constant folding) so that widen8 is one instruction
-    uint32_t nibble_mask = 0xf0f0f0f0u;
+    constexpr int kCarry = BITS == 4 ? 6 : 8;   // log2 of the factor the products carry (8 u or 16 u per operand)
+    uint32_t nibble_mask = BITS == 4 ? 0xf0f0f0f0u : 0xe0e0e0e0u;
     asm volatile("" : "+v"(nibble_mask));
 
     const int steps = K / WTK;
@@ -567,7 +577,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     float sa_reg[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        sa_reg[i] = a_scales[min(m0 + wm * 128 + i * 32 + lm, M - 1)] * (1.0f / 64.0f);
+        sa_reg[i] = a_scales[min(m0 + wm * 128 + i * 32 + lm, M - 1)] * (1.0f / (float)(1 << kCarry));
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -605,16 +615,16 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj) {
                     int w0, w1, w2, w3;
-                    widen8(e ? bf[p & 1][jj].z : bf[p & 1][jj].x, nibble_mask, w0, w1);
-                    widen8(e ? bf[p & 1][jj].w : bf[p & 1][jj].y, nibble_mask, w2, w3);
+                    widen8<BITS>(e ? bf[p & 1][jj].z : bf[p & 1][jj].x, nibble_mask, w0, w1);
+                    widen8<BITS>(e ? bf[p & 1][jj].w : bf[p & 1][jj].y, nibble_mask, w2, w3);
                     bw[jj] = v4i{w0, w1, w2, w3};
                 }
             }
             v4i aw;
             {
                 int w0, w1, w2, w3;
-                widen8(e ? af[p & 1][i].z : af[p & 1][i].x, nibble_mask, w0, w1);
-                widen8(e ? af[p & 1][i].w : af[p & 1][i].y, nibble_mask, w2, w3);
+                widen8<BITS>(e ? af[p & 1][i].z : af[p & 1][i].x, nibble_mask, w0, w1);
+                widen8<BITS>(e ? af[p & 1][i].w : af[p & 1][i].y, nibble_mask, w2, w3);
                 aw = v4i{w0, w1, w2, w3};
             }
             // weight fragment as the row operand: transposed accumulator tiles
@@ -650,7 +660,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
                     const int m = m0 + wm * 128 + i * 32 + lm;
                     const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                     if (m < M && n < N)
-                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> 6;   // exact: a multiple of 64
+                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> kCarry;   // exact: a multiple of 2^kCarry
                 }
     }
     if (!y)
@@ -709,36 +719,54 @@ hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream)
         return hipSuccess;
     const int levels = 1 << a.bits;
     auto *y = static_cast<uint16_t *>(a.y);
-    if (a.bits == 4 && (a.K % WTK) == 0 && a.K >= 4096 && a.M >= 512 && a.N >= 512) {
+    if ((a.bits == 4 || a.bits == 3) && (a.K % WTK) == 0 && a.K >= 4096 && a.M >= 512 && a.N >= 512) {
         const int tiles_m = (int)((a.M + WTM - 1) / WTM), tiles_n = (int)((a.N + WTN - 1) / WTN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
         static bool wide_attr_set = false;
         if (!wide_attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel),
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<4>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
+            if (err == hipSuccess)
+                err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<3>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
             if (err != hipSuccess)
                 return err;
             wide_attr_set = true;
         }
-        hipLaunchKernelGGL(lowbit_gemm_wide_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kWideThreads),
-                           kWideLds, stream, a.a_codes, a.a_scales, a.b_codes, a.b_scales, (int)a.M,
-                           (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y, a.acc_out);
+        const dim3 grid((unsigned)(per_xcd * 8)), block(kWideThreads);
+        if (a.bits == 4)
+            hipLaunchKernelGGL(lowbit_gemm_wide_kernel<4>, grid, block, kWideLds, stream, a.a_codes, a.a_scales,
+                               a.b_codes, a.b_scales, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y,
+                               a.acc_out);
+        else
+            hipLaunchKernelGGL(lowbit_gemm_wide_kernel<3>, grid, block, kWideLds, stream, a.a_codes, a.a_scales,
+                               a.b_codes, a.b_scales, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y,
+                               a.acc_out);
         return hipGetLastError();
     }
-    if (a.bits == 4 && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
+    if ((a.bits == 4 || a.bits == 3) && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
         const int tiles_m = (int)((a.M + TM - 1) / TM), tiles_n = (int)((a.N + TN - 1) / TN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel),
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<4>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
+            if (err == hipSuccess)
+                err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<3>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
             if (err != hipSuccess)
                 return err;
             attr_set = true;
         }
-        hipLaunchKernelGGL(lowbit_gemm_tile_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kTileThreads),
-                           kTileLds, stream, a.a_codes, a.a_scales, a.b_codes, a.b_scales, (int)a.M,
-                           (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y, a.acc_out);
+        const dim3 grid((unsigned)(per_xcd * 8)), block(kTileThreads);
+        if (a.bits == 4)
+            hipLaunchKernelGGL(lowbit_gemm_tile_kernel<4>, grid, block, kTileLds, stream, a.a_codes, a.a_scales,
+                               a.b_codes, a.b_scales, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y,
+                               a.acc_out);
+        else
+            hipLaunchKernelGGL(lowbit_gemm_tile_kernel<3>, grid, block, kTileLds, stream, a.a_codes, a.a_scales,
+                               a.b_codes, a.b_scales, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y,
+                               a.acc_out);
         return hipGetLastError();
     }
     const dim3 grid((unsigned)((a.N + BN - 1) / BN), (unsigned)((a.M + BM - 1) / BM));

@@ -206,7 +206,9 @@ GEMM_CASES = [(256, 512, 512, 4), (130, 200, 1024, 4), (1, 1, 64, 4), (257, 129,
               # shapes that run the 256 x 128 tile kernel: whole tiles, ragged edges, several steps
               (512, 512, 256, 4), (700, 600, 512, 4), (513, 1025, 1024, 4), (768, 512, 5632, 4),
               # more tiles than the chip holds at once, ragged last tile row and column, one step only
-              (4096, 4090, 256, 4), (4096, 4096, 128, 4), (4000, 4100, 384, 4)]
+              (4096, 4090, 256, 4), (4096, 4096, 128, 4), (4000, 4100, 384, 4),
+              # b = 3 on the tile kernels (one more shift in the widening, products carry 256)
+              (700, 600, 512, 3), (768, 512, 5632, 3), (513, 1025, 1024, 3)]
 
 
 @pytest.mark.parametrize("M,N,K,bits", GEMM_CASES)
