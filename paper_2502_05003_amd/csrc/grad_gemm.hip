@@ -3,6 +3,8 @@
 // matrix cores with fp32 accumulation.
 //   which = 0:  out[M, K] = dy[M, N]   * what_h[N, K]   (contraction over N)
 //   which = 1:  out[N, K] = dy[M, N]^T * xhat_h[M, K]   (contraction over M)
+// and, with the same machinery, the weight-only forward product (Sec. 4.4):
+//   which = 2:  out[M, N] = x[M, K]    * what_h[N, K]^T (contraction over K)
 #include <algorithm>
 #include <mutex>
 #include <numeric>
