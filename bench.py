@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0      # dense INT8 MFMA (5.0 POP/s)
 BF16_PEAK_TFLOPS = 2500.0    # dense bf16 MFMA
+FP4_PEAK_TOPS = 10100.0      # dense FP4 MFMA (--grid fp4)
 
 WORKLOAD = "mlp_up_1p6b"     # the headline: X 16384x2048, W 5632x2048, Hadamard block 2048, b = 4
 WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b")   # down: X 16384x5632, W 2048x5632, block 512
@@ -84,9 +85,21 @@ class BufferSet:
         self.dw = torch.empty(N, K, dtype=b16, device=dev)
 
 
-def step_kernels(q, b, cfg):
+def step_kernels(q, b, cfg, fp4=False):
     """The seven launches of one step as (name, thunk) pairs, in execution order."""
     M, N, K, n, bits = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"], cfg["bits"]
+    if fp4:   # the FP4 variant of the method (Sec. 4.4): E2M1 codes, FP4 matrix instructions
+        return [
+            ("quantize_x", lambda: q.quest_hadamard_quantize_fp4(b.x, n, codes=b.x_codes, scales=b.x_scales,
+                                                                 mask=b.x_mask)),
+            ("quantize_w", lambda: q.quest_hadamard_quantize_fp4(b.w, n, codes=b.w_codes, scales=b.w_scales,
+                                                                 mask=b.w_mask)),
+            ("lowbit_gemm", lambda: q.quest_lowbit_gemm_fp4(b.x_codes, b.x_scales, b.w_codes, b.w_scales, K, y=b.y)),
+            ("grad_gemm_x", lambda: q.quest_grad_gemm_fp4(0, b.dy, b.w_codes, b.w_scales, M, N, K, out=b.g_x)),
+            ("grad_gemm_w", lambda: q.quest_grad_gemm_fp4(1, b.dy, b.x_codes, b.x_scales, M, N, K, out=b.g_w)),
+            ("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx)),
+            ("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw)),
+        ]
     return [
         ("quantize_x", lambda: q.quest_hadamard_quantize(b.x, n, bits, codes=b.x_codes,
                                                          scales=b.x_scales, mask=b.x_mask)),
@@ -140,6 +153,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=WORKLOADS, default=WORKLOAD,
                     help="layer shape; the default is the one the headline metric is quoted on")
+    ap.add_argument("--grid", choices=("int4", "fp4"), default="int4",
+                    help="int4: the headline path (Eq. 1 grid, INT8 matrix cores); fp4: the FP4 variant of "
+                         "Sec. 4.4 end to end (E2M1 codes, FP4 matrix instructions)")
     ap.add_argument("--only", choices=KERNELS + FP4_KERNELS, default=None,
                     help="profiling aid: launch just this kernel --warmup + --steps times back to back "
                          "(outputs of a whole step prepared once) and print its mean time; no benchmark line")
@@ -173,7 +189,7 @@ def main():
     if args.only:
         # one whole step first, so that every input of the chosen kernel exists
         for b in sets:
-            for _, launch in step_kernels(q, b, cfg):
+            for _, launch in step_kernels(q, b, cfg, args.grid == "fp4"):
                 launch()
         if args.only in FP4_KERNELS:
             n, bits = cfg["had_block"], cfg["bits"]
@@ -188,7 +204,7 @@ def main():
                                                              scales=b.x_scales, mask=b.x_mask)
             if args.only == "lowbit_gemm_fp4":
                 return lambda: q.quest_lowbit_gemm_fp4(b.x_codes, b.x_scales, b.w_codes, b.w_scales, K, y=b.y)
-            return dict(step_kernels(q, b, cfg))[args.only]
+            return dict(step_kernels(q, b, cfg, args.grid == "fp4"))[args.only]
 
         launches = [chosen(b) for b in sets]
         for i in range(args.warmup):
@@ -218,7 +234,7 @@ def main():
     scratch_pair = event_pair()
 
     def timed_step(i, pairs, gap_pair):
-        for name, launch in step_kernels(q, sets[i % n_sets], cfg):
+        for name, launch in step_kernels(q, sets[i % n_sets], cfg, args.grid == "fp4"):
             start, end = pairs[name] if pairs else scratch_pair
             start.record()
             launch()
@@ -245,7 +261,7 @@ def main():
     step_ops = 3.0 * gemm_ops
 
     def traffic(name):   # measured for the headline workload only
-        return MEASURED_TRAFFIC[name] if args.workload == WORKLOAD else None
+        return MEASURED_TRAFFIC[name] if args.workload == WORKLOAD and args.grid == "int4" else None
 
     def hbm(name, nbytes):
         gbs = nbytes / (ms[name] * 1e-3) / 1e9
@@ -256,13 +272,13 @@ def main():
     def mfma(name, peak):
         t = gemm_ops / (ms[name] * 1e-3) / 1e12
         return {"kernel": name, "bound": "mfma", "achieved": t, "peak": peak,
-                "unit": "TOPS" if peak == INT8_PEAK_TOPS else "TFLOP/s", "frac": t / peak,
+                "unit": "TFLOP/s" if peak == BF16_PEAK_TFLOPS else "TOPS", "frac": t / peak,
                 "traffic": traffic(name), "ms": ms[name]}
 
     rooflines = {
         "quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K)),
         "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K)),
-        "lowbit_gemm": mfma("lowbit_gemm", INT8_PEAK_TOPS),
+        "lowbit_gemm": mfma("lowbit_gemm", FP4_PEAK_TOPS if args.grid == "fp4" else INT8_PEAK_TOPS),
         "grad_gemm_x": mfma("grad_gemm_x", BF16_PEAK_TFLOPS),
         "grad_gemm_w": mfma("grad_gemm_w", BF16_PEAK_TFLOPS),
         "trust_backward_x": hbm("trust_backward_x", algorithmic_bytes_backward(M, K)),
@@ -277,12 +293,12 @@ def main():
         "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 (forward matmul) / bf16 (gradient matmuls) / f32 (transform, quantizer)",
+        "dtype": ("fp4" if args.grid == "fp4" else "int8") + " (forward matmul) / bf16 (gradient matmuls) / f32 (transform, quantizer)",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: X {M}x{K} bf16 N(0,1) + 0.5% outlier channels x50, "
                                f"W {N}x{K} bf16 N(0,0.02^2), dY {M}x{N} bf16, Hadamard block "
                                f"{cfg['had_block']}, b={cfg['bits']}, forward+backward",
-                   "M": M, "N": N, "K": K, "had_block": cfg["had_block"], "bits": cfg["bits"],
+                   "grid": args.grid, "M": M, "N": N, "K": K, "had_block": cfg["had_block"], "bits": cfg["bits"],
                    "buffer_sets": n_sets, "event_gap_us_subtracted": gap_ms * 1e3},
         "quantizer_GBps": rooflines["quantize_x"]["achieved"],
         "gemm_TOPS": rooflines["lowbit_gemm"]["achieved"],
@@ -296,7 +312,7 @@ def main():
         for _ in range(3):
             torch.add(src, 1, out=dst)   # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.grid == "int4":   # the oracle leg times the headline (integer-grid) path
         result["cpu_baseline"] = cpu_baseline(x_bits, w_bits, dy_bits, cfg)
     print(json.dumps(result))
 

@@ -177,6 +177,17 @@ quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_cod
                              void *out, void *stream);
 
 /*
+ * quest_grad_gemm for operands quantized by quest_hadamard_quantize_fp4: the code-packed operand's
+ * value is bf16(s * v), v the signed E2M1 value of its code (the backward pass of the FP4 variant,
+ * Sec. 4.4, is Algorithm 2 unchanged).  which = 0 or 1 as there.  The output must be made of whole
+ * 256 x 256 tiles and the contraction a multiple of 64 (QUEST_ERR_SHAPE otherwise).  Uses the
+ * library-owned device memory described at quest_grad_gemm.
+ */
+quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q_codes,
+                                 const float *q_scales, int64_t M, int64_t N, int64_t K, void *out,
+                                 void *stream);
+
+/*
  * Weight-only forward product (Sec. 4.4 "Weight-only quantization": 16-bit activations against
  * 1..4-bit weights):  y[M, N] = x[M, K] * what_h^T,  what_h[n, k] = bf16(s_w[n] * u_w[n, k]).
  *   x        bf16 [M, K] row-major (the activations in the domain the weights were quantized in:

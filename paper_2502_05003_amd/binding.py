@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libquest.so")
 QUEST_F32, QUEST_BF16 = 0, 1
 EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
            "quest_lowbit_gemm", "quest_lowbit_gemm_fp4", "quest_trust_backward",
-           "quest_grad_gemm", "quest_weight_only_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
+           "quest_grad_gemm", "quest_grad_gemm_fp4", "quest_weight_only_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
 
 _i64, _i32, _f32, _p = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 _lib = None
@@ -52,6 +52,8 @@ def load():
         lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
         lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
         lib.quest_weight_only_gemm.argtypes = [_p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
+        lib.quest_grad_gemm_fp4.argtypes = [_i32, _p, _p, _p, _i64, _i64, _i64, _p, _p]
+        lib.quest_grad_gemm_fp4.restype = ctypes.c_int
         for name in ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_lowbit_gemm",
                      "quest_trust_backward", "quest_grad_gemm", "quest_weight_only_gemm"):
             getattr(lib, name).restype = ctypes.c_int
@@ -173,6 +175,14 @@ def quest_grad_gemm(which: int, dy: torch.Tensor, q_codes: torch.Tensor, q_scale
     _check(load().quest_grad_gemm(which, _ptr(dy), _ptr(q_codes), _ptr(q_scales), bits, M, N, K,
                                   _ptr(out), _stream()),
            "quest_grad_gemm")
+
+
+def quest_grad_gemm_fp4(which: int, dy: torch.Tensor, q_codes: torch.Tensor, q_scales: torch.Tensor,
+                        M: int, N: int, K: int, *, out: torch.Tensor) -> None:
+    """quest_grad_gemm for E2M1 codes (operands from quest_hadamard_quantize_fp4)."""
+    _check(load().quest_grad_gemm_fp4(which, _ptr(dy), _ptr(q_codes), _ptr(q_scales), M, N, K, _ptr(out),
+                                      _stream()),
+           "quest_grad_gemm_fp4")
 
 
 def quest_weight_only_gemm(x: torch.Tensor, w_codes: torch.Tensor, w_scales: torch.Tensor, bits: int,

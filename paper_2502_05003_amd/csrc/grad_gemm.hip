@@ -166,6 +166,7 @@ __device__ __forceinline__ void static_for(F &&f)
 }
 
 // Expands packed codes to bf16(fp32(s * u)), u = 2 c - (L - 1): eight elements per thread.
+// levels = 0 stands for E2M1 codes (Sec. 4.4): u is then the signed E2M1 value of the code.
 __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__restrict__ codes,
                                                            const float *__restrict__ scales, int levels,
                                                            int cb, int K, int64_t groups,
@@ -188,8 +189,17 @@ __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__rest
     const uint32_t field = (1u << cb) - 1u;
     float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        v[e] = __fmul_rn(s, __fmaf_rn((float)((bits >> (e * cb)) & field), 2.0f, offset));
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t c = (bits >> (e * cb)) & field;
+        if (levels == 0) {
+            // magnitudes 0 .5 1 1.5 | 2 3 4 6: index < 4 is index / 2, else (2 + (index & 1)) * 2^((index >> 1) - 2)
+            const uint32_t i = c & 7u;
+            const float mag = i < 4u ? 0.5f * (float)i : (float)((2u + (i & 1u)) << ((i >> 1) - 2u));
+            v[e] = __fmul_rn(s, (c & 8u) ? -mag : mag);
+        } else {
+            v[e] = __fmul_rn(s, __fmaf_rn((float)c, 2.0f, offset));
+        }
+    }
     *reinterpret_cast<uint4 *>(qhat + g * 8) = make_uint4(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]),
                                                           pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7]));
 }
@@ -582,7 +592,7 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
 {
     if (a.M == 0 || a.N == 0 || a.K == 0)
         return hipSuccess;
-    const int levels = 1 << a.bits;
+    const int levels = a.fp4 ? 0 : 1 << a.bits;
     const auto *dy = static_cast<const uint16_t *>(a.dy);
     auto *out = static_cast<uint16_t *>(a.out);
     // which = 0: out[M, K] = dy what;  1: out[N, K] = dy^T xhat;  2: out[M, N] = x what^T (weight-only)
@@ -593,7 +603,7 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
     const bool whole_tiles = (out_rows % GT) == 0 && (out_cols % GT) == 0 && (contraction % GC) == 0 &&
                              out_rows * out_cols < ((int64_t)1 << 31) &&
                              std::max(a.M, a.N) * std::max(a.K, a.N) < ((int64_t)1 << 30);
-    if (a.which == 2 && !whole_tiles)
+    if ((a.which == 2 || a.fp4) && !whole_tiles)
         return hipErrorInvalidValue;
     if (whole_tiles) {
         const int tiles_r = (int)(out_rows / GT), tiles_k = (int)(out_cols / GT);

@@ -302,11 +302,44 @@ quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_cod
 
     quest::GradGemmArgs args;
     args.which = which;
+    args.fp4 = false;
     args.dy = dy;
     args.q_codes = q_codes;
     args.q_scales = q_scales;
     args.bits = bits;
     args.cb = container_bits(bits);
+    args.M = M;
+    args.N = N;
+    args.K = K;
+    args.out = out;
+    return quest::launch_grad_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUEST_OK
+               : QUEST_ERR_LAUNCH;
+}
+
+quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q_codes,
+                                 const float *q_scales, int64_t M, int64_t N, int64_t K, void *out,
+                                 void *stream)
+{
+    if (!dy || !q_codes || !q_scales || !out)
+        return QUEST_ERR_NULL;
+    if (which != 0 && which != 1)
+        return QUEST_ERR_ARG;
+    const int64_t out_rows = which == 0 ? M : N, contraction = which == 0 ? N : M;
+    if (M < 0 || N < 0 || K < 0 || (out_rows & 255) || (K & 255) || (contraction & 63) ||
+        M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K > (int64_t(1) << 22) ||
+        out_rows * K >= (int64_t(1) << 31) || (M > N ? M : N) * (K > N ? K : N) >= (int64_t(1) << 30))
+        return QUEST_ERR_SHAPE;
+    if (!aligned16(dy) || !aligned16(q_codes) || !aligned16(out))
+        return QUEST_ERR_ALIGN;
+    quest::GradGemmArgs args;
+    args.which = which;
+    args.fp4 = true;
+    args.dy = dy;
+    args.q_codes = q_codes;
+    args.q_scales = q_scales;
+    args.bits = 4;
+    args.cb = 4;
     args.M = M;
     args.N = N;
     args.K = K;
@@ -333,6 +366,7 @@ quest_status quest_weight_only_gemm(const void *x, const uint8_t *w_codes, const
 
     quest::GradGemmArgs args;
     args.which = 2;
+    args.fp4 = false;
     args.dy = x;
     args.q_codes = w_codes;
     args.q_scales = w_scales;

@@ -79,6 +79,7 @@ struct GradGemmArgs {
     const uint8_t *q_codes;
     const float *q_scales;
     int bits, cb;
+    bool fp4;          // the codes are E2M1 codes (bits = cb = 4)
     int64_t M, N, K;
     void *out;
 };

@@ -557,6 +557,35 @@ def test_split_tiles_are_summed_in_a_fixed_order():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[1], outs[2])
 
 
+@pytest.mark.parametrize("which,M,N,K", [(0, 512, 256, 512), (1, 512, 256, 512), (0, 768, 8192, 512),
+                                          (1, 8192, 768, 512)])
+def test_fp4_grad_gemm_matches_oracle(which, M, N, K):
+    """Backward matmuls of the FP4 variant (Algorithm 2 on E2M1-coded operands), whole and split tiles."""
+    n = 256
+    x = synth.gaussian(M, K, 1.0, 11, "bf16")
+    w = synth.gaussian(N, K, 0.02, 12, "bf16")
+    dy = synth.upstream_gradient(M, N, 0, "bf16")
+    gq = gpu_quantize(w if which == 0 else x, n, 4, want_xh=False, fp4=True)
+    out = torch.empty(M if which == 0 else N, K, dtype=torch.bfloat16, device=DEV)
+    q.quest_grad_gemm_fp4(which, to_device(dy), gq["dev"]["codes"], gq["dev"]["scales"], M, N, K, out=out)
+    torch.cuda.synchronize()
+    v = qo.unpack_fp4(gq["codes"], K)
+    u2 = np.rint(2.0 * v).astype(np.int32)                      # E2M1 values are multiples of 1/2
+    s_half = 0.5 * gq["scales"].astype(np.float64)
+    dyd = qo.widen(dy)
+    q16 = qo.widen(synth.to_bf16_bits((gq["scales"][:, None] * v.astype(np.float32)).astype(np.float32)))
+    if which == 0:
+        ref, mirror = qo.grad_input(dyd, u2, s_half), dyd @ q16
+        spread = np.sqrt((dyd ** 2) @ (q16 ** 2))
+    else:
+        ref, mirror = qo.grad_weight(dyd, u2, s_half), dyd.T @ q16
+        spread = np.sqrt((dyd.T ** 2) @ (q16 ** 2))
+    got = to_host_f64(out)
+    assert np.all(np.abs(got - mirror) <= BF16_HALF_ULP * 1.001 * np.abs(mirror) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+    assert np.linalg.norm(got - ref) <= 4e-3 * np.linalg.norm(ref)
+
+
 def test_full_linear_forward_backward_small():
     """Algorithm 1 + Algorithm 2 end to end through the C ABI on a small layer."""
     M, N, K, bits, n = 128, 192, 512, 4, 512

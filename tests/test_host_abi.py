@@ -99,6 +99,11 @@ def test_variant_entry_points_reject_bad_arguments(lib):
     assert gemm4(K=64) == 2 and gemm4(K=192) == 2 and gemm4(K=131072) == 2 and gemm4(N=8, ld=4) == 2
     assert gemm4(b=ctypes.c_void_p(0x10004)) == 5
 
+    def grad4(which=0, dy=FAKE, qc=FAKE, qs=FAKE, M=0, N=0, K=0, out=FAKE):
+        return lib.quest_grad_gemm_fp4(which, dy, qc, qs, M, N, K, out, None)
+    assert grad4() == 0 and grad4(which=2) == 8 and grad4(qc=None) == 1
+    assert grad4(M=128, N=256, K=256) == 2 and grad4(M=256, N=32, K=256) == 2
+
     def wonly(x=FAKE, wc=FAKE, ws=FAKE, bits=4, M=0, N=0, K=0, y=FAKE):
         return lib.quest_weight_only_gemm(x, wc, ws, bits, M, N, K, y, None)
     assert wonly() == 0
