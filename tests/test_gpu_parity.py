@@ -266,7 +266,9 @@ def test_gemm_full_size_sampled_rows():
 
 
 FP4_GEMM_CASES = [(256, 512, 512), (130, 200, 1024), (1, 1, 128), (257, 129, 2048), (64, 640, 5632),
-                  (700, 600, 512), (513, 1025, 1024), (4000, 4100, 384)]
+                  (700, 600, 512), (513, 1025, 1024), (4000, 4100, 384),
+                  # long contractions, whole and ragged tiles
+                  (768, 512, 5632), (513, 1025, 4096), (1024, 777, 4224)]
 
 
 @pytest.mark.parametrize("M,N,K", FP4_GEMM_CASES)
