@@ -221,6 +221,14 @@ __global__ __launch_bounds__(kTileThreads, 2) void fp4_gemm_tile_kernel(
         return;
 
     uint8_t *park = smem + wave * (128 * 128);
+    // the weight scales of this lane's columns, read once (the park writes below would otherwise keep
+    // the compiler from re-using them across the four row blocks)
+    float4 sb_reg[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            sb_reg[j][q] = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + j * 32 + 8 * q + 4 * lh);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = i * 32 + lm;   // row within the wave's block
@@ -230,7 +238,7 @@ __global__ __launch_bounds__(kTileThreads, 2) void fp4_gemm_tile_kernel(
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int col = j * 32 + 8 * q + 4 * lh;   // first of four consecutive columns
-                const float4 sb = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + col);
+                const float4 sb = sb_reg[j][q];
                 const float v0 = __fmul_rn(__fmul_rn(acc[i][j][4 * q + 0], sa), sb.x);
                 const float v1 = __fmul_rn(__fmul_rn(acc[i][j][4 * q + 1], sa), sb.y);
                 const float v2 = __fmul_rn(__fmul_rn(acc[i][j][4 * q + 2], sa), sb.z);
