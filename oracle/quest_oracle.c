@@ -11,6 +11,9 @@
  *   trust mask ................ Sec. 3.2, T = alpha / (2^b - 1)
  *   forward matmul ............ Algorithm 1 (y = xhat_h what_h^T)
  *   backward .................. Algorithm 2 (masked inverse transform, 16-bit matmuls)
+ *   AbsMax projection ......... Sec. 4.1 (the AbsMax-scaled comparison quantizer)
+ *   FP4 projection ............ Sec. 4.4 "The FP4 Format"
+ *   weight-only product ....... Sec. 4.4 "Weight-only quantization"
  * The clip constant alpha* is NOT in this file: callers pass alpha, and the Python
  * side of the oracle derives alpha* by minimising the Gaussian MSE.
  *
@@ -24,7 +27,12 @@
  * definition vs recursion, H H^T = n I, norm preservation, nearest-level brute
  * force, closed-form mask threshold, naive triple loops, adjoint identities).
  * The outer-trust generalisation for b = 1 is "parity unpinned" away from
- * outer_trust = 1 (the paper's two descriptions of the factor disagree).
+ * outer_trust = 1 (the paper's two descriptions of the factor disagree).  The AbsMax
+ * projection is pinned as a function (reduction to the RMS projection, hand-checked row,
+ * invariants), but which scaling the paper's baseline used exactly is not stated there:
+ * "parity unpinned" in that sense.  The FP4 variant's tie rule, signed zero and scale are
+ * this build's reading of two sentences; its pins fix the grid, the nearest-point rule,
+ * alpha*_FP4 and the paper's INT4-beats-FP4 statement.
  */
 #include <math.h>
 #include <stdint.h>
