@@ -309,9 +309,14 @@ def main():
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         for _ in range(3):
             torch.add(src, 1, out=dst)   # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
         torch.cuda.synchronize()
+        # what a plain streaming kernel reaches on this machine, next to the 8 TB/s of the datasheet
+        result["streaming_kernel_GBps"] = 3 * 2.0 * (1 << 30) / (time.perf_counter() - t0) / 1e9
     if not args.no_cpu_baseline and args.grid == "int4":   # the oracle leg times the headline (integer-grid) path
         result["cpu_baseline"] = cpu_baseline(x_bits, w_bits, dy_bits, cfg)
     print(json.dumps(result))
