@@ -145,6 +145,31 @@ def cpu_baseline(x_bits, w_bits, dy_bits, cfg):
                        f"{seconds:.1f} s; value = 6*{rows_g}*N*K ops / time")}
 
 
+def library_gemm_us(torch, dev, M, N, K, reps=20):
+    """The vendor library on the step's three products, with ready-made operands: int8 codes for
+    the forward product (no widening from nibbles), bf16 matrices for the gradient products (no
+    expansion of codes).  Mean microseconds per call, launched back to back."""
+    a8 = torch.randint(-15, 16, (M, K), device=dev, dtype=torch.int8)
+    b8 = torch.randint(-15, 16, (N, K), device=dev, dtype=torch.int8)
+    dy = torch.randn(M, N, device=dev, dtype=torch.bfloat16)
+    w = torch.randn(N, K, device=dev, dtype=torch.bfloat16)
+    x = torch.randn(M, K, device=dev, dtype=torch.bfloat16)
+    cases = {"int8_forward": lambda: torch._int_mm(a8, b8.t()),
+             "bf16_grad_x": lambda: torch.matmul(dy, w),
+             "bf16_grad_w": lambda: torch.matmul(dy.t(), x)}
+    out = {}
+    for name, f in cases.items():
+        for _ in range(5):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            f()
+        torch.cuda.synchronize()
+        out[name] = (time.perf_counter() - t0) * 1e6 / reps
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,6 +187,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain streaming kernel of known size (reads and writes 1 GiB each), "
                          "the yardstick for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the vendor library (torch.matmul bf16, torch._int_mm int8) on this "
+                         "workload's three matrix products, operands already in the library's own format: "
+                         "context for the kernels' rooflines, not part of the step")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (one MI355X per box); run with --gpus 1")
@@ -317,6 +346,8 @@ def main():
         torch.cuda.synchronize()
         # what a plain streaming kernel reaches on this machine, next to the 8 TB/s of the datasheet
         result["streaming_kernel_GBps"] = 3 * 2.0 * (1 << 30) / (time.perf_counter() - t0) / 1e9
+    if args.library_gemm:
+        result["library_gemm_us"] = library_gemm_us(torch, dev, M, N, K)
     if not args.no_cpu_baseline and args.grid == "int4":   # the oracle leg times the headline (integer-grid) path
         result["cpu_baseline"] = cpu_baseline(x_bits, w_bits, dy_bits, cfg)
     print(json.dumps(result))
