@@ -279,14 +279,9 @@ hipError_t launch_fp4_gemm(const Fp4GemmArgs &a, hipStream_t stream)
 {
     if (a.M == 0 || a.N == 0)
         return hipSuccess;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(fp4_gemm_tile_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
-        if (err != hipSuccess)
-            return err;
-        attr_set = true;
-    }
+    const hipError_t attr_err = allow_dynamic_lds(reinterpret_cast<const void *>(fp4_gemm_tile_kernel), kTileLds);
+    if (attr_err != hipSuccess)
+        return attr_err;
     const int tiles_m = (int)((a.M + TM - 1) / TM), tiles_n = (int)((a.N + TN - 1) / TN);
     const int per_xcd = (tiles_m * tiles_n + 7) / 8;
     hipLaunchKernelGGL(fp4_gemm_tile_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kTileThreads), kTileLds,

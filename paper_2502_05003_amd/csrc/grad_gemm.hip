@@ -610,26 +610,18 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
         const int tiles = tiles_r * tiles_k, steps = (int)(contraction / GC);
         constexpr int kStages = 5;
         constexpr int kLds = kStages * kGStage;
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t err = hipFuncSetAttribute(
-                reinterpret_cast<const void *>(grad_gemm_tile_kernel<0, kStages>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-            if (err == hipSuccess)
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(grad_gemm_tile_kernel<1, kStages>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-            if (err == hipSuccess)
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(grad_gemm_tile_kernel<2, kStages>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-            if (err != hipSuccess)
-                return err;
-            attr_set = true;
-        }
+        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<0, kStages>), kLds);
+        if (err == hipSuccess)
+            err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<1, kStages>), kLds);
+        if (err == hipSuccess)
+            err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<2, kStages>), kLds);
+        if (err != hipSuccess)
+            return err;
         // One workgroup per CU at a time.  When the last round of whole tiles would leave more than
         // a tenth of the CU-rounds idle, every CU gets the same share of (tile, step) units instead
         // and the split tiles are summed by a second, small kernel.
         int device = 0, cus = 0;
-        hipError_t err = hipGetDevice(&device);
+        err = hipGetDevice(&device);
         if (err == hipSuccess)
             err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
         if (err != hipSuccess)

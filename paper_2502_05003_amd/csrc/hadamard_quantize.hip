@@ -192,8 +192,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
     if (a.dtype == QUEST_BF16) {
         auto kernel = hq_generic_kernel<uint16_t>;
         if (lds_bytes > 48 * 1024)
-            err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            err = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)lds_bytes);
         if (err != hipSuccess)
             return err;
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream,
@@ -202,8 +201,7 @@ hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
     } else {
         auto kernel = hq_generic_kernel<float>;
         if (lds_bytes > 48 * 1024)
-            err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            err = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)lds_bytes);
         if (err != hipSuccess)
             return err;
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream,

@@ -1,7 +1,8 @@
 // Low-bit integer GEMM with a dequantizing bf16 epilogue: y = xhat_h what_h^T computed on the
 // packed codes (Algorithm 1, last step; Sec. 5 "Kernel Overview" stage 3 of arXiv 2502.05003).
-// The codes are widened to the signed odd integers u = 2c - (L - 1) on their way into LDS and
-// contracted on the INT8 matrix cores; acc = sum_k u_a u_b is exact in int32.
+// The codes are widened to signed bytes proportional to the odd integers u = 2c - (L - 1) (on their
+// way into LDS in the general kernel, at the consumer in the tile kernels) and contracted on the
+// INT8 matrix cores; acc = sum_k u_a u_b is exact in int32.
 #include <utility>
 
 #include "quest_device.h"
@@ -182,8 +183,8 @@ __global__ __launch_bounds__(kThreads) void lowbit_gemm_kernel(
 
 
 // ------------------------------------------------------------------------------------------
-// Main kernel for b = 4.  Workgroup tile 256 (M) x 128 (N), four waves of 128 x 64 (eight 32 x 32
-// accumulator tiles each), 128 contraction elements per step, two LDS stages, two workgroups per
+// Main kernel for b = 4 and b = 3 (nibble containers).  Workgroup tile 256 (M) x 128 (N), four waves of 128 x 64 (eight 32 x 32
+// accumulator tiles each), 128 contraction elements per step, three LDS stages, two workgroups per
 // CU so that one group's staging, barriers and epilogue hide behind the other's MFMAs.
 //
 // LDS holds the codes still packed (64 bytes per row and step): the LDS pipe moves 128 bytes per
@@ -738,17 +739,11 @@ hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream)
     if ((a.bits == 4 || a.bits == 3) && (a.K % WTK) == 0 && a.K >= 4096 && a.M >= 512 && a.N >= 512) {
         const int tiles_m = (int)((a.M + WTM - 1) / WTM), tiles_n = (int)((a.N + WTN - 1) / WTN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-        static bool wide_attr_set = false;
-        if (!wide_attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<4>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
-            if (err == hipSuccess)
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<3>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds);
-            if (err != hipSuccess)
-                return err;
-            wide_attr_set = true;
-        }
+        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<4>), kWideLds);
+        if (err == hipSuccess)
+            err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<3>), kWideLds);
+        if (err != hipSuccess)
+            return err;
         const dim3 grid((unsigned)(per_xcd * 8)), block(kWideThreads);
         if (a.bits == 4)
             hipLaunchKernelGGL(lowbit_gemm_wide_kernel<4>, grid, block, kWideLds, stream, a.a_codes, a.a_scales,
@@ -763,17 +758,11 @@ hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream)
     if ((a.bits == 4 || a.bits == 3) && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
         const int tiles_m = (int)((a.M + TM - 1) / TM), tiles_n = (int)((a.N + TN - 1) / TN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<4>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
-            if (err == hipSuccess)
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<3>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
-            if (err != hipSuccess)
-                return err;
-            attr_set = true;
-        }
+        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<4>), kTileLds);
+        if (err == hipSuccess)
+            err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<3>), kTileLds);
+        if (err != hipSuccess)
+            return err;
         const dim3 grid((unsigned)(per_xcd * 8)), block(kTileThreads);
         if (a.bits == 4)
             hipLaunchKernelGGL(lowbit_gemm_tile_kernel<4>, grid, block, kTileLds, stream, a.a_codes, a.a_scales,

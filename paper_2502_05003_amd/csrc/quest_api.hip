@@ -2,6 +2,10 @@
 // See include/quest.h for the contract of every function.
 #include <math.h>
 
+#include <map>
+#include <mutex>
+#include <tuple>
+
 #include "quest_internal.h"
 
 namespace {
@@ -71,6 +75,28 @@ quest_status shape_checks(int64_t rows, int64_t cols, int32_t had_block, int *lo
 }
 
 }  // namespace
+
+namespace quest {
+
+hipError_t allow_dynamic_lds(const void *kernel, int bytes)
+{
+    static std::mutex guard;
+    static std::map<std::tuple<const void *, int>, int> allowed;   // (kernel, device) -> bytes granted
+    int device = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess)
+        return err;
+    std::lock_guard<std::mutex> lock(guard);
+    int &granted = allowed[std::make_tuple(kernel, device)];
+    if (granted >= bytes)
+        return hipSuccess;
+    err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (err == hipSuccess)
+        granted = bytes;
+    return err;
+}
+
+}  // namespace quest
 
 extern "C" {
 

@@ -86,4 +86,8 @@ struct GradGemmArgs {
 
 hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream);
 
+// Raise the dynamic LDS limit of `kernel` to `bytes` on the current device.  The attribute is set
+// once per (kernel, device, size) and remembered; safe to call from several host threads.
+hipError_t allow_dynamic_lds(const void *kernel, int bytes);
+
 }  // namespace quest

@@ -62,9 +62,7 @@ hipError_t launch_generic(const BackwardArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)(a.rows < max_blocks ? a.rows : max_blocks));
     auto kernel = tb_generic_kernel<In, Out>;
     if (lds_bytes > 48 * 1024) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
+        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)lds_bytes);
         if (err != hipSuccess)
             return err;
     }
