@@ -23,6 +23,12 @@
 //   * codes and mask bits are formed in register order, packed per lane, transposed across lanes
 //     (8 x 8 nibbles, 32 x 32 bits) through the LDS crossbar, and stored as coalesced dwords in
 //     natural element order.
+//
+// fp32 rows and the AbsMax scale use the same kernel in its "hold all" form: every tile of the row
+// is transformed before anything is rounded (the scale needs the whole transformed row, or, for
+// fp32 rows, the sum of squares is gathered while the tiles stream in).  An fp32 input is cut into
+// three bf16 pieces, x = hi + mid + lo exactly (8 + 8 + 8 significant bits), each of which goes
+// through the same exact +-1 product; the fp32 MFMA would be sixteen times slower.
 #include "quest_device.h"
 #include "quest_internal.h"
 
@@ -148,11 +154,23 @@ struct TransposePlan {
  * code is the top b bits of the byte sat_u8(rne(2^(8-b) cell + 127.5)) = clamp(floor(cell) + L/2,
  * 0, L - 1); for b = 1 it is the complement of the sign bit.  What differs is how many codes make
  * a dword and hence over how many lanes the fields are transposed before the store.
+ * In: uint16_t (bf16 bits) or float.  ABSMAX: the grid spans the row's largest |x_h| instead of
+ * alpha rms (the comparison quantizer of Sec. 4.1); nothing is clipped, every element is trusted.
  */
-template <int HT, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(QUEST_HQ_WAVES_PER_EU)))
+// Waves per SIMD the register budget is set for.  Holding a long row (8 HT transformed values per
+// lane, next to the fp32 inputs still on their way) needs more than the 128 registers of four waves.
+template <int HT, bool HOLD_ALL, bool F32>
+constexpr int hq_waves_per_eu()
+{
+    return (HOLD_ALL && (HT > 8 || (F32 && HT == 8))) ? 2 : QUEST_HQ_WAVES_PER_EU;
+}
+
+template <int HT, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4, typename In = uint16_t,
+          bool ABSMAX = false>
+__global__ __launch_bounds__(kThreads)
+__attribute__((amdgpu_waves_per_eu(hq_waves_per_eu<HT, (sizeof(In) == 4 || ABSMAX), sizeof(In) == 4>())))
 void hq_mfma_kernel(
-    const uint16_t *__restrict__ x, int64_t rows, int64_t ld, int log2n, float alpha,
+    const In *__restrict__ x, int64_t rows, int64_t ld, int log2n, float alpha,
     float trust_edge, uint8_t *__restrict__ codes, float *__restrict__ scales,
     uint8_t *__restrict__ mask, float *__restrict__ xh_out)
 {
@@ -160,8 +178,12 @@ void hq_mfma_kernel(
     constexpr int NI = 8 * HT;             // elements per lane
     constexpr int cols = 512 * HT;
     constexpr bool kHalfTail = (HT & 1) != 0;
-    // tiles transformed together: all of them when the block spans tiles, else two (one mask word)
-    constexpr int G = (LOG2N > 10) ? T : (T >= 2 ? 2 : 1);
+    constexpr bool kF32 = sizeof(In) == 4;
+    constexpr bool kHoldAll = kF32 || ABSMAX;
+    static_assert(!kHoldAll || (!FP4 && BITS == 4), "fp32 rows and AbsMax: 4-bit integer grid only");
+    // tiles transformed together: all of them when the block spans tiles or the whole row is held,
+    // else two (one mask word)
+    constexpr int G = (LOG2N > 10 || kHoldAll) ? T : (T >= 2 ? 2 : 1);
     constexpr int kLevels = 1 << BITS;
     constexpr int CB = BITS == 3 ? 4 : BITS;   // container bits
     static_assert(!FP4 || BITS == 4, "the E2M1 grid has 4-bit codes");
@@ -191,6 +213,19 @@ void hq_mfma_kernel(
             __builtin_memcpy(&bmat[s], w, 16);
         }
     }
+    // fp32 rows: the middle piece is carried with its sign flipped (see below) and meets -H
+    v8bf bneg[2];
+    if constexpr (kF32) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            uint32_t w[4];
+            __builtin_memcpy(w, &bmat[s], 16);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] ^= (w[i] & 0x00800080u) << 8;   // bit 7 is set in +-1 and clear in 0: flip the sign of the former
+            __builtin_memcpy(&bneg[s], w, 16);
+        }
+    }
     TransposePlan<3, 4> nibble_plan;   // 8 codes of 4 bits per dword
     TransposePlan<2, 8> byte_plan;     // 4 codes of 8 bits
     TransposePlan<4, 2> pair_plan;     // 16 codes of 2 bits
@@ -213,26 +248,28 @@ void hq_mfma_kernel(
                                      : (float)(1 << (log2n >> 1));
     const int code_word = ((lane >> 3) & 3) + 4 * h + 8 * (lane & 7);
 
-    // Raw inputs of one row: two 16-byte pieces per tile and lane.
+    // Raw inputs of one bf16 row: two 16-byte pieces per tile and lane.
     struct RawRow {
-        uint4 a[T][2];
+        uint4 a[kF32 ? 1 : T][2];
     };
     auto load_row = [&](int64_t row, RawRow &raw) {
-        const uint16_t *src = x + row * ld + 32 * m + 16 * h;
+        if constexpr (!kF32) {   // fp32 rows stream in tile by tile, see below
+            const uint16_t *src = reinterpret_cast<const uint16_t *>(x) + row * ld + 32 * m + 16 * h;
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            raw.a[t][0] = make_uint4(0, 0, 0, 0);
-            raw.a[t][1] = make_uint4(0, 0, 0, 0);
-            if (!(kHalfTail && t == T - 1) || m < 16) {
+            for (int t = 0; t < T; ++t) {
+                raw.a[t][0] = make_uint4(0, 0, 0, 0);
+                raw.a[t][1] = make_uint4(0, 0, 0, 0);
+                if (!(kHalfTail && t == T - 1) || m < 16) {
 #if QUEST_HQ_NONTEMPORAL
-                const v4u n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
-                const v4u n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
-                raw.a[t][0] = make_uint4(n0.x, n0.y, n0.z, n0.w);
-                raw.a[t][1] = make_uint4(n1.x, n1.y, n1.z, n1.w);
+                    const v4u n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
+                    const v4u n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
+                    raw.a[t][0] = make_uint4(n0.x, n0.y, n0.z, n0.w);
+                    raw.a[t][1] = make_uint4(n1.x, n1.y, n1.z, n1.w);
 #else
-                raw.a[t][0] = *reinterpret_cast<const uint4 *>(src + 1024 * t);
-                raw.a[t][1] = *reinterpret_cast<const uint4 *>(src + 1024 * t + 8);
+                    raw.a[t][0] = *reinterpret_cast<const uint4 *>(src + 1024 * t);
+                    raw.a[t][1] = *reinterpret_cast<const uint4 *>(src + 1024 * t + 8);
 #endif
+                }
             }
         }
     };
@@ -253,34 +290,46 @@ void hq_mfma_kernel(
         RawRow raw;
         load_row(row, raw);
 #endif
-        // sum of squares from the packed inputs (the block transform is orthonormal)
-        float sumsq = 0.0f;
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const uint4 a0 = raw.a[t][0], a1 = raw.a[t][1];
-            const uint32_t w[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                v2bf pair;
-                __builtin_memcpy(&pair, &w[i], 4);
-                sumsq = __builtin_amdgcn_fdot2_f32_bf16(pair, pair, sumsq, false);
-            }
-        }
-        sumsq = wave_sum(sumsq);
-
         // Per-row constants in the un-normalised domain (x_h = raw / sqrt(n)).  The reciprocal and
         // the square root are the hardware approximations (1 ulp): the codes are decided on
         // raw * raw_to_cell, and a relative error of 1e-7 there is the size of one fp32 rounding.
-        const float rms = __builtin_amdgcn_sqrtf(sumsq * (1.0f / (float)cols));
-        const float clip = alpha * rms;
-        const bool zero_row = !(rms > 0.0f);
-        const float inv_step = zero_row ? 0.0f : (float)(kLevels - 1) * 0.5f * __builtin_amdgcn_rcpf(clip);
-        // raw -> 2^(8-b) * (position in grid cells): the code ends up in the top b bits of a byte
-        const float cell16 = inv_step * inv_sqrt_n * (float)(256 >> BITS);
-        const float to_e2m1 = zero_row ? 0.0f : 6.0f * __builtin_amdgcn_rcpf(clip) * inv_sqrt_n;   // raw -> E2M1 units
-        const float trust_raw = trust_edge * rms * sqrt_n;
-        if (lane == 0)
-            scales[row] = clip * (FP4 ? 1.0f / 6.0f : 1.0f / (float)(kLevels - 1));
+        float cell16 = 0.0f, to_e2m1 = 0.0f, trust_raw = 0.0f;
+        // `sumsq`: this lane's share of the row's sum of squares; `raw_max`: the row's largest |raw|
+        auto set_row_constants = [&](float sumsq, float raw_max) {
+            float clip;   // half-width of the grid in x_h units
+            if constexpr (ABSMAX) {
+                clip = __fmul_rn(raw_max, inv_sqrt_n);
+                trust_raw = raw_max;
+            } else {
+                const float rms = __builtin_amdgcn_sqrtf(wave_sum(sumsq) * (1.0f / (float)cols));
+                clip = alpha * rms;
+                trust_raw = trust_edge * rms * sqrt_n;
+            }
+            const bool zero_row = !(clip > 0.0f);
+            const float inv_step = zero_row ? 0.0f : (float)(kLevels - 1) * 0.5f * __builtin_amdgcn_rcpf(clip);
+            // raw -> 2^(8-b) * (position in grid cells): the code ends up in the top b bits of a byte
+            cell16 = inv_step * inv_sqrt_n * (float)(256 >> BITS);
+            to_e2m1 = zero_row ? 0.0f : 6.0f * __builtin_amdgcn_rcpf(clip) * inv_sqrt_n;   // raw -> E2M1 units
+            if (lane == 0)
+                scales[row] = clip * (FP4 ? 1.0f / 6.0f : 1.0f / (float)(kLevels - 1));
+        };
+        float sumsq = 0.0f;
+        if constexpr (!kF32) {
+            // sum of squares from the packed inputs (the block transform is orthonormal)
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const uint4 a0 = raw.a[t][0], a1 = raw.a[t][1];
+                const uint32_t w[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    v2bf pair;
+                    __builtin_memcpy(&pair, &w[i], 4);
+                    sumsq = __builtin_amdgcn_fdot2_f32_bf16(pair, pair, sumsq, false);
+                }
+            }
+        }
+        if constexpr (!kHoldAll)
+            set_row_constants(sumsq, 0.0f);
         uint32_t *code_row = reinterpret_cast<uint32_t *>(codes + row * (cols * CB / 8));
         uint32_t *mask_row = reinterpret_cast<uint32_t *>(mask + row * (cols / 8));
 
@@ -294,15 +343,72 @@ void hq_mfma_kernel(
             for (int u = 0; u < G; ++u) {
                 const int t = g0 + u;
                 if (t < T) {
-                    v8bf f0, f1;
-                    __builtin_memcpy(&f0, &raw.a[t][0], 16);
-                    __builtin_memcpy(&f1, &raw.a[t][1], 16);
                     v16f z;
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         z[r] = 0.0f;
-                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
-                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+                    if constexpr (kF32) {
+                        // this lane's sixteen consecutive floats of tile row m: q = 16 h .. 16 h + 15
+                        const float *src = reinterpret_cast<const float *>(x) + row * ld + 1024 * t + 32 * m + 16 * h;
+                        float f[16];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            v4u piece = {0, 0, 0, 0};
+                            if (!(kHalfTail && t == T - 1) || m < 16)
+                                piece = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 4 * i));
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                f[4 * i + e] = __uint_as_float(piece[e]);
+                        }
+                        // x = hi + mid + lo, each piece the top 16 bits of what the pieces before it
+                        // leave (exact: the remainders have 16 and 8 significant bits).  Remainders
+                        // come from the two-way bf16 dot product, packed piece times (1, 0) or (0, 1)
+                        // minus the value: s1 = hi - x = -(mid + lo), s2 = top16(s1) - s1 = lo.
+                        uint32_t hi[8], mid[8], lo[8];
+                        // (1, 0) and (0, 1) as bf16 pairs, held in registers the compiler cannot see through: written
+                        // as literals the pair (1, 0) reaches the instruction as (0, 1)
+                        uint32_t first_bits = 0x00003F80u, second_bits = 0x3F800000u;
+                        asm volatile("" : "+v"(first_bits), "+v"(second_bits));
+                        v2bf first, second;
+                        __builtin_memcpy(&first, &first_bits, 4);
+                        __builtin_memcpy(&second, &second_bits, 4);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const float a = f[2 * i], b = f[2 * i + 1];
+                            sumsq = __fmaf_rn(a, a, sumsq);
+                            sumsq = __fmaf_rn(b, b, sumsq);
+                            hi[i] = __builtin_amdgcn_perm(__float_as_uint(b), __float_as_uint(a), 0x07060302u);
+                            v2bf hp;
+                            __builtin_memcpy(&hp, &hi[i], 4);
+                            const float s1a = __builtin_amdgcn_fdot2_f32_bf16(hp, first, -a, false);
+                            const float s1b = __builtin_amdgcn_fdot2_f32_bf16(hp, second, -b, false);
+                            mid[i] = __builtin_amdgcn_perm(__float_as_uint(s1b), __float_as_uint(s1a), 0x07060302u);
+                            v2bf mp;
+                            __builtin_memcpy(&mp, &mid[i], 4);
+                            const float s2a = __builtin_amdgcn_fdot2_f32_bf16(mp, first, -s1a, false);
+                            const float s2b = __builtin_amdgcn_fdot2_f32_bf16(mp, second, -s1b, false);
+                            lo[i] = __builtin_amdgcn_perm(__float_as_uint(s2b), __float_as_uint(s2a), 0x07060302u);
+                        }
+                        v8bf p0, p1;
+                        __builtin_memcpy(&p0, &lo[0], 16);      // smallest piece first
+                        __builtin_memcpy(&p1, &lo[4], 16);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, bmat[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, bmat[1], z, 0, 0, 0);
+                        __builtin_memcpy(&p0, &mid[0], 16);     // holds -mid
+                        __builtin_memcpy(&p1, &mid[4], 16);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, bneg[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, bneg[1], z, 0, 0, 0);
+                        __builtin_memcpy(&p0, &hi[0], 16);
+                        __builtin_memcpy(&p1, &hi[4], 16);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, bmat[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, bmat[1], z, 0, 0, 0);
+                    } else {
+                        v8bf f0, f1;
+                        __builtin_memcpy(&f0, &raw.a[t][0], 16);
+                        __builtin_memcpy(&f1, &raw.a[t][1], 16);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+                    }
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         acc[u][r] = z[r];
@@ -372,6 +478,21 @@ void hq_mfma_kernel(
                                 bfly(acc[u][r], acc[u | (1 << k)][r]);
                         }
                 }
+            }
+
+            if constexpr (kHoldAll) {   // the whole row is transformed: now its scale can be fixed
+                float raw_max = 0.0f;
+                if constexpr (ABSMAX) {
+#pragma unroll
+                    for (int u = 0; u < G; ++u)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            raw_max = fmaxf(raw_max, fabsf(acc[u][r]));
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1)
+                        raw_max = fmaxf(raw_max, __shfl_xor(raw_max, off, kWave));
+                }
+                set_row_constants(sumsq, raw_max);
             }
 
             // in-lane elements of this group: iota = 16 g0 .. , as far as the row goes
@@ -506,20 +627,20 @@ void hq_mfma_kernel(
     }
 }
 
-template <int HT, int LOG2N, bool FP4 = false, int BITS = 4>
+template <int HT, int LOG2N, bool FP4 = false, int BITS = 4, typename In = uint16_t, bool ABSMAX = false>
 void launch(const QuantizeArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
     const int64_t max_blocks = QUEST_HQ_MAX_BLOCKS;
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
-    const auto *x = static_cast<const uint16_t *>(a.x);
+    const auto *x = static_cast<const In *>(a.x);
     if (a.mask)
-        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, true, FP4, BITS>), grid, dim3(kThreads), 0, stream, x,
-                           a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, true, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
+                           stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
     else
-        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, false, FP4, BITS>), grid, dim3(kThreads), 0, stream, x,
-                           a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
+        hipLaunchKernelGGL((hq_mfma_kernel<HT, LOG2N, false, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
+                           stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
 }
 
@@ -527,13 +648,32 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
 
 // Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
 // Covered: bf16 input, b = 4, rows of 512, 1024, 2048, 4096 or 5632 elements, and a Hadamard
-// block of at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row.
+// block of at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row; fp32 input and the
+// AbsMax scale (b = 4) and the other grids (bf16) for rows of 512 .. 5632 with their widest block.
 bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream)
 {
-    if (a.dtype != QUEST_BF16 || (a.cols % 512) != 0 || a.mode == kQuantAbsMax)
+    if ((a.cols % 512) != 0)
         return false;
     const int ht = (int)(a.cols / 512);
     const int l = a.log2n <= 5 ? 5 : a.log2n;
+    if (a.dtype == QUEST_F32 || a.mode == kQuantAbsMax) {   // the whole row is held before anything is rounded
+        if (a.bits != 4 || a.mode == kQuantFp4)
+            return false;
+#define QUEST_HOLD_CASE(HT_, L_)                                         \
+    if (ht == HT_ && l == L_) {                                          \
+        if (a.dtype == QUEST_F32 && a.mode == kQuantAbsMax)              \
+            launch<HT_, L_, false, 4, float, true>(a, stream);           \
+        else if (a.dtype == QUEST_F32)                                   \
+            launch<HT_, L_, false, 4, float, false>(a, stream);          \
+        else                                                             \
+            launch<HT_, L_, false, 4, uint16_t, true>(a, stream);        \
+        return true;                                                     \
+    }
+        QUEST_HOLD_CASE(1, 9) QUEST_HOLD_CASE(2, 10) QUEST_HOLD_CASE(4, 11) QUEST_HOLD_CASE(8, 12)
+        QUEST_HOLD_CASE(11, 9)
+#undef QUEST_HOLD_CASE
+        return false;
+    }
     if (a.bits != 4) {   // the other widths of the Eq. 1 grid: rows of 1024 .. 5632 with their full-width block
         if (a.mode != kQuantRms)
             return false;

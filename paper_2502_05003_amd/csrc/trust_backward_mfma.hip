@@ -1,4 +1,4 @@
-// Matrix-core assisted trust-masked inverse Hadamard transform, bf16 in / bf16 out (Algorithm 2,
+// Matrix-core assisted trust-masked inverse Hadamard transform, bf16 in, bf16 or fp32 out (Algorithm 2,
 // out = IHT(M (.) g); Sec. 3.2 of arXiv 2502.05003).  Same data flow as the fused quantizer
 // (hadamard_quantize_mfma.hip), which see for the index bookkeeping:
 //   * one wavefront per row of 512 * HT elements, tiles of 1024 elements seen as 32 x 32 matrices;
@@ -9,7 +9,8 @@
 //   * afterwards lane l & 31 holds index bits 0..4, l >> 5 bit 5, and the in-lane index iota the
 //     bits from 6 up; values are scaled by 1 / sqrt(n), rounded to bf16 in pairs (iota, iota + 1),
 //     and one exchange with the neighbouring lane turns those into pairs of adjacent elements, so
-//     that a wave stores 256 contiguous bytes per instruction.
+//     that a wave stores 256 contiguous bytes per instruction;
+//   * fp32 outputs are stored as they are, 64 consecutive floats per wave instruction.
 #include "quest_device.h"
 #include "quest_internal.h"
 
@@ -61,11 +62,12 @@ __device__ __forceinline__ uint32_t keep_trusted(uint32_t pair, uint32_t mask_bi
     return pair & __builtin_amdgcn_perm(hi, lo, 0x07060100u);   // low half from lo, high half from hi
 }
 
-template <int HT, int LOG2N, bool WITH_MASK>
+template <int HT, int LOG2N, bool WITH_MASK, typename Out = uint16_t>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4)))
 void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ mask, int64_t rows,
-                    int log2n, uint16_t *__restrict__ out)
+                    int log2n, Out *__restrict__ out)
 {
+    constexpr bool kF32Out = sizeof(Out) == 4;
     constexpr int T = (HT + 1) / 2;
     constexpr int NI = 8 * HT;
     constexpr int cols = 512 * HT;
@@ -197,49 +199,69 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
             }
         }
 
-        // element = (lane & 31) + 32 h + 64 iota.  Round (iota, iota + 1) to a bf16 pair, swap halves
-        // with lane ^ 1: an even lane then holds elements (l, l + 1) of iota, an odd lane elements
-        // (l - 1, l) of iota + 1.  A wave instruction stores 2 x 128 contiguous bytes.
-        uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * cols) + (m >> 1) + 16 * h +
-                        32 * (lane & 1);
+        // element = (lane & 31) + 32 h + 64 iota.
+        if constexpr (kF32Out) {
+            float *dst = out + row * cols + lane;
 #pragma unroll
-        for (int i = 0; i < NI; i += 2) {
-            const float v0 = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
-            const float v1 = __fmul_rn(acc[(i + 1) >> 4][reg_of_iota((i + 1) & 15)], inv_sqrt_n);
-            const uint32_t own = pack_bf16_pair(v0, v1);
-            const uint32_t other = (uint32_t)__builtin_amdgcn_ds_swizzle((int)own, (1 << 10) | 0x1f);
-            __builtin_nontemporal_store(__builtin_amdgcn_perm(other, own, pair_sel), dst + 32 * i);
+            for (int i = 0; i < NI; ++i)
+                __builtin_nontemporal_store(__fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n), dst + 64 * i);
+        } else {
+            // Round (iota, iota + 1) to a bf16 pair, swap halves with lane ^ 1: an even lane then
+            // holds elements (l, l + 1) of iota, an odd lane elements (l - 1, l) of iota + 1.  A wave
+            // instruction stores 2 x 128 contiguous bytes.
+            uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * cols) + (m >> 1) + 16 * h +
+                            32 * (lane & 1);
+#pragma unroll
+            for (int i = 0; i < NI; i += 2) {
+                const float v0 = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
+                const float v1 = __fmul_rn(acc[(i + 1) >> 4][reg_of_iota((i + 1) & 15)], inv_sqrt_n);
+                const uint32_t own = pack_bf16_pair(v0, v1);
+                const uint32_t other = (uint32_t)__builtin_amdgcn_ds_swizzle((int)own, (1 << 10) | 0x1f);
+                __builtin_nontemporal_store(__builtin_amdgcn_perm(other, own, pair_sel), dst + 32 * i);
+            }
         }
     }
 }
 
-template <int HT, int LOG2N>
+template <int HT, int LOG2N, typename Out = uint16_t>
 void launch(const BackwardArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
     const int64_t max_blocks = QUEST_TB_MAX_BLOCKS;
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *g = static_cast<const uint16_t *>(a.g);
-    auto *out = static_cast<uint16_t *>(a.out);
+    auto *out = static_cast<Out *>(a.out);
     if (a.mask)
-        hipLaunchKernelGGL((tb_mfma_kernel<HT, LOG2N, true>), grid, dim3(kThreads), 0, stream, g,
+        hipLaunchKernelGGL((tb_mfma_kernel<HT, LOG2N, true, Out>), grid, dim3(kThreads), 0, stream, g,
                            a.mask, a.rows, a.log2n, out);
     else
-        hipLaunchKernelGGL((tb_mfma_kernel<HT, LOG2N, false>), grid, dim3(kThreads), 0, stream, g,
+        hipLaunchKernelGGL((tb_mfma_kernel<HT, LOG2N, false, Out>), grid, dim3(kThreads), 0, stream, g,
                            a.mask, a.rows, a.log2n, out);
 }
 
 }  // namespace
 
 // Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
-// Covered: bf16 in and out, rows of 512, 1024, 2048, 4096 or 5632 elements, and a Hadamard block of
-// at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row.
+// Covered: bf16 in, rows of 512, 1024, 2048, 4096 or 5632 elements; bf16 out with a Hadamard block
+// of at most 32, or 128, 512, 1024, 2048, 4096 where it divides the row; fp32 out (a weight gradient
+// for an fp32 optimizer) with the row's widest block.
 bool launch_trust_backward_mfma(const BackwardArgs &a, hipStream_t stream)
 {
-    if (a.g_dtype != QUEST_BF16 || a.out_dtype != QUEST_BF16 || (a.cols % 512) != 0)
+    if (a.g_dtype != QUEST_BF16 || (a.cols % 512) != 0)
         return false;
     const int ht = (int)(a.cols / 512);
     const int l = a.log2n <= 5 ? 5 : a.log2n;
+    if (a.out_dtype != QUEST_BF16) {
+#define QUEST_F32_OUT_CASE(HT_, L_)                \
+    if (ht == HT_ && l == L_) {                    \
+        launch<HT_, L_, float>(a, stream);         \
+        return true;                               \
+    }
+        QUEST_F32_OUT_CASE(1, 9) QUEST_F32_OUT_CASE(2, 10) QUEST_F32_OUT_CASE(4, 11) QUEST_F32_OUT_CASE(8, 12)
+        QUEST_F32_OUT_CASE(11, 9)
+#undef QUEST_F32_OUT_CASE
+        return false;
+    }
 #define QUEST_CASE(HT_, L_)                       \
     if (ht == HT_ && l == L_) {                   \
         launch<HT_, L_>(a, stream);               \

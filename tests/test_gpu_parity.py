@@ -58,6 +58,9 @@ QUANT_CASES = [
     (70, 5632, 512, 1, "bf16"), (70, 5632, 512, 2, "bf16"), (70, 5632, 512, 3, "bf16"), (70, 5632, 512, 8, "bf16"),
     (9, 1024, 1024, 1, "bf16"), (9, 1024, 1024, 2, "bf16"), (9, 1024, 1024, 3, "bf16"), (9, 1024, 1024, 8, "bf16"),
     (5, 4096, 4096, 1, "bf16"), (5, 4096, 4096, 2, "bf16"), (5, 4096, 4096, 3, "bf16"), (5, 4096, 4096, 8, "bf16"),
+    # fp32 rows on the matrix-core path (fp32 MFMA): rows of 512 .. 5632 with their widest block
+    (21, 512, 512, 4, "f32"), (37, 1024, 1024, 4, "f32"), (130, 2048, 2048, 4, "f32"), (9, 4096, 4096, 4, "f32"),
+    (70, 5632, 512, 4, "f32"),
 ]
 
 
@@ -67,11 +70,39 @@ def test_quantizer_matches_oracle(rows, cols, n, bits, dtype):
     got = gpu_quantize(x, n, bits)
     ref = qo.hadamard_quantize(x, n, bits, dense=(n <= 512))
     compare_quantizer(got, ref, cols, bits)
+    # inference form (no mask, no debug output): another kernel instance, the same codes and scales
+    lean = gpu_quantize(x, n, bits, want_mask=False, want_xh=False)
+    assert np.array_equal(lean["codes"], got["codes"]) and np.array_equal(lean["scales"], got["scales"])
+
+
+@pytest.mark.parametrize("cols,n", [(512, 512), (1024, 1024), (2048, 2048), (4096, 4096), (5632, 512)])
+def test_fp32_rows_keep_all_24_bits(cols, n):
+    """fp32 rows reach the matrix cores as three bf16 pieces: rows whose entries are +-v in the
+    pattern of one Hadamard row, with v using all 24 significant bits, must come out as sqrt(n) v at
+    that row's index and zero elsewhere, to fp32 rounding (a lost or mis-signed piece is 2^-16 or more)."""
+    values = [1.0 + 2.0 ** -8 + 2.0 ** -16 + 2.0 ** -23, 3.0 - 2.0 ** -22, 0.7499999403953552, 1.0 + 2.0 ** -20]
+    picks = [0, 1, n - 1, n // 2 + 3, 37 % n, n // 4]
+    rows = len(values) * len(picks)
+    x = np.empty((rows, cols), dtype=np.float32)
+    j = np.arange(cols)
+    expect = np.zeros((rows, cols))
+    for a, v in enumerate(values):
+        for b, r in enumerate(picks):
+            parity = np.array([bin(int(r) & int(c % n)).count("1") & 1 for c in j])
+            x[a * len(picks) + b] = np.float32(v) * (1.0 - 2.0 * parity)
+            expect[a * len(picks) + b, r::n] = np.sqrt(n) * float(np.float32(v))
+    got = gpu_quantize(x, n, 4)
+    bound = 3e-7 * np.sqrt(n) * np.abs(x[:, :1]).astype(np.float64)
+    assert np.all(np.abs(got["xh"].astype(np.float64) - expect) <= bound)
 
 
 ABSMAX_CASES = [(37, 1024, 128, 4, "bf16"), (130, 2048, 2048, 4, "bf16"), (70, 5632, 512, 4, "bf16"),
                 (33, 2048, 1, 4, "bf16"), (33, 2048, 2048, 2, "bf16"), (33, 2048, 2048, 8, "f32"),
-                (19, 512, 1, 3, "f32"), (21, 1536, 512, 1, "f32"), (4100, 256, 256, 4, "bf16")]
+                (19, 512, 1, 3, "f32"), (21, 1536, 512, 1, "f32"), (4100, 256, 256, 4, "bf16"),
+                # the matrix-core path, bf16 and fp32 rows
+                (21, 512, 512, 4, "bf16"), (37, 1024, 1024, 4, "bf16"), (9, 4096, 4096, 4, "bf16"),
+                (21, 512, 512, 4, "f32"), (37, 1024, 1024, 4, "f32"), (130, 2048, 2048, 4, "f32"),
+                (9, 4096, 4096, 4, "f32"), (70, 5632, 512, 4, "f32")]
 
 
 @pytest.mark.parametrize("rows,cols,n,bits,dtype", ABSMAX_CASES)
@@ -86,6 +117,8 @@ def test_absmax_quantizer_matches_oracle(rows, cols, n, bits, dtype):
     assert np.all(got["mask"] == 0xFF)
     assert got["scales"][2] == 0.0
     assert np.all(qo.unpack_odd(got["codes"][2:3], cols, bits) == 1)
+    lean = gpu_quantize(x, n, bits, absmax=True, want_mask=False, want_xh=False)
+    assert np.array_equal(lean["codes"], got["codes"]) and np.array_equal(lean["scales"], got["scales"])
 
 
 def test_transform_and_gaussian_clip_each_reduce_the_error():
@@ -330,7 +363,13 @@ BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16")
               (19, 512, 1, "f32", "f32"), (5, 16384, 16384, "bf16", "bf16"), (300, 64, 64, "f32", "bf16"),
               (1, 8, 2, "f32", "f32"), (70, 5632, 512, "bf16", "bf16"), (33, 4096, 4096, "bf16", "bf16"),
               (20, 512, 32, "bf16", "bf16"), (16, 2048, 1, "bf16", "bf16"), (9, 1024, 1024, "bf16", "bf16"),
-              (6, 512, 512, "bf16", "bf16"), (11, 2048, 8, "bf16", "bf16")]
+              (6, 512, 512, "bf16", "bf16"), (11, 2048, 8, "bf16", "bf16"),
+              # fp32 on either side of the matrix-core path
+              (6, 512, 512, "f32", "f32"), (6, 512, 512, "bf16", "f32"), (6, 512, 512, "f32", "bf16"),
+              (37, 1024, 1024, "f32", "f32"), (37, 1024, 1024, "bf16", "f32"), (37, 1024, 1024, "f32", "bf16"),
+              (130, 2048, 2048, "f32", "f32"), (130, 2048, 2048, "bf16", "f32"), (130, 2048, 2048, "f32", "bf16"),
+              (9, 4096, 4096, "f32", "f32"), (9, 4096, 4096, "bf16", "f32"), (9, 4096, 4096, "f32", "bf16"),
+              (70, 5632, 512, "f32", "f32"), (70, 5632, 512, "f32", "bf16")]
 
 
 @pytest.mark.parametrize("rows,cols,n,gd,od", BACK_CASES)
