@@ -16,7 +16,8 @@
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer unless the comment says "host".  The caller owns
  *     all buffers; the library allocates nothing, frees nothing and never synchronises (the one
- *     exception, quest_grad_gemm's scratch memory, is described there): a call validates its
+ *     exception, the device memory it keeps for the gradient matmuls and for 1- and 2-bit
+ *     matmuls, is described at quest_grad_gemm): a call validates its
  *     arguments on the host and enqueues kernels on `stream` (a hipStream_t passed as void*,
  *     NULL = the default stream).
  *   - Errors are return codes.  On any code other than QUEST_OK nothing was launched.
@@ -125,6 +126,9 @@ float quest_alpha_star_fp4(void);
  *   y        out bf16 [M, ld_y], ld_y >= N (row stride in elements);  may be NULL if acc_out is given
  *   acc_out  out int32 [M, N] raw accumulators, or NULL (NULL in production)
  * M = 0 or N = 0 is a no-op.  Code pointers must be 16-byte aligned.
+ * bits = 1 or 2 with M >= 512, N >= 256 and K a multiple of 128: both operands are first re-coded
+ * as 4-bit codes of the same odd integers, into the library-owned device memory described at
+ * quest_grad_gemm (same consequences), and multiplied by the 4-bit kernel.
  */
 quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,
                                const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
@@ -170,7 +174,8 @@ quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint
  * (hipMalloc) or grown on the first call that needs the size and kept until the process ends.
  * Consequences: calls on one device must not overlap (issue them to one stream); a call that has
  * to grow the buffer synchronises the device and cannot be captured into a graph; an allocation
- * failure is reported as QUEST_ERR_LAUNCH.  All other entry points allocate nothing.
+ * failure is reported as QUEST_ERR_LAUNCH.  The entry points that use this memory say so; all
+ * others allocate nothing.
  */
 quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_codes,
                              const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,

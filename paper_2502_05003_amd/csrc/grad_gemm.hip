@@ -6,7 +6,6 @@
 // and, with the same machinery, the weight-only forward product (Sec. 4.4):
 //   which = 2:  out[M, N] = x[M, K]    * what_h[N, K]^T (contraction over K)
 #include <algorithm>
-#include <mutex>
 #include <numeric>
 #include <utility>
 
@@ -550,40 +549,6 @@ __global__ __launch_bounds__(256) void grad_gemm_fixup_kernel(const float4 *__re
         const uint4 v = *reinterpret_cast<const uint4 *>(park + prow * 256 + ((c ^ (prow & 15)) << 4));
         *reinterpret_cast<uint4 *>(out_base + (int64_t)prow * K + c * 8) = v;
     }
-}
-
-/*
- * Device memory for the expanded operand and the partial tiles, one buffer per device, grown on
- * demand and kept until the process ends.  All launches of the main path on a device share it, so
- * they must not overlap (they do not when issued to one stream).  Growing frees the old buffer
- * after a device synchronisation.
- */
-hipError_t library_memory(int device, size_t bytes, char **out_ptr)
-{
-    constexpr int kMaxDevices = 64;
-    static std::mutex guard;
-    static void *buffer[kMaxDevices] = {};
-    static size_t capacity[kMaxDevices] = {};
-    if (device < 0 || device >= kMaxDevices)
-        return hipErrorInvalidDevice;
-    std::lock_guard<std::mutex> lock(guard);
-    if (capacity[device] < bytes) {
-        if (buffer[device] != nullptr) {
-            hipError_t err = hipDeviceSynchronize();
-            if (err == hipSuccess)
-                err = hipFree(buffer[device]);
-            if (err != hipSuccess)
-                return err;
-            buffer[device] = nullptr;
-            capacity[device] = 0;
-        }
-        hipError_t err = hipMalloc(&buffer[device], bytes);
-        if (err != hipSuccess)
-            return err;
-        capacity[device] = bytes;
-    }
-    *out_ptr = static_cast<char *>(buffer[device]);
-    return hipSuccess;
 }
 
 }  // namespace

@@ -728,12 +728,71 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// b = 1 and b = 2 on the tile kernels: the codes are first re-coded into nibbles that stand for the
+// same odd integers on the 4-bit grid (u = 2c - (L - 1) = 2(c + (16 - L) / 2) - 15), sixteen codes
+// per thread, into library-owned memory; the accumulators are unchanged.
+// ------------------------------------------------------------------------------------------
+template <int CB>
+__global__ __launch_bounds__(256) void recode_to_nibbles_kernel(const uint8_t *__restrict__ in,
+                                                                uint2 *__restrict__ out, int64_t groups)
+{
+    static_assert(CB == 1 || CB == 2, "containers narrower than a nibble");
+    constexpr uint32_t kField = (1u << CB) - 1u, kOffset = (16u - (1u << CB)) / 2u;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t w = CB == 2 ? reinterpret_cast<const uint32_t *>(in)[g]
+                                   : (uint32_t) reinterpret_cast<const uint16_t *>(in)[g];
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            lo |= (((w >> (CB * j)) & kField) + kOffset) << (4 * j);
+            hi |= (((w >> (CB * (j + 8))) & kField) + kOffset) << (4 * j);
+        }
+        out[g] = make_uint2(lo, hi);
+    }
+}
+
+hipError_t launch_recode(const uint8_t *in, uint8_t *out, int64_t rows, int64_t K, int cb, hipStream_t stream)
+{
+    const int64_t groups = rows * K / 16;
+    const int64_t blocks = (groups + 255) / 256;
+    const dim3 grid((unsigned)(blocks < 8192 ? blocks : 8192));
+    if (cb == 2)
+        hipLaunchKernelGGL(recode_to_nibbles_kernel<2>, grid, dim3(256), 0, stream, in,
+                           reinterpret_cast<uint2 *>(out), groups);
+    else
+        hipLaunchKernelGGL(recode_to_nibbles_kernel<1>, grid, dim3(256), 0, stream, in,
+                           reinterpret_cast<uint2 *>(out), groups);
+    return hipGetLastError();
+}
+
 }  // namespace
 
-hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream)
+hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
 {
-    if (a.M == 0 || a.N == 0)
+    if (args.M == 0 || args.N == 0)
         return hipSuccess;
+    GemmArgs a = args;
+    if (a.bits <= 2 && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
+        int device = 0;
+        char *memory = nullptr;
+        hipError_t err = hipGetDevice(&device);
+        if (err == hipSuccess)
+            err = library_memory(device, (size_t)((a.M + a.N) * a.K / 2), &memory);
+        uint8_t *a_nibbles = reinterpret_cast<uint8_t *>(memory);
+        uint8_t *b_nibbles = a_nibbles + a.M * a.K / 2;
+        if (err == hipSuccess)
+            err = launch_recode(a.a_codes, a_nibbles, a.M, a.K, a.cb, stream);
+        if (err == hipSuccess)
+            err = launch_recode(a.b_codes, b_nibbles, a.N, a.K, a.cb, stream);
+        if (err != hipSuccess)
+            return err;
+        a.a_codes = a_nibbles;
+        a.b_codes = b_nibbles;
+        a.bits = 4;
+        a.cb = 4;
+    }
     const int levels = 1 << a.bits;
     auto *y = static_cast<uint16_t *>(a.y);
     if ((a.bits == 4 || a.bits == 3) && (a.K % WTK) == 0 && a.K >= 4096 && a.M >= 512 && a.N >= 512) {

@@ -96,6 +96,41 @@ hipError_t allow_dynamic_lds(const void *kernel, int bytes)
     return err;
 }
 
+/*
+ * Device memory the library owns (the expanded operand and the partial tiles of the gradient
+ * matmuls, re-coded operands of the 1- and 2-bit matmul): one buffer per device, grown on demand
+ * and kept until the process ends.  All launches that use it on a device share it, so they must
+ * not overlap (they do not when issued to one stream).  Growing frees the old buffer after a
+ * device synchronisation.
+ */
+hipError_t library_memory(int device, size_t bytes, char **out_ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void *buffer[kMaxDevices] = {};
+    static size_t capacity[kMaxDevices] = {};
+    if (device < 0 || device >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    if (capacity[device] < bytes) {
+        if (buffer[device] != nullptr) {
+            hipError_t err = hipDeviceSynchronize();
+            if (err == hipSuccess)
+                err = hipFree(buffer[device]);
+            if (err != hipSuccess)
+                return err;
+            buffer[device] = nullptr;
+            capacity[device] = 0;
+        }
+        hipError_t err = hipMalloc(&buffer[device], bytes);
+        if (err != hipSuccess)
+            return err;
+        capacity[device] = bytes;
+    }
+    *out_ptr = static_cast<char *>(buffer[device]);
+    return hipSuccess;
+}
+
 }  // namespace quest
 
 extern "C" {

@@ -86,6 +86,10 @@ struct GradGemmArgs {
 
 hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream);
 
+// Library-owned device memory of at least `bytes` on `device` (one buffer per device, grown on
+// demand with hipMalloc after a device synchronisation, never shrunk): users on one device share it.
+hipError_t library_memory(int device, size_t bytes, char **out_ptr);
+
 // Raise the dynamic LDS limit of `kernel` to `bytes` on the current device.  The attribute is set
 // once per (kernel, device, size) and remembered; safe to call from several host threads.
 hipError_t allow_dynamic_lds(const void *kernel, int bytes);

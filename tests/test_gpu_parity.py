@@ -241,7 +241,10 @@ GEMM_CASES = [(256, 512, 512, 4), (130, 200, 1024, 4), (1, 1, 64, 4), (257, 129,
               # more tiles than the chip holds at once, ragged last tile row and column, one step only
               (4096, 4090, 256, 4), (4096, 4096, 128, 4), (4000, 4100, 384, 4),
               # b = 3 on the tile kernels (one more shift in the widening, products carry 256)
-              (700, 600, 512, 3), (768, 512, 5632, 3), (513, 1025, 1024, 3)]
+              (700, 600, 512, 3), (768, 512, 5632, 3), (513, 1025, 1024, 3),
+              # b = 1, 2 re-coded to nibbles for the tile kernels (and for the wide one at K = 5632)
+              (700, 600, 512, 2), (513, 1025, 1024, 1), (768, 512, 5632, 2), (768, 512, 5632, 1),
+              (4000, 4100, 384, 1), (512, 256, 128, 2)]
 
 
 @pytest.mark.parametrize("M,N,K,bits", GEMM_CASES)
