@@ -170,6 +170,63 @@ def library_gemm_us(torch, dev, M, N, K, reps=20):
     return out
 
 
+# Linear layers of the 1.6B model the paper trained and of the proportionally scaled 7B model its
+# per-layer figure also shows (Sec. 5, "Runtime Results"): name, K (inputs), N (outputs).
+SWEEP_LAYERS = [("1.6B attention 2048->2048", 2048, 2048), ("1.6B up/gate 2048->5632", 2048, 5632),
+                ("1.6B down 5632->2048", 5632, 2048), ("7B attention 4096->4096", 4096, 4096),
+                ("7B up/gate 4096->11008", 4096, 11008), ("7B down 11008->4096", 11008, 4096)]
+
+
+def layer_sweep(torch, q, synth, dev, tokens, reps=10):
+    """Per-layer forward time of the 4-bit path against the 16-bit product (the paper's per-layer
+    speedup figure, Sec. 5): activations quantized per call with and without the Hadamard transform
+    (no mask: inference form), weights quantized beforehand, the vendor library's bf16 product as
+    the baseline.  Microseconds per launch, launched back to back over rotating buffer sets."""
+    def timed(launches):
+        for f in launches:
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(reps):
+            launches[i % len(launches)]()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / reps
+
+    out = []
+    for name, K, N in SWEEP_LAYERS:
+        n = K & -K                                  # widest power-of-two block that divides the row
+        n_sets = max(2, min(4, int(1.5e9 // (tokens * (K + N) * 2))))
+        w_bits = synth.gaussian(N, K, 0.02, seed=1)
+        w = torch.from_numpy(w_bits.view("int16")).to(dev).view(torch.bfloat16)
+        w_codes = torch.empty(N, K // 2, dtype=torch.uint8, device=dev)
+        w_scales = torch.empty(N, dtype=torch.float32, device=dev)
+        q.quest_hadamard_quantize(w, n, 4, codes=w_codes, scales=w_scales)
+        x_bits = synth.outlier_activations(tokens, K, 0.005, 50.0, seed=0)
+        xs = [torch.from_numpy(x_bits.view("int16")).to(dev).view(torch.bfloat16) for _ in range(n_sets)]
+        codes = [torch.empty(tokens, K // 2, dtype=torch.uint8, device=dev) for _ in range(n_sets)]
+        scales = [torch.empty(tokens, dtype=torch.float32, device=dev) for _ in range(n_sets)]
+        ys = [torch.empty(tokens, N, dtype=torch.bfloat16, device=dev) for _ in range(n_sets)]
+
+        def quantize(i, block):
+            return lambda: q.quest_hadamard_quantize(xs[i], block, 4, codes=codes[i], scales=scales[i])
+
+        t_q = timed([quantize(i, n) for i in range(n_sets)])
+        t_q_plain = timed([quantize(i, 1) for i in range(n_sets)])
+        for i in range(n_sets):
+            quantize(i, n)()
+        t_gemm = timed([(lambda i=i: q.quest_lowbit_gemm(codes[i], scales[i], w_codes, w_scales, K, 4, y=ys[i]))
+                        for i in range(n_sets)])
+        t_bf16 = timed([(lambda i=i: torch.matmul(xs[i], w.t(), out=ys[i])) for i in range(n_sets)])
+        out.append({"layer": name, "tokens": tokens, "K": K, "N": N, "had_block": n,
+                    "quantize_us": t_q, "quantize_no_transform_us": t_q_plain, "gemm_int4_us": t_gemm,
+                    "matmul_bf16_library_us": t_bf16,
+                    "speedup_with_transform": t_bf16 / (t_q + t_gemm),
+                    "speedup_without_transform": t_bf16 / (t_q_plain + t_gemm)})
+        del xs, codes, scales, ys, w, w_codes, w_scales
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -191,6 +248,11 @@ def main():
                     help="also time the vendor library (torch.matmul bf16, torch._int_mm int8) on this "
                          "workload's three matrix products, operands already in the library's own format: "
                          "context for the kernels' rooflines, not part of the step")
+    ap.add_argument("--layer-sweep", action="store_true",
+                    help="instead of the benchmark step: forward time of the 4-bit path per linear-layer "
+                         "shape of the 1.6B and 7B models against the library's bf16 product (the paper's "
+                         "per-layer speedup figure); prints one JSON line of its own")
+    ap.add_argument("--tokens", type=int, default=16384, help="rows of the activations in --layer-sweep")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (one MI355X per box); run with --gpus 1")
@@ -207,6 +269,10 @@ def main():
     q.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.layer_sweep:
+        print(json.dumps({"layer_sweep": layer_sweep(torch, q, synth, dev, args.tokens)}))
+        return
 
     x_bits, w_bits, cfg = synth.make_config(args.workload, seed=0)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]

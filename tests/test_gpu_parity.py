@@ -61,6 +61,8 @@ QUANT_CASES = [
     # fp32 rows on the matrix-core path (fp32 MFMA): rows of 512 .. 5632 with their widest block
     (21, 512, 512, 4, "f32"), (37, 1024, 1024, 4, "f32"), (130, 2048, 2048, 4, "f32"), (9, 4096, 4096, 4, "f32"),
     (70, 5632, 512, 4, "f32"),
+    # rows of 11008 = 43 x 256 (the last 1024-element tile is three quarters full)
+    (70, 11008, 256, 4, "bf16"), (33, 11008, 128, 4, "bf16"), (33, 11008, 16, 4, "bf16"), (5, 11008, 1, 4, "bf16"),
 ]
 
 
@@ -372,7 +374,9 @@ BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16")
               (37, 1024, 1024, "f32", "f32"), (37, 1024, 1024, "bf16", "f32"), (37, 1024, 1024, "f32", "bf16"),
               (130, 2048, 2048, "f32", "f32"), (130, 2048, 2048, "bf16", "f32"), (130, 2048, 2048, "f32", "bf16"),
               (9, 4096, 4096, "f32", "f32"), (9, 4096, 4096, "bf16", "f32"), (9, 4096, 4096, "f32", "bf16"),
-              (70, 5632, 512, "f32", "f32"), (70, 5632, 512, "f32", "bf16")]
+              (70, 5632, 512, "f32", "f32"), (70, 5632, 512, "f32", "bf16"),
+              # rows of 11008 = 43 x 256
+              (70, 11008, 256, "bf16", "bf16"), (33, 11008, 128, "bf16", "bf16"), (9, 11008, 4, "bf16", "bf16")]
 
 
 @pytest.mark.parametrize("rows,cols,n,gd,od", BACK_CASES)
