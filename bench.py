@@ -182,15 +182,23 @@ def layer_sweep(torch, q, synth, dev, tokens, reps=10):
     speedup figure, Sec. 5): activations quantized per call with and without the Hadamard transform
     (no mask: inference form), weights quantized beforehand, the vendor library's bf16 product as
     the baseline.  Microseconds per launch, launched back to back over rotating buffer sets."""
+    # A millisecond of other GPU work goes first, so that the host has queued all timed launches
+    # before the first of them starts: short kernels are then timed back to back on the GPU, not
+    # at the rate the host can issue them.
+    filler = [torch.zeros(8192, 8192, dtype=torch.bfloat16, device=dev) for _ in range(3)]
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
     def timed(launches):
         for f in launches:
             f()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
+        torch.matmul(filler[0], filler[1], out=filler[2])
+        start.record()
         for i in range(reps):
             launches[i % len(launches)]()
+        end.record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e6 / reps
+        return start.elapsed_time(end) * 1e3 / reps
 
     out = []
     for name, K, N in SWEEP_LAYERS:

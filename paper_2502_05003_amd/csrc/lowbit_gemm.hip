@@ -795,7 +795,10 @@ hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
     }
     const int levels = 1 << a.bits;
     auto *y = static_cast<uint16_t *>(a.y);
-    if ((a.bits == 4 || a.bits == 3) && (a.K % WTK) == 0 && a.K >= 4096 && a.M >= 512 && a.N >= 512) {
+    // the wide kernel runs one workgroup per CU: it needs about a round of 256 x 256 tiles to fill the chip
+    const int64_t wide_tiles = ((a.M + WTM - 1) / WTM) * ((a.N + WTN - 1) / WTN);
+    if ((a.bits == 4 || a.bits == 3) && (a.K % WTK) == 0 && a.K >= 4096 && a.M >= 512 && a.N >= 512 &&
+        wide_tiles >= 192) {
         const int tiles_m = (int)((a.M + WTM - 1) / WTM), tiles_n = (int)((a.N + WTN - 1) / WTN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
         hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<4>), kWideLds);
