@@ -27,7 +27,8 @@ BF16_PEAK_TFLOPS = 2500.0    # dense bf16 MFMA
 FP4_PEAK_TOPS = 10100.0      # dense FP4 MFMA (--grid fp4)
 
 WORKLOAD = "mlp_up_1p6b"     # the headline: X 16384x2048, W 5632x2048, Hadamard block 2048, b = 4
-WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b")   # down: X 16384x5632, W 2048x5632, block 512
+# down: X 16384x5632, W 2048x5632, block 512; the 7B pair: 4096 -> 11008 (block 4096) and back (block 256)
+WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b", "mlp_up_7b", "mlp_down_7b")
 KERNELS = ("quantize_x", "quantize_w", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w",
            "trust_backward_x", "trust_backward_w")
 FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the forward (--only)

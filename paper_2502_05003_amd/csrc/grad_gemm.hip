@@ -212,8 +212,10 @@ __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__rest
 // for grad_gemm_fixup_kernel to add up.  A slot is [wave][accumulator quad 0..63][lane] float4.
 //
 // Workgroups that are phase_period apart in that order walk through their tiles at the same
-// contraction position all the time, and with column-major tile order they tend to work on tiles
-// of one tile-row or tile-column, that is on the same operand rows at the same moment.  Such
+// contraction position all the time, and with the tiles numbered along the longer side of the tile
+// grid (a run of neighbours shares one operand panel, and the longer the run, the more often two
+// such workgroups fall into the same one) they tend to work on tiles of one tile-row or
+// tile-column, that is on the same operand rows at the same moment.  Such
 // workgroups are placed on one XCD (hardware deals workgroup ids out to the eight XCDs in turn) so
 // that they share the fetch through that XCD's L2.  phase_period = 0: whole tiles, all in phase.
 constexpr int kSlotQuads = 4 * 64 * 64;   // float4 per partial tile (256 KiB)
@@ -221,9 +223,14 @@ constexpr int kSlotQuads = 4 * 64 * 64;   // float4 per partial tile (256 KiB)
 __device__ __forceinline__ void tile_origin(int tile, int tiles_r, int tiles_k, int phase_period, int &r0,
                                             int &k0)
 {
-    if (phase_period != 0) {   // split tiles: plain column-major order
-        r0 = (tile % tiles_r) * GT;
-        k0 = (tile / tiles_r) * GT;
+    if (phase_period != 0) {   // split tiles: plain order along the longer side of the tile grid
+        if (tiles_k > tiles_r) {
+            r0 = (tile / tiles_k) * GT;
+            k0 = (tile % tiles_k) * GT;
+        } else {
+            r0 = (tile % tiles_r) * GT;
+            k0 = (tile / tiles_r) * GT;
+        }
         return;
     }
     // four tile-rows deep, column by column: neighbours in the order share operand rows in L2

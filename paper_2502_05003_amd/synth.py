@@ -64,7 +64,7 @@ def student_t_activations(rows: int, cols: int, nu: float, seed: int,
     return _store(x, dtype)
 
 
-# The five workload configurations: name -> dict of recipe parameters.
+# The workload configurations: name -> dict of recipe parameters.
 CONFIGS = {
     "tiny": dict(M=256, K=512, N=512, had_block=512, bits=4, dtype="f32"),
     "mlp_up_100m": dict(M=8192, K=1024, N=4096, had_block=1024, bits=4, dtype="bf16",
@@ -74,6 +74,11 @@ CONFIGS = {
                         outlier_frac=0.005, outlier_gain=50.0),
     "mlp_down_1p6b": dict(M=16384, K=5632, N=2048, had_block=512, bits=4, dtype="bf16",
                           outlier_frac=0.005, outlier_gain=50.0),
+    # the proportionally scaled 7B model of the paper's per-layer runtime figure (hidden 4096, MLP 11008)
+    "mlp_up_7b": dict(M=16384, K=4096, N=11008, had_block=4096, bits=4, dtype="bf16",
+                      outlier_frac=0.005, outlier_gain=50.0),
+    "mlp_down_7b": dict(M=16384, K=11008, N=4096, had_block=256, bits=4, dtype="bf16",
+                        outlier_frac=0.005, outlier_gain=50.0),
 }
 
 
