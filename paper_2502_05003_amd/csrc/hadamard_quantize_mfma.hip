@@ -9,7 +9,7 @@
 // (exact products, fp32 accumulation: the same roundings as a butterfly network), and they cost
 // four MFMA instructions per row instead of 160 vector instructions.
 //
-// Data flow, one wavefront per row of 256 * Q elements:
+// Data flow, one wavefront per row of 128 * U elements:
 //   * the row is cut into tiles of 1024 elements seen as 32 x 32 matrices X[p][q] (element
 //     32 p + q); lane (m = l & 31, h = l >> 5) loads the 32 contiguous bytes of row p = m that
 //     hold q = 16 h .. 16 h + 15, which is exactly its share of the MFMA A operand;
@@ -145,7 +145,7 @@ struct TransposePlan {
 };
 
 /*
- * Q: row length / 256.  LOG2N: log2 of the Hadamard block when it is >= 32; 5 also stands for
+ * U: row length / 128.  LOG2N: log2 of the Hadamard block when it is >= 32; 5 also stands for
  * every smaller block (then only the MFMA operand differs, and `log2n` carries the true value).
  * FP4: the codes are E2M1 values of 6 x_h / (alpha rms) (Sec. 4.4 "The FP4 Format"), made by the
  * hardware conversion (nearest, ties to even, saturating, sign kept on underflow), and the scale
@@ -157,29 +157,29 @@ struct TransposePlan {
  * In: uint16_t (bf16 bits) or float.  ABSMAX: the grid spans the row's largest |x_h| instead of
  * alpha rms (the comparison quantizer of Sec. 4.1); nothing is clipped, every element is trusted.
  */
-// Waves per SIMD the register budget is set for.  Holding a long row (4 Q transformed values per
+// Waves per SIMD the register budget is set for.  Holding a long row (2 U transformed values per
 // lane, next to the fp32 inputs still on their way) needs more than the 128 registers of four waves,
 // and so do the packed inputs of a row of 11008.
-template <int Q, bool HOLD_ALL, bool F32>
+template <int U, bool HOLD_ALL, bool F32>
 constexpr int hq_waves_per_eu()
 {
-    return (HOLD_ALL && (Q > 16 || (F32 && Q == 16))) ? 2 : Q > 32 ? 3 : QUEST_HQ_WAVES_PER_EU;
+    return (HOLD_ALL && (U > 32 || (F32 && U == 32))) ? 2 : U > 64 ? 3 : QUEST_HQ_WAVES_PER_EU;
 }
 
-template <int Q, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4, typename In = uint16_t,
+template <int U, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4, typename In = uint16_t,
           bool ABSMAX = false>
 __global__ __launch_bounds__(kThreads)
-__attribute__((amdgpu_waves_per_eu(hq_waves_per_eu<Q, (sizeof(In) == 4 || ABSMAX), sizeof(In) == 4>())))
+__attribute__((amdgpu_waves_per_eu(hq_waves_per_eu<U, (sizeof(In) == 4 || ABSMAX), sizeof(In) == 4>())))
 void hq_mfma_kernel(
     const In *__restrict__ x, int64_t rows, int64_t ld, int log2n, float alpha,
     float trust_edge, uint8_t *__restrict__ codes, float *__restrict__ scales,
     uint8_t *__restrict__ mask, float *__restrict__ xh_out)
 {
-    constexpr int T = (Q + 3) / 4;         // tiles of 1024 elements; the last one may be partial
-    constexpr int NI = 4 * Q;              // elements per lane
-    constexpr int cols = 256 * Q;
-    // rows p of the last tile that exist (the row ends after a quarter, half or three quarters of it)
-    constexpr int kTailRows = (Q % 4) ? 8 * (Q % 4) : 32;
+    constexpr int T = (U + 7) / 8;         // tiles of 1024 elements; the last one may be partial
+    constexpr int NI = 2 * U;              // elements per lane
+    constexpr int cols = 128 * U;
+    // rows p of the last tile that exist (the row may end after any eighth of it)
+    constexpr int kTailRows = (U % 8) ? 4 * (U % 8) : 32;
     constexpr bool kF32 = sizeof(In) == 4;
     constexpr bool kHoldAll = kF32 || ABSMAX;
     static_assert(!kHoldAll || (!FP4 && BITS == 4), "fp32 rows and AbsMax: 4-bit integer grid only");
@@ -189,7 +189,7 @@ void hq_mfma_kernel(
     constexpr int kLevels = 1 << BITS;
     constexpr int CB = BITS == 3 ? 4 : BITS;   // container bits
     static_assert(!FP4 || BITS == 4, "the E2M1 grid has 4-bit codes");
-    static_assert((Q % 2) == 0 || (BITS == 3 || BITS == 4), "rows ending on a quarter tile: nibble codes only");
+    static_assert((U % 4) == 0 || (BITS == 3 || BITS == 4), "rows that do not end on half a tile: nibble codes only");
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
@@ -634,7 +634,7 @@ void hq_mfma_kernel(
     }
 }
 
-template <int Q, int LOG2N, bool FP4 = false, int BITS = 4, typename In = uint16_t, bool ABSMAX = false>
+template <int U, int LOG2N, bool FP4 = false, int BITS = 4, typename In = uint16_t, bool ABSMAX = false>
 void launch(const QuantizeArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -642,11 +642,11 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *x = static_cast<const In *>(a.x);
     if (a.mask)
-        hipLaunchKernelGGL((hq_mfma_kernel<Q, LOG2N, true, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
+        hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, true, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
                            stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
     else
-        hipLaunchKernelGGL((hq_mfma_kernel<Q, LOG2N, false, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
+        hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, false, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
                            stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
                            a.xh_out);
 }
@@ -654,71 +654,77 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
 }  // namespace
 
 // Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
-// Covered (Q = row length / 256):
+// Covered (U = row length / 128):
 //   bf16 rows, b = 4: rows of 512, 1024, 2048, 4096, 5632 or 11008 elements with a Hadamard block of
-//     at most 32, or 128, 256 (11008 only), 512, 1024, 2048, 4096 where it divides the row;
+//     at most 32, or 128, 256 (11008 only), 512, 1024, 2048, 4096 where it divides the row; the other
+//     hidden and MLP widths of the paper's model family (640, 768, 1280, 1664, 1792, 2816, 3584,
+//     4608) with a block of at most 32 or their widest one;
 //   bf16 rows, b = 1, 2, 3, 8 and the E2M1 grid: rows of 1024 .. 5632 with their widest block;
 //   fp32 rows and the AbsMax scale, b = 4: rows of 512 .. 5632 with their widest block.
 bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream)
 {
-    if ((a.cols % 256) != 0)
+    if ((a.cols % 128) != 0)
         return false;
-    const int q = (int)(a.cols / 256);
+    const int u = (int)(a.cols / 128);
     const int l = a.log2n <= 5 ? 5 : a.log2n;
     if (a.dtype == QUEST_F32 || a.mode == kQuantAbsMax) {   // the whole row is held before anything is rounded
         if (a.bits != 4 || a.mode == kQuantFp4)
             return false;
-#define QUEST_HOLD_CASE(Q_, L_)                                          \
-    if (q == Q_ && l == L_) {                                            \
+#define QUEST_HOLD_CASE(U_, L_)                                          \
+    if (u == U_ && l == L_) {                                            \
         if (a.dtype == QUEST_F32 && a.mode == kQuantAbsMax)              \
-            launch<Q_, L_, false, 4, float, true>(a, stream);            \
+            launch<U_, L_, false, 4, float, true>(a, stream);            \
         else if (a.dtype == QUEST_F32)                                   \
-            launch<Q_, L_, false, 4, float, false>(a, stream);           \
+            launch<U_, L_, false, 4, float, false>(a, stream);           \
         else                                                             \
-            launch<Q_, L_, false, 4, uint16_t, true>(a, stream);         \
+            launch<U_, L_, false, 4, uint16_t, true>(a, stream);         \
         return true;                                                     \
     }
-        QUEST_HOLD_CASE(2, 9) QUEST_HOLD_CASE(4, 10) QUEST_HOLD_CASE(8, 11) QUEST_HOLD_CASE(16, 12)
-        QUEST_HOLD_CASE(22, 9)
+        QUEST_HOLD_CASE(4, 9) QUEST_HOLD_CASE(8, 10) QUEST_HOLD_CASE(16, 11) QUEST_HOLD_CASE(32, 12)
+        QUEST_HOLD_CASE(44, 9)
 #undef QUEST_HOLD_CASE
         return false;
     }
     if (a.bits != 4) {   // the other widths of the Eq. 1 grid
         if (a.mode != kQuantRms)
             return false;
-#define QUEST_BITS_CASE(Q_, L_, B_)                    \
-    if (q == Q_ && l == L_ && a.bits == B_) {          \
-        launch<Q_, L_, false, B_>(a, stream);          \
+#define QUEST_BITS_CASE(U_, L_, B_)                    \
+    if (u == U_ && l == L_ && a.bits == B_) {          \
+        launch<U_, L_, false, B_>(a, stream);          \
         return true;                                   \
     }
-#define QUEST_BITS_CASES(Q_, L_) \
-    QUEST_BITS_CASE(Q_, L_, 1) QUEST_BITS_CASE(Q_, L_, 2) QUEST_BITS_CASE(Q_, L_, 3) QUEST_BITS_CASE(Q_, L_, 8)
-        QUEST_BITS_CASES(4, 10) QUEST_BITS_CASES(8, 11) QUEST_BITS_CASES(16, 12) QUEST_BITS_CASES(22, 9)
+#define QUEST_BITS_CASES(U_, L_) \
+    QUEST_BITS_CASE(U_, L_, 1) QUEST_BITS_CASE(U_, L_, 2) QUEST_BITS_CASE(U_, L_, 3) QUEST_BITS_CASE(U_, L_, 8)
+        QUEST_BITS_CASES(8, 10) QUEST_BITS_CASES(16, 11) QUEST_BITS_CASES(32, 12) QUEST_BITS_CASES(44, 9)
 #undef QUEST_BITS_CASES
 #undef QUEST_BITS_CASE
         return false;
     }
     if (a.mode == kQuantFp4) {   // the E2M1 grid
-#define QUEST_FP4_CASE(Q_, L_)                    \
-    if (q == Q_ && l == L_) {                     \
-        launch<Q_, L_, true>(a, stream);          \
+#define QUEST_FP4_CASE(U_, L_)                    \
+    if (u == U_ && l == L_) {                     \
+        launch<U_, L_, true>(a, stream);          \
         return true;                              \
     }
-        QUEST_FP4_CASE(4, 10) QUEST_FP4_CASE(8, 11) QUEST_FP4_CASE(16, 12) QUEST_FP4_CASE(22, 9)
+        QUEST_FP4_CASE(8, 10) QUEST_FP4_CASE(16, 11) QUEST_FP4_CASE(32, 12) QUEST_FP4_CASE(44, 9)
 #undef QUEST_FP4_CASE
         return false;
     }
-#define QUEST_CASE(Q_, L_)                        \
-    if (q == Q_ && l == L_) {                     \
-        launch<Q_, L_>(a, stream);                \
+#define QUEST_CASE(U_, L_)                        \
+    if (u == U_ && l == L_) {                     \
+        launch<U_, L_>(a, stream);                \
         return true;                              \
     }
-    QUEST_CASE(2, 5) QUEST_CASE(2, 7) QUEST_CASE(2, 9)
-    QUEST_CASE(4, 5) QUEST_CASE(4, 7) QUEST_CASE(4, 9) QUEST_CASE(4, 10)
-    QUEST_CASE(8, 5) QUEST_CASE(8, 7) QUEST_CASE(8, 9) QUEST_CASE(8, 10) QUEST_CASE(8, 11)
-    QUEST_CASE(16, 5) QUEST_CASE(16, 7) QUEST_CASE(16, 9) QUEST_CASE(16, 10) QUEST_CASE(16, 11) QUEST_CASE(16, 12)
-    QUEST_CASE(22, 5) QUEST_CASE(22, 7) QUEST_CASE(22, 9)
-    QUEST_CASE(43, 5) QUEST_CASE(43, 7) QUEST_CASE(43, 8)   // 11008 = 43 x 256: ends three quarters into a tile
+    QUEST_CASE(4, 5) QUEST_CASE(4, 7) QUEST_CASE(4, 9)
+    QUEST_CASE(8, 5) QUEST_CASE(8, 7) QUEST_CASE(8, 9) QUEST_CASE(8, 10)
+    QUEST_CASE(16, 5) QUEST_CASE(16, 7) QUEST_CASE(16, 9) QUEST_CASE(16, 10) QUEST_CASE(16, 11)
+    QUEST_CASE(32, 5) QUEST_CASE(32, 7) QUEST_CASE(32, 9) QUEST_CASE(32, 10) QUEST_CASE(32, 11) QUEST_CASE(32, 12)
+    QUEST_CASE(44, 5) QUEST_CASE(44, 7) QUEST_CASE(44, 9)
+    QUEST_CASE(86, 5) QUEST_CASE(86, 7) QUEST_CASE(86, 8)   // 11008 = 86 x 128: ends three quarters into a tile
+    // the other widths of the paper's models (hidden 640 .. 1664, MLP 1792 .. 4608): no transform / widest block
+    QUEST_CASE(5, 5) QUEST_CASE(5, 7) QUEST_CASE(6, 5) QUEST_CASE(6, 8) QUEST_CASE(10, 5) QUEST_CASE(10, 8)
+    QUEST_CASE(13, 5) QUEST_CASE(13, 7) QUEST_CASE(14, 5) QUEST_CASE(14, 8) QUEST_CASE(22, 5) QUEST_CASE(22, 8)
+    QUEST_CASE(28, 5) QUEST_CASE(28, 9) QUEST_CASE(36, 5) QUEST_CASE(36, 9)
 #undef QUEST_CASE
     return false;
 }

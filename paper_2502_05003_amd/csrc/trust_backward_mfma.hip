@@ -1,7 +1,7 @@
 // Matrix-core assisted trust-masked inverse Hadamard transform, bf16 in, bf16 or fp32 out (Algorithm 2,
 // out = IHT(M (.) g); Sec. 3.2 of arXiv 2502.05003).  Same data flow as the fused quantizer
 // (hadamard_quantize_mfma.hip), which see for the index bookkeeping:
-//   * one wavefront per row of 256 * Q elements, tiles of 1024 elements seen as 32 x 32 matrices;
+//   * one wavefront per row of 128 * U elements, tiles of 1024 elements seen as 32 x 32 matrices;
 //     lane (m = l & 31, h = l >> 5) loads the 32 contiguous bytes of tile row m holding columns
 //     16 h .. 16 h + 15 together with their 16 mask bits, and zeroes the untrusted bf16 values;
 //   * index bits 0..4 are transformed by one exact +-1 bf16 MFMA product per tile, the other stages
@@ -62,16 +62,16 @@ __device__ __forceinline__ uint32_t keep_trusted(uint32_t pair, uint32_t mask_bi
     return pair & __builtin_amdgcn_perm(hi, lo, 0x07060100u);   // low half from lo, high half from hi
 }
 
-template <int Q, int LOG2N, bool WITH_MASK, typename Out = uint16_t>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Q > 32 ? 2 : 4)))
+template <int U, int LOG2N, bool WITH_MASK, typename Out = uint16_t>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(U > 64 ? 2 : 4)))
 void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ mask, int64_t rows,
                     int log2n, Out *__restrict__ out)
 {
     constexpr bool kF32Out = sizeof(Out) == 4;
-    constexpr int T = (Q + 3) / 4;         // tiles of 1024 elements; the last one may be partial
-    constexpr int NI = 4 * Q;              // elements per lane
-    constexpr int cols = 256 * Q;
-    constexpr int kTailRows = (Q % 4) ? 8 * (Q % 4) : 32;   // rows of the last tile that exist
+    constexpr int T = (U + 7) / 8;         // tiles of 1024 elements; the last one may be partial
+    constexpr int NI = 2 * U;              // elements per lane
+    constexpr int cols = 128 * U;
+    constexpr int kTailRows = (U % 8) ? 4 * (U % 8) : 32;   // rows of the last tile that exist
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
@@ -223,7 +223,7 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
     }
 }
 
-template <int Q, int LOG2N, typename Out = uint16_t>
+template <int U, int LOG2N, typename Out = uint16_t>
 void launch(const BackwardArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -232,48 +232,53 @@ void launch(const BackwardArgs &a, hipStream_t stream)
     const auto *g = static_cast<const uint16_t *>(a.g);
     auto *out = static_cast<Out *>(a.out);
     if (a.mask)
-        hipLaunchKernelGGL((tb_mfma_kernel<Q, LOG2N, true, Out>), grid, dim3(kThreads), 0, stream, g,
+        hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, true, Out>), grid, dim3(kThreads), 0, stream, g,
                            a.mask, a.rows, a.log2n, out);
     else
-        hipLaunchKernelGGL((tb_mfma_kernel<Q, LOG2N, false, Out>), grid, dim3(kThreads), 0, stream, g,
+        hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, false, Out>), grid, dim3(kThreads), 0, stream, g,
                            a.mask, a.rows, a.log2n, out);
 }
 
 }  // namespace
 
 // Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
-// Covered (Q = row length / 256): bf16 in; bf16 out for rows of 512, 1024, 2048, 4096, 5632 or 11008
+// Covered (U = row length / 128): bf16 in; bf16 out for rows of 512, 1024, 2048, 4096, 5632 or 11008
 // elements with a Hadamard block of at most 32, or 128, 256 (11008 only), 512, 1024, 2048, 4096 where
-// it divides the row; fp32 out (a weight gradient for an fp32 optimizer) for rows of 512 .. 5632
-// with their widest block.
+// it divides the row, and for the other widths of the paper's model family (640, 768, 1280, 1664,
+// 1792, 2816, 3584, 4608) with a block of at most 32 or their widest one; fp32 out (a weight
+// gradient for an fp32 optimizer) for rows of 512 .. 5632 with their widest block.
 bool launch_trust_backward_mfma(const BackwardArgs &a, hipStream_t stream)
 {
-    if (a.g_dtype != QUEST_BF16 || (a.cols % 256) != 0)
+    if (a.g_dtype != QUEST_BF16 || (a.cols % 128) != 0)
         return false;
-    const int q = (int)(a.cols / 256);
+    const int u = (int)(a.cols / 128);
     const int l = a.log2n <= 5 ? 5 : a.log2n;
     if (a.out_dtype != QUEST_BF16) {
-#define QUEST_F32_OUT_CASE(Q_, L_)                 \
-    if (q == Q_ && l == L_) {                      \
-        launch<Q_, L_, float>(a, stream);          \
+#define QUEST_F32_OUT_CASE(U_, L_)                 \
+    if (u == U_ && l == L_) {                      \
+        launch<U_, L_, float>(a, stream);          \
         return true;                               \
     }
-        QUEST_F32_OUT_CASE(2, 9) QUEST_F32_OUT_CASE(4, 10) QUEST_F32_OUT_CASE(8, 11) QUEST_F32_OUT_CASE(16, 12)
-        QUEST_F32_OUT_CASE(22, 9)
+        QUEST_F32_OUT_CASE(4, 9) QUEST_F32_OUT_CASE(8, 10) QUEST_F32_OUT_CASE(16, 11) QUEST_F32_OUT_CASE(32, 12)
+        QUEST_F32_OUT_CASE(44, 9)
 #undef QUEST_F32_OUT_CASE
         return false;
     }
-#define QUEST_CASE(Q_, L_)                        \
-    if (q == Q_ && l == L_) {                     \
-        launch<Q_, L_>(a, stream);                \
+#define QUEST_CASE(U_, L_)                        \
+    if (u == U_ && l == L_) {                     \
+        launch<U_, L_>(a, stream);                \
         return true;                              \
     }
-    QUEST_CASE(2, 5) QUEST_CASE(2, 7) QUEST_CASE(2, 9)
-    QUEST_CASE(4, 5) QUEST_CASE(4, 7) QUEST_CASE(4, 9) QUEST_CASE(4, 10)
-    QUEST_CASE(8, 5) QUEST_CASE(8, 7) QUEST_CASE(8, 9) QUEST_CASE(8, 10) QUEST_CASE(8, 11)
-    QUEST_CASE(16, 5) QUEST_CASE(16, 7) QUEST_CASE(16, 9) QUEST_CASE(16, 10) QUEST_CASE(16, 11) QUEST_CASE(16, 12)
-    QUEST_CASE(22, 5) QUEST_CASE(22, 7) QUEST_CASE(22, 9)
-    QUEST_CASE(43, 5) QUEST_CASE(43, 7) QUEST_CASE(43, 8)   // 11008 = 43 x 256: ends three quarters into a tile
+    QUEST_CASE(4, 5) QUEST_CASE(4, 7) QUEST_CASE(4, 9)
+    QUEST_CASE(8, 5) QUEST_CASE(8, 7) QUEST_CASE(8, 9) QUEST_CASE(8, 10)
+    QUEST_CASE(16, 5) QUEST_CASE(16, 7) QUEST_CASE(16, 9) QUEST_CASE(16, 10) QUEST_CASE(16, 11)
+    QUEST_CASE(32, 5) QUEST_CASE(32, 7) QUEST_CASE(32, 9) QUEST_CASE(32, 10) QUEST_CASE(32, 11) QUEST_CASE(32, 12)
+    QUEST_CASE(44, 5) QUEST_CASE(44, 7) QUEST_CASE(44, 9)
+    QUEST_CASE(86, 5) QUEST_CASE(86, 7) QUEST_CASE(86, 8)   // 11008 = 86 x 128: ends three quarters into a tile
+    // the other widths of the paper's models (hidden 640 .. 1664, MLP 1792 .. 4608): no transform / widest block
+    QUEST_CASE(5, 5) QUEST_CASE(5, 7) QUEST_CASE(6, 5) QUEST_CASE(6, 8) QUEST_CASE(10, 5) QUEST_CASE(10, 8)
+    QUEST_CASE(13, 5) QUEST_CASE(13, 7) QUEST_CASE(14, 5) QUEST_CASE(14, 8) QUEST_CASE(22, 5) QUEST_CASE(22, 8)
+    QUEST_CASE(28, 5) QUEST_CASE(28, 9) QUEST_CASE(36, 5) QUEST_CASE(36, 9)
 #undef QUEST_CASE
     return false;
 }

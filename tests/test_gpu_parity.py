@@ -63,6 +63,10 @@ QUANT_CASES = [
     (70, 5632, 512, 4, "f32"),
     # rows of 11008 = 43 x 256 (the last 1024-element tile is three quarters full)
     (70, 11008, 256, 4, "bf16"), (33, 11008, 128, 4, "bf16"), (33, 11008, 16, 4, "bf16"), (5, 11008, 1, 4, "bf16"),
+    # the other hidden and MLP widths of the paper's model family, widest block and none
+    (37, 640, 128, 4, "bf16"), (37, 768, 256, 4, "bf16"), (37, 1280, 256, 4, "bf16"), (37, 1664, 128, 4, "bf16"),
+    (37, 1792, 256, 4, "bf16"), (37, 2816, 256, 4, "bf16"), (37, 3584, 512, 4, "bf16"), (37, 4608, 512, 4, "bf16"),
+    (9, 640, 1, 4, "bf16"), (9, 1664, 32, 4, "bf16"), (9, 2816, 8, 4, "bf16"), (9, 4608, 1, 4, "bf16"),
 ]
 
 
@@ -376,7 +380,11 @@ BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16")
               (9, 4096, 4096, "f32", "f32"), (9, 4096, 4096, "bf16", "f32"), (9, 4096, 4096, "f32", "bf16"),
               (70, 5632, 512, "f32", "f32"), (70, 5632, 512, "f32", "bf16"),
               # rows of 11008 = 43 x 256
-              (70, 11008, 256, "bf16", "bf16"), (33, 11008, 128, "bf16", "bf16"), (9, 11008, 4, "bf16", "bf16")]
+              (70, 11008, 256, "bf16", "bf16"), (33, 11008, 128, "bf16", "bf16"), (9, 11008, 4, "bf16", "bf16"),
+              # the other widths of the paper's model family
+              (37, 640, 128, "bf16", "bf16"), (37, 768, 256, "bf16", "bf16"), (37, 1280, 256, "bf16", "bf16"),
+              (37, 1664, 128, "bf16", "bf16"), (37, 1792, 256, "bf16", "bf16"), (37, 2816, 256, "bf16", "bf16"),
+              (37, 3584, 512, "bf16", "bf16"), (37, 4608, 512, "bf16", "bf16"), (9, 1664, 16, "bf16", "bf16")]
 
 
 @pytest.mark.parametrize("rows,cols,n,gd,od", BACK_CASES)
