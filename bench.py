@@ -247,6 +247,9 @@ def main():
     ap.add_argument("--grid", choices=("int4", "fp4"), default="int4",
                     help="int4: the headline path (Eq. 1 grid, INT8 matrix cores); fp4: the FP4 variant of "
                          "Sec. 4.4 end to end (E2M1 codes, FP4 matrix instructions)")
+    ap.add_argument("--bits", type=int, choices=(1, 2, 3, 4), default=None,
+                    help="bit width b of the integer grid for both operands (default: the workload's, 4); the "
+                         "paper trains at 1 to 4 bits, the matrix cores see signed bytes at every width")
     ap.add_argument("--only", choices=KERNELS + FP4_KERNELS, default=None,
                     help="profiling aid: launch just this kernel --warmup + --steps times back to back "
                          "(outputs of a whole step prepared once) and print its mean time; no benchmark line")
@@ -285,6 +288,11 @@ def main():
 
     x_bits, w_bits, cfg = synth.make_config(args.workload, seed=0)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
+    if args.bits is not None:
+        if args.grid == "fp4" and args.bits != 4:
+            sys.exit("bench.py: the FP4 grid has 4-bit codes")
+        cfg["bits"] = args.bits
+    cb = q.quest_container_bits(cfg["bits"])
     dy_bits = synth.upstream_gradient(M, N, seed=0)
     n_sets = 3   # ~0.7 GiB per set: > 1 GiB of other traffic between two uses of any buffer
     sets = [BufferSet(torch, dev, x_bits, w_bits, dy_bits, cfg) for _ in range(n_sets)]
@@ -365,7 +373,8 @@ def main():
     step_ops = 3.0 * gemm_ops
 
     def traffic(name):   # measured for the headline workload only
-        return MEASURED_TRAFFIC[name] if args.workload == WORKLOAD and args.grid == "int4" else None
+        headline = args.workload == WORKLOAD and args.grid == "int4" and cfg["bits"] == 4
+        return MEASURED_TRAFFIC[name] if headline else None
 
     def hbm(name, nbytes):
         gbs = nbytes / (ms[name] * 1e-3) / 1e9
@@ -380,8 +389,8 @@ def main():
                 "traffic": traffic(name), "ms": ms[name]}
 
     rooflines = {
-        "quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K)),
-        "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K)),
+        "quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K, cb)),
+        "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K, cb)),
         "lowbit_gemm": mfma("lowbit_gemm", FP4_PEAK_TOPS if args.grid == "fp4" else INT8_PEAK_TOPS),
         "grad_gemm_x": mfma("grad_gemm_x", BF16_PEAK_TFLOPS),
         "grad_gemm_w": mfma("grad_gemm_w", BF16_PEAK_TFLOPS),
@@ -392,7 +401,8 @@ def main():
     headline["unit"] = "TFLOP/s"   # integer multiply-adds counted as 2 ops each, in units of 1e12/s
 
     result = {
-        "metric": "W4A4 QuEST-linear TOPS at d=2048 (forward + backward step; quantizer GB/s in kernels)",
+        "metric": f"W{cfg['bits']}A{cfg['bits']} QuEST-linear TOPS at d={min(K, N) if args.workload.endswith('7b') else 2048} "
+                  "(forward + backward step; quantizer GB/s in kernels)",
         "value": step_ops / (ms_per_step * 1e-3) / 1e12,
         "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
