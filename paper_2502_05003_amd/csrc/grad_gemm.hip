@@ -259,12 +259,14 @@ __device__ __forceinline__ void tile_origin(int tile, int tiles_r, int tiles_k, 
  * MODE 1: out[N, K] = dy[M, N]^T xhat[M, K]      left = dy columns (column form), right = expanded [c][k]
  * MODE 2: out[M, N] = x[M, K] what[N, K]^T       left = x rows (row form),       right = expanded rows
  *         (row form: the weight-only forward product, contraction over the expanded matrix's columns)
- * `left` has row pitch ld_left elements, the expanded operand ld_right, `out` has K columns.
+ * `left` has row pitch ld_left elements, the expanded operand ld_right, `out` is [R, K] (K columns).
+ * R and K need not be whole tiles: the transfers of an edge tile fetch the last rows or columns
+ * that exist in place of those that do not (results of those positions are never stored).
  */
 template <int MODE, int STAGES>
 __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     const uint16_t *__restrict__ dy, int64_t ld_dy, const uint16_t *__restrict__ qhat, int64_t ld_right,
-    int C, int K, int tiles_r, int tiles_k, int per_block, int phase_period, uint16_t *__restrict__ out,
+    int C, int R, int K, int tiles_r, int tiles_k, int per_block, int phase_period, uint16_t *__restrict__ out,
     float4 *__restrict__ partial)
 {
     constexpr bool TRANSPOSED = MODE == 1;   // left operand in column form
@@ -292,23 +294,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     const int l16 = lane & 15, lg = lane >> 4;
     const uint32_t smem_addr = lds_address(smem);
 
-    // Transfers: piece q (0..3) of an operand is the 1 KiB at offset (4 q + wave) KiB.  Per-lane
-    // byte offsets from the operand's position of the step:
-    //   row form:    row 16 (4 q + wave) + l / 4, chunk (l % 4) ^ ((l / 16) & 3)
-    //   column form: contraction row 2 (4 q + wave) + l / 32, chunk (l % 32) ^ ((2 wave + l / 32) & 3) << 2
-    uint32_t left_voff[4], right_voff[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int piece = 4 * q + wave;
-        const int crow = 2 * piece + lh;
-        const uint32_t column_form = (uint32_t)(((lane & 31) ^ ((crow & 3) << 2)) << 4);
-        const uint32_t row_form_row = (uint32_t)(16 * piece + (lane >> 2));
-        const uint32_t row_form_chunk = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
-        right_voff[q] = RIGHT_ROWS ? row_form_row * (uint32_t)ld_right * 2u + row_form_chunk
-                                   : (uint32_t)crow * (uint32_t)ld_right * 2u + column_form;
-        left_voff[q] = TRANSPOSED ? (uint32_t)crow * (uint32_t)ld_dy * 2u + column_form
-                                  : row_form_row * (uint32_t)ld_dy * 2u + row_form_chunk;
-    }
     // byte advance per step
     const int64_t left_step = TRANSPOSED ? (int64_t)GC * ld_dy * 2 : (int64_t)GC * 2;
     const int64_t right_step = RIGHT_ROWS ? (int64_t)GC * 2 : (int64_t)GC * ld_right * 2;
@@ -349,6 +334,27 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     unit += s_end - s_begin;
     int r0, k0;
     tile_origin(tile, tiles_r, tiles_k, phase_period, r0, k0);
+    // Transfers: piece q (0..3) of an operand is the 1 KiB at offset (4 q + wave) KiB.  Per-lane
+    // byte offsets from the operand's position of the step:
+    //   row form:    row 16 (4 q + wave) + l / 4, chunk (l % 4) ^ ((l / 16) & 3)
+    //   column form: contraction row 2 (4 q + wave) + l / 32, chunk (l % 32) ^ ((2 wave + l / 32) & 3) << 2
+    // with rows and columns beyond the output's edge replaced by the last ones inside it.
+    uint32_t left_voff[4], right_voff[4];
+    {
+        const int rows_left = R - r0, cols_left = K - k0;   // what exists of this tile: >= 64, multiples of 8
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int piece = 4 * q + wave;
+            const int crow = 2 * piece + lh;
+            const int column = ((lane & 31) ^ ((crow & 3) << 2)) * 8;    // first of the chunk's eight columns
+            const int row_form_row = 16 * piece + (lane >> 2);
+            const uint32_t row_form_chunk = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+            right_voff[q] = RIGHT_ROWS ? (uint32_t)min(row_form_row, cols_left - 1) * (uint32_t)ld_right * 2u + row_form_chunk
+                                       : (uint32_t)crow * (uint32_t)ld_right * 2u + (uint32_t)min(column, cols_left - 8) * 2u;
+            left_voff[q] = TRANSPOSED ? (uint32_t)crow * (uint32_t)ld_dy * 2u + (uint32_t)min(column, rows_left - 8) * 2u
+                                      : (uint32_t)min(row_form_row, rows_left - 1) * (uint32_t)ld_dy * 2u + row_form_chunk;
+        }
+    }
     // operand positions of contraction step 0 (wave-uniform)
     const char *left_base = reinterpret_cast<const char *>(TRANSPOSED ? dy + r0 : dy + (int64_t)r0 * ld_dy);
     const char *right_base = reinterpret_cast<const char *>(RIGHT_ROWS ? qhat + (int64_t)k0 * ld_right : qhat + k0);
@@ -493,7 +499,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
         const int row = pass * 4 + (lane >> 4);
         const int c = lane & 15;
         const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 256 + ((c ^ (row & 15)) << 4));
-        *reinterpret_cast<uint4 *>(out_base + (int64_t)row * K + c * 8) = v;
+        if (r0 + wr * 128 + row < R && k0 + wc * 128 + c * 8 < K)
+            *reinterpret_cast<uint4 *>(out_base + (int64_t)row * K + c * 8) = v;
     }
     __syncthreads();   // the next segment's first stage overwrites the parked block
     }
@@ -501,60 +508,57 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
 
 /*
  * Adds up the partial tiles of every tile that more than one workgroup worked on (in workgroup
- * order, so the sum does not depend on timing) and writes the bf16 result.  One workgroup per
- * 128 x 128 quadrant of a tile (the block of one wave of the main kernel); its wave i takes the
- * four accumulator tiles (i, 0..3).
+ * order, so the sum does not depend on timing) and writes the bf16 result.  One wave per workgroup
+ * and 32 x 32 accumulator tile: quadrant = the 128 x 128 block of one wave of the main kernel,
+ * (i, j) = the accumulator tile in it.  (Sixty-four small workgroups per output tile, and several
+ * partial tiles in flight per lane: a small output split over many CUs has few tiles and many
+ * partial tiles each, and the sum is a chain of loads.)
  */
-__global__ __launch_bounds__(256) void grad_gemm_fixup_kernel(const float4 *__restrict__ partial, int steps,
-                                                              int per_block, int phase_period, int K,
-                                                              int tiles_r, int tiles_k,
-                                                              uint16_t *__restrict__ out)
+__global__ __launch_bounds__(64) void grad_gemm_fixup_kernel(const float4 *__restrict__ partial, int steps,
+                                                             int per_block, int phase_period, int R, int K,
+                                                             int tiles_r, int tiles_k,
+                                                             uint16_t *__restrict__ out)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t park[32768];
-    const int tile = blockIdx.x >> 2, quadrant = blockIdx.x & 3;
+    __shared__ __attribute__((aligned(16))) uint8_t park[2048];
+    const int tile = blockIdx.x >> 6, quadrant = (blockIdx.x >> 4) & 3, i = (blockIdx.x >> 2) & 3, j = blockIdx.x & 3;
     const int64_t first_unit = (int64_t)tile * steps, last_unit = first_unit + steps - 1;
     const int b_first = (int)(first_unit / per_block), b_last = (int)(last_unit / per_block);
     if (b_first == b_last)
         return;   // computed whole by one workgroup, already written
-    const int tid = threadIdx.x, lane = tid & 63, i = tid >> 6;
+    const int lane = threadIdx.x;
     const int lm = lane & 31, lh = lane >> 5;
-    float4 sum[4][4];
+    float4 sum[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            sum[j][q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int q = 0; q < 4; ++q)
+        sum[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll 4
     for (int b = b_first; b <= b_last; ++b) {
         const bool continues = (int64_t)b * per_block > first_unit;
         const float4 *slot = partial + ((int64_t)(2 * b + (continues ? 0 : 1)) * 4 + quadrant) * (64 * 64) + lane;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = slot[((i * 4 + j) * 4 + q) * 64];
-                sum[j][q].x += v.x; sum[j][q].y += v.y; sum[j][q].z += v.z; sum[j][q].w += v.w;
-            }
-    }
-    const int row = i * 32 + lm;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int col = j * 32 + 8 * q + 4 * lh;
-            const int chunk = (col >> 3) ^ (row & 15);
-            *reinterpret_cast<uint2 *>(park + row * 256 + chunk * 16 + (col & 4) * 2) =
-                make_uint2(pack2_bf16(sum[j][q].x, sum[j][q].y), pack2_bf16(sum[j][q].z, sum[j][q].w));
+            const float4 v = slot[((i * 4 + j) * 4 + q) * 64];
+            sum[q].x += v.x; sum[q].y += v.y; sum[q].z += v.z; sum[q].w += v.w;
         }
+    }
+    // park the 32 x 32 tile as bf16 (row lm, 64 bytes), write 16-byte chunks: 4 per row, 2 passes
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int col = 8 * q + 4 * lh;
+        *reinterpret_cast<uint2 *>(park + lm * 64 + col * 2) =
+            make_uint2(pack2_bf16(sum[q].x, sum[q].y), pack2_bf16(sum[q].z, sum[q].w));
+    }
     __syncthreads();
     int r0, k0;
     tile_origin(tile, tiles_r, tiles_k, phase_period, r0, k0);
-    uint16_t *out_base = out + (int64_t)(r0 + (quadrant >> 1) * 128) * K + k0 + (quadrant & 1) * 128;
+    const int row0 = r0 + (quadrant >> 1) * 128 + i * 32, col0 = k0 + (quadrant & 1) * 128 + j * 32;
 #pragma unroll
-    for (int pass = 0; pass < 8; ++pass) {
-        const int prow = pass * 16 + (tid >> 4);
-        const int c = tid & 15;
-        const uint4 v = *reinterpret_cast<const uint4 *>(park + prow * 256 + ((c ^ (prow & 15)) << 4));
-        *reinterpret_cast<uint4 *>(out_base + (int64_t)prow * K + c * 8) = v;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int prow = pass * 16 + (lane >> 2);
+        const int c = lane & 3;
+        const uint4 v = *reinterpret_cast<const uint4 *>(park + prow * 64 + c * 16);
+        if (row0 + prow < R && col0 + c * 8 < K)
+            *reinterpret_cast<uint4 *>(out + (int64_t)(row0 + prow) * K + col0 + c * 8) = v;
     }
 }
 
@@ -572,13 +576,15 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
     const int64_t contraction = a.which == 0 ? a.N : a.which == 1 ? a.M : a.K;
     const int64_t q_rows = a.which == 1 ? a.M : a.N;          // rows of the code-packed operand [q_rows, K]
     const int64_t ld_left = a.which == 2 ? a.K : a.N;
-    const bool whole_tiles = (out_rows % GT) == 0 && (out_cols % GT) == 0 && (contraction % GC) == 0 &&
-                             out_rows * out_cols < ((int64_t)1 << 31) &&
-                             std::max(a.M, a.N) * std::max(a.K, a.N) < ((int64_t)1 << 30);
-    if ((a.which == 2 || a.fp4) && !whole_tiles)
+    const bool whole_tiles = (out_rows % GT) == 0 && (out_cols % GT) == 0;
+    // the tile kernels: edge tiles may be partial (every size is a multiple of 64), offsets are 32-bit
+    const bool tile_path = out_rows >= GT / 2 && out_cols >= GT / 2 && (contraction % GC) == 0 &&
+                           out_rows * out_cols < ((int64_t)1 << 31) &&
+                           std::max(a.M, a.N) * std::max(a.K, a.N) < ((int64_t)1 << 30);
+    if ((a.which == 2 || a.fp4) && !(whole_tiles && tile_path))
         return hipErrorInvalidValue;
-    if (whole_tiles) {
-        const int tiles_r = (int)(out_rows / GT), tiles_k = (int)(out_cols / GT);
+    if (tile_path) {
+        const int tiles_r = (int)((out_rows + GT - 1) / GT), tiles_k = (int)((out_cols + GT - 1) / GT);
         const int tiles = tiles_r * tiles_k, steps = (int)(contraction / GC);
         constexpr int kStages = 5;
         constexpr int kLds = kStages * kGStage;
@@ -589,9 +595,10 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
             err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<2, kStages>), kLds);
         if (err != hipSuccess)
             return err;
-        // One workgroup per CU at a time.  When the last round of whole tiles would leave more than
-        // a tenth of the CU-rounds idle, every CU gets the same share of (tile, step) units instead
-        // and the split tiles are summed by a second, small kernel.
+        // One workgroup per CU at a time.  When rounds of whole tiles would leave CUs idle, every CU
+        // can get the same share of (tile, step) units instead, the split tiles being summed by a
+        // second, small kernel.  That pays when the steps saved outweigh the partial tiles written
+        // and read back (two 256 KiB slots per workgroup at most, one per tile at least).
         int device = 0, cus = 0;
         err = hipGetDevice(&device);
         if (err == hipSuccess)
@@ -600,7 +607,11 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
             return err;
         cus = cus / 8 * 8;
         const int rounds = cus > 0 ? (tiles + cus - 1) / cus : 0;
-        const bool split = cus >= 8 && 10 * tiles < 9 * rounds * cus && (int64_t)tiles * steps >= 4 * (int64_t)cus;
+        const int64_t units = (int64_t)tiles * steps;
+        // measured on this kernel: 0.6 us per step, 0.08 us per partial tile written and read, 10 us for the second launch
+        const double whole_cost = 0.6 * rounds * steps;
+        const double split_cost = cus > 0 ? 0.6 * (double)((units + cus - 1) / cus) + 0.08 * (cus + tiles) + 10.0 : 0.0;
+        const bool split = cus >= 8 && split_cost < whole_cost && units >= 4 * (int64_t)cus;
         int blocks = (tiles + 7) / 8 * 8, per_block = steps, phase_period = 0;
         if (split) {
             blocks = cus;
@@ -630,20 +641,20 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
         const dim3 grid((unsigned)blocks), block(kGemmThreads);
         if (a.which == 0)
             hipLaunchKernelGGL((grad_gemm_tile_kernel<0, kStages>), grid, block, kLds, stream, dy, ld_left, qhat,
-                               a.K, (int)contraction, (int)out_cols, tiles_r, tiles_k, per_block,
+                               a.K, (int)contraction, (int)out_rows, (int)out_cols, tiles_r, tiles_k, per_block,
                                phase_period, out, partial);
         else if (a.which == 1)
             hipLaunchKernelGGL((grad_gemm_tile_kernel<1, kStages>), grid, block, kLds, stream, dy, ld_left, qhat,
-                               a.K, (int)contraction, (int)out_cols, tiles_r, tiles_k, per_block,
+                               a.K, (int)contraction, (int)out_rows, (int)out_cols, tiles_r, tiles_k, per_block,
                                phase_period, out, partial);
         else
             hipLaunchKernelGGL((grad_gemm_tile_kernel<2, kStages>), grid, block, kLds, stream, dy, ld_left, qhat,
-                               a.K, (int)contraction, (int)out_cols, tiles_r, tiles_k, per_block,
+                               a.K, (int)contraction, (int)out_rows, (int)out_cols, tiles_r, tiles_k, per_block,
                                phase_period, out, partial);
         err = hipGetLastError();
         if (err == hipSuccess && split) {
-            hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles * 4)), dim3(256), 0, stream, partial,
-                               steps, per_block, phase_period, (int)out_cols, tiles_r, tiles_k, out);
+            hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles * 64)), dim3(64), 0, stream, partial,
+                               steps, per_block, phase_period, (int)out_rows, (int)out_cols, tiles_r, tiles_k, out);
             err = hipGetLastError();
         }
         return err;

@@ -427,12 +427,15 @@ def test_trust_backward_full_size_headline_shape():
                                    # evenly (12 steps over 4) and unevenly (128 steps in threes)
                                    (768, 8192, 512), (8192, 768, 512),
                                    # more tiles than CUs, two steps each: whole tiles and halves mixed
-                                   (5120, 128, 3840), (128, 5120, 3840)])
+                                   (5120, 128, 3840), (128, 5120, 3840),
+                                   # outputs that end inside a tile (hidden 640 and 1664 of the paper's models)
+                                   (640, 1664, 384), (1664, 640, 896), (320, 192, 448), (4096, 640, 1664)])
 @pytest.mark.parametrize("which", [0, 1])
 def test_grad_gemm_matches_oracle(which, M, N, K):
-    """Small shapes run the 64x64 kernel; shapes made of whole 256x256 tiles run the main kernel,
-    which splits tiles between workgroups when whole tiles would leave CUs idle."""
-    bits, n = 4, 256
+    """Small shapes run the 64x64 kernel; outputs of at least half a 256x256 tile each way run the
+    main kernel (edge tiles may be partial), which splits tiles between workgroups when whole tiles
+    would leave CUs idle."""
+    bits, n = 4, min(256, K & -K)
     x = synth.gaussian(M, K, 1.0, 11, "bf16")
     w = synth.gaussian(N, K, 0.02, 12, "bf16")
     dy = synth.upstream_gradient(M, N, 0, "bf16")
