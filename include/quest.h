@@ -168,7 +168,7 @@ quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint
  *   which = 1:  out[N, K] = dy[M, N]^T * xhat_h[M, K]    (q = activation codes [M, K*cb/8], scales [M])
  *   dy bf16 [M, N] row-major, out bf16, fp32 accumulation.  bits in {1,2,3,4}.
  *   M, N, K multiples of 64.
- * Device memory: when the output is made of whole 256 x 256 tiles the call first expands the packed
+ * Device memory: when the output is at least 128 x 128 the call first expands the packed
  * operand to bf16 and, if the tiles do not fill the GPU's compute units evenly, sums partial tiles
  * in a second pass.  Both live in memory the library owns: one buffer per device, allocated
  * (hipMalloc) or grown on the first call that needs the size and kept until the process ends.
@@ -184,9 +184,9 @@ quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_cod
 /*
  * quest_grad_gemm for operands quantized by quest_hadamard_quantize_fp4: the code-packed operand's
  * value is bf16(s * v), v the signed E2M1 value of its code (the backward pass of the FP4 variant,
- * Sec. 4.4, is Algorithm 2 unchanged).  which = 0 or 1 as there.  The output must be made of whole
- * 256 x 256 tiles and the contraction a multiple of 64 (QUEST_ERR_SHAPE otherwise).  Uses the
- * library-owned device memory described at quest_grad_gemm.
+ * Sec. 4.4, is Algorithm 2 unchanged).  which = 0 or 1 as there.  M, N, K multiples of 64 and the
+ * output at least 128 x 128 (QUEST_ERR_SHAPE otherwise).  Uses the library-owned device memory
+ * described at quest_grad_gemm.
  */
 quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q_codes,
                                  const float *q_scales, int64_t M, int64_t N, int64_t K, void *out,
@@ -200,7 +200,7 @@ quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q
  *            when called without a mask)
  *   w_codes  [N, K*cb/8], w_scales [N] from either quantizer entry point;  bits in {1,2,3,4}
  *   y        out bf16 [M, N] row-major, fp32 accumulation on the bf16 matrix cores
- * M and N multiples of 256, K a multiple of 64, M*N < 2^31 (QUEST_ERR_SHAPE otherwise).
+ * M, N, K multiples of 64, M and N at least 128, M*N < 2^31 (QUEST_ERR_SHAPE otherwise).
  * Uses the same library-owned device memory as quest_grad_gemm, with the same consequences.
  */
 quest_status quest_weight_only_gemm(const void *x, const uint8_t *w_codes, const float *w_scales,

@@ -576,12 +576,11 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
     const int64_t contraction = a.which == 0 ? a.N : a.which == 1 ? a.M : a.K;
     const int64_t q_rows = a.which == 1 ? a.M : a.N;          // rows of the code-packed operand [q_rows, K]
     const int64_t ld_left = a.which == 2 ? a.K : a.N;
-    const bool whole_tiles = (out_rows % GT) == 0 && (out_cols % GT) == 0;
     // the tile kernels: edge tiles may be partial (every size is a multiple of 64), offsets are 32-bit
     const bool tile_path = out_rows >= GT / 2 && out_cols >= GT / 2 && (contraction % GC) == 0 &&
                            out_rows * out_cols < ((int64_t)1 << 31) &&
                            std::max(a.M, a.N) * std::max(a.K, a.N) < ((int64_t)1 << 30);
-    if ((a.which == 2 || a.fp4) && !(whole_tiles && tile_path))
+    if ((a.which == 2 || a.fp4) && !tile_path)   // only the tile kernels know these forms
         return hipErrorInvalidValue;
     if (tile_path) {
         const int tiles_r = (int)((out_rows + GT - 1) / GT), tiles_k = (int)((out_cols + GT - 1) / GT);

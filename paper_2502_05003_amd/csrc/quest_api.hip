@@ -387,8 +387,9 @@ quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q
     if (which != 0 && which != 1)
         return QUEST_ERR_ARG;
     const int64_t out_rows = which == 0 ? M : N, contraction = which == 0 ? N : M;
-    if (M < 0 || N < 0 || K < 0 || (out_rows & 255) || (K & 255) || (contraction & 63) ||
-        M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K > (int64_t(1) << 22) ||
+    const bool empty = M == 0 || N == 0 || K == 0;
+    if (M < 0 || N < 0 || K < 0 || (out_rows & 63) || (K & 63) || (contraction & 63) ||
+        (!empty && (out_rows < 128 || K < 128)) || M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K > (int64_t(1) << 22) ||
         out_rows * K >= (int64_t(1) << 31) || (M > N ? M : N) * (K > N ? K : N) >= (int64_t(1) << 30))
         return QUEST_ERR_SHAPE;
     if (!aligned16(dy) || !aligned16(q_codes) || !aligned16(out))
@@ -418,7 +419,9 @@ quest_status quest_weight_only_gemm(const void *x, const uint8_t *w_codes, const
         return QUEST_ERR_NULL;
     if (bits < 1 || bits > 4)
         return QUEST_ERR_BITS;
-    if (M < 0 || N < 0 || K < 0 || (M & 255) || (N & 255) || (K & 63) || M > (int64_t(1) << 22) ||
+    const bool empty = M == 0 || N == 0 || K == 0;
+    if (M < 0 || N < 0 || K < 0 || (M & 63) || (N & 63) || (K & 63) || (!empty && (M < 128 || N < 128)) ||
+        M > (int64_t(1) << 22) ||
         N > (int64_t(1) << 22) || K > (int64_t(1) << 22) || M * N >= (int64_t(1) << 31) ||
         (M > N ? M : N) * (K > N ? K : N) >= (int64_t(1) << 30))
         return QUEST_ERR_SHAPE;

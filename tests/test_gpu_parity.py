@@ -565,7 +565,8 @@ def test_down_projection_full_size():
 
 @pytest.mark.parametrize("M,N,K,bits", [(256, 256, 64, 4), (512, 256, 2048, 4), (256, 768, 320, 2),
                                         (768, 512, 1024, 1), (256, 256, 5632, 3),
-                                        (4096, 2304, 128, 4)])   # 144 tiles: split over the CUs
+                                        (4096, 2304, 128, 4),   # 144 tiles: split over the CUs
+                                        (640, 1664, 384, 4), (192, 320, 448, 2)])   # outputs ending inside a tile
 def test_weight_only_gemm_matches_oracle(M, N, K, bits):
     """Sec. 4.4: bf16 activations in the Hadamard domain (the transform alone is the trust
     backward without a mask) against 1..4-bit weights expanded on the fly."""
@@ -617,10 +618,11 @@ def test_split_tiles_are_summed_in_a_fixed_order():
 
 
 @pytest.mark.parametrize("which,M,N,K", [(0, 512, 256, 512), (1, 512, 256, 512), (0, 768, 8192, 512),
-                                          (1, 8192, 768, 512)])
+                                          (1, 8192, 768, 512),
+                                          (0, 640, 1664, 384), (1, 1664, 640, 896)])   # outputs ending inside a tile
 def test_fp4_grad_gemm_matches_oracle(which, M, N, K):
     """Backward matmuls of the FP4 variant (Algorithm 2 on E2M1-coded operands), whole and split tiles."""
-    n = 256
+    n = min(256, K & -K)
     x = synth.gaussian(M, K, 1.0, 11, "bf16")
     w = synth.gaussian(N, K, 0.02, 12, "bf16")
     dy = synth.upstream_gradient(M, N, 0, "bf16")

@@ -102,13 +102,13 @@ def test_variant_entry_points_reject_bad_arguments(lib):
     def grad4(which=0, dy=FAKE, qc=FAKE, qs=FAKE, M=0, N=0, K=0, out=FAKE):
         return lib.quest_grad_gemm_fp4(which, dy, qc, qs, M, N, K, out, None)
     assert grad4() == 0 and grad4(which=2) == 8 and grad4(qc=None) == 1
-    assert grad4(M=128, N=256, K=256) == 2 and grad4(M=256, N=32, K=256) == 2
+    assert grad4(M=64, N=256, K=256) == 2 and grad4(M=256, N=32, K=256) == 2 and grad4(M=256, N=256, K=64) == 2
 
     def wonly(x=FAKE, wc=FAKE, ws=FAKE, bits=4, M=0, N=0, K=0, y=FAKE):
         return lib.quest_weight_only_gemm(x, wc, ws, bits, M, N, K, y, None)
     assert wonly() == 0
     assert wonly(x=None) == 1 and wonly(bits=8) == 3
-    assert wonly(M=128, N=256, K=64) == 2 and wonly(M=256, N=256, K=32) == 2
+    assert wonly(M=64, N=256, K=64) == 2 and wonly(M=256, N=256, K=32) == 2 and wonly(M=256, N=192 + 8, K=64) == 2
     assert wonly(y=ctypes.c_void_p(0x10002)) == 5
 
 
