@@ -508,24 +508,25 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
 
 /*
  * Adds up the partial tiles of every tile that more than one workgroup worked on (in workgroup
- * order, so the sum does not depend on timing) and writes the bf16 result.  One wave per workgroup
- * and 32 x 32 accumulator tile: quadrant = the 128 x 128 block of one wave of the main kernel,
- * (i, j) = the accumulator tile in it.  (Sixty-four small workgroups per output tile, and several
- * partial tiles in flight per lane: a small output split over many CUs has few tiles and many
- * partial tiles each, and the sum is a chain of loads.)
+ * order, so the sum does not depend on timing) and writes the bf16 result.  One wave per 32 x 32
+ * accumulator tile: quadrant = the 128 x 128 block of one wave of the main kernel, (i, j) = the
+ * accumulator tile in it, j = the wave of a workgroup.  (Sixty-four waves per output tile, and
+ * several partial tiles in flight per lane: a small output split over many CUs has few tiles and
+ * many partial tiles each, and the sum is a chain of loads.)
  */
-__global__ __launch_bounds__(64) void grad_gemm_fixup_kernel(const float4 *__restrict__ partial, int steps,
+__global__ __launch_bounds__(256) void grad_gemm_fixup_kernel(const float4 *__restrict__ partial, int steps,
                                                              int per_block, int phase_period, int R, int K,
                                                              int tiles_r, int tiles_k,
                                                              uint16_t *__restrict__ out)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t park[2048];
-    const int tile = blockIdx.x >> 6, quadrant = (blockIdx.x >> 4) & 3, i = (blockIdx.x >> 2) & 3, j = blockIdx.x & 3;
+    __shared__ __attribute__((aligned(16))) uint8_t park_all[4 * 2048];
+    const int tile = blockIdx.x >> 4, quadrant = (blockIdx.x >> 2) & 3, i = blockIdx.x & 3, j = threadIdx.x >> 6;
+    uint8_t *park = park_all + j * 2048;
     const int64_t first_unit = (int64_t)tile * steps, last_unit = first_unit + steps - 1;
     const int b_first = (int)(first_unit / per_block), b_last = (int)(last_unit / per_block);
     if (b_first == b_last)
         return;   // computed whole by one workgroup, already written
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     const int lm = lane & 31, lh = lane >> 5;
     float4 sum[4];
 #pragma unroll
@@ -652,7 +653,7 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
                                phase_period, out, partial);
         err = hipGetLastError();
         if (err == hipSuccess && split) {
-            hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles * 64)), dim3(64), 0, stream, partial,
+            hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles * 16)), dim3(256), 0, stream, partial,
                                steps, per_block, phase_period, (int)out_rows, (int)out_cols, tiles_r, tiles_k, out);
             err = hipGetLastError();
         }
