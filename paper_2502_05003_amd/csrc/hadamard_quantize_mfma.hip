@@ -159,11 +159,11 @@ struct TransposePlan {
  */
 // Waves per SIMD the register budget is set for.  Holding a long row (2 U transformed values per
 // lane, next to the fp32 inputs still on their way) needs more than the 128 registers of four waves,
-// and so do the packed inputs of a row of 11008.
+// and so do the packed inputs of a row of 5632 or 11008 (measured: 52 instead of 57 us for 16384 x 5632).
 template <int U, bool HOLD_ALL, bool F32>
 constexpr int hq_waves_per_eu()
 {
-    return (HOLD_ALL && (U > 32 || (F32 && U == 32))) ? 2 : U > 64 ? 3 : QUEST_HQ_WAVES_PER_EU;
+    return (HOLD_ALL && (U > 32 || (F32 && U == 32))) ? 2 : U > 40 ? 3 : QUEST_HQ_WAVES_PER_EU;
 }
 
 template <int U, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4, typename In = uint16_t,
@@ -183,9 +183,10 @@ void hq_mfma_kernel(
     constexpr bool kF32 = sizeof(In) == 4;
     constexpr bool kHoldAll = kF32 || ABSMAX;
     static_assert(!kHoldAll || (!FP4 && BITS == 4), "fp32 rows and AbsMax: 4-bit integer grid only");
-    // tiles transformed together: all of them when the block spans tiles or the whole row is held,
-    // else two (one mask word)
-    constexpr int G = (LOG2N > 10 || kHoldAll) ? T : (T >= 2 ? 2 : 1);
+    // tiles transformed together: all of them when the whole row is held, else those one Hadamard
+    // block spans, and at least two (one mask word)
+    constexpr int kSpan = LOG2N > 10 ? (1 << (LOG2N - 10)) : 1;
+    constexpr int G = kHoldAll ? T : (kSpan >= T ? T : (kSpan >= 2 ? kSpan : (T >= 2 ? 2 : 1)));
     constexpr int kLevels = 1 << BITS;
     constexpr int CB = BITS == 3 ? 4 : BITS;   // container bits
     static_assert(!FP4 || BITS == 4, "the E2M1 grid has 4-bit codes");

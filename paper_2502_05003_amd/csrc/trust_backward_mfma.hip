@@ -63,7 +63,7 @@ __device__ __forceinline__ uint32_t keep_trusted(uint32_t pair, uint32_t mask_bi
 }
 
 template <int U, int LOG2N, bool WITH_MASK, typename Out = uint16_t>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(U > 64 ? 2 : 4)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4)))
 void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ mask, int64_t rows,
                     int log2n, Out *__restrict__ out)
 {
@@ -72,6 +72,9 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
     constexpr int NI = 2 * U;              // elements per lane
     constexpr int cols = 128 * U;
     constexpr int kTailRows = (U % 8) ? 4 * (U % 8) : 32;   // rows of the last tile that exist
+    // tiles transformed together: those one Hadamard block spans
+    constexpr int kSpan = LOG2N > 10 ? (1 << (LOG2N - 10)) : 1;
+    constexpr int G = kSpan < T ? kSpan : T;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
@@ -107,117 +110,128 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
          row += (int64_t)gridDim.x * kRowsPerBlock) {
         const uint16_t *src = g + row * cols + 32 * m + 16 * h;
         const uint8_t *mask_src = mask + row * (cols / 8) + 4 * m + 2 * h;
-        float acc[T][16];
+        // tiles that one Hadamard block couples are transformed together, the others one after another
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            v4u n0 = {0, 0, 0, 0}, n1 = {0, 0, 0, 0};
-            uint32_t bits = 0xffffu;
-            if (t < T - 1 || m < kTailRows) {
-                n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
-                n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
-                if (WITH_MASK)
-                    bits = *reinterpret_cast<const uint16_t *>(mask_src + 128 * t);
+        for (int g0 = 0; g0 < T; g0 += G) {
+            float acc[G][16];
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+                const int t = g0 + u;
+                v4u n0 = {0, 0, 0, 0}, n1 = {0, 0, 0, 0};
+                uint32_t bits = 0xffffu;
+                if (t < T && (t < T - 1 || m < kTailRows)) {
+                    n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
+                    n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
+                    if (WITH_MASK)
+                        bits = *reinterpret_cast<const uint16_t *>(mask_src + 128 * t);
+                }
+                uint32_t w[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+                if (WITH_MASK) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        w[i] = keep_trusted(w[i], bits, 2 * i);
+                }
+                v8bf f0, f1;
+                __builtin_memcpy(&f0, &w[0], 16);
+                __builtin_memcpy(&f1, &w[4], 16);
+                v16f z;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    z[r] = 0.0f;
+                z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
+                z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc[u][r] = z[r];
             }
-            uint32_t w[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
-            if (WITH_MASK) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    w[i] = keep_trusted(w[i], bits, 2 * i);
-            }
-            v8bf f0, f1;
-            __builtin_memcpy(&f0, &w[0], 16);
-            __builtin_memcpy(&f1, &w[4], 16);
-            v16f z;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                z[r] = 0.0f;
-            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
-            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[t][r] = z[r];
-        }
 
-        if (LOG2N > 5) {  // bit 5 = register bit 0
+            if (LOG2N > 5) {  // bit 5 = register bit 0
 #pragma unroll
-            for (int t = 0; t < T; ++t)
+                for (int u = 0; u < G; ++u)
 #pragma unroll
-                for (int r = 0; r < 16; r += 2)
-                    bfly(acc[t][r], acc[t][r + 1]);
-        }
-        if (LOG2N > 6) {  // bit 6 = register bit 1
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!(r & 2))
-                        bfly(acc[t][r], acc[t][r + 2]);
-        }
-        // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][r]),
-                                                                 __float_as_uint(acc[t][r + 1]),
-                                                                 false, false);
-                acc[t][r] = __uint_as_float(sw[0]);
-                acc[t][r + 1] = __uint_as_float(sw[1]);
+                    for (int r = 0; r < 16; r += 2)
+                        bfly(acc[u][r], acc[u][r + 1]);
             }
-        if (LOG2N > 7) {
+            if (LOG2N > 6) {  // bit 6 = register bit 1
 #pragma unroll
-            for (int t = 0; t < T; ++t)
+                for (int u = 0; u < G; ++u)
 #pragma unroll
-                for (int r = 0; r < 16; r += 2)
-                    bfly(acc[t][r], acc[t][r + 1]);
-        }
-        if (LOG2N > 8) {  // bit 8 = register bit 2
+                    for (int r = 0; r < 16; ++r)
+                        if (!(r & 2))
+                            bfly(acc[u][r], acc[u][r + 2]);
+            }
+            // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
 #pragma unroll
-            for (int t = 0; t < T; ++t)
+            for (int u = 0; u < G; ++u)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!(r & 4))
-                        bfly(acc[t][r], acc[t][r + 4]);
-        }
-        if (LOG2N > 9) {  // bit 9 = register bit 3
+                for (int r = 0; r < 16; r += 2) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[u][r]),
+                                                                     __float_as_uint(acc[u][r + 1]),
+                                                                     false, false);
+                    acc[u][r] = __uint_as_float(sw[0]);
+                    acc[u][r + 1] = __uint_as_float(sw[1]);
+                }
+            if (LOG2N > 7) {
 #pragma unroll
-            for (int t = 0; t < T; ++t)
+                for (int u = 0; u < G; ++u)
 #pragma unroll
-                for (int r = 0; r < 8; ++r)
-                    bfly(acc[t][r], acc[t][r + 8]);
-        }
+                    for (int r = 0; r < 16; r += 2)
+                        bfly(acc[u][r], acc[u][r + 1]);
+            }
+            if (LOG2N > 8) {  // bit 8 = register bit 2
 #pragma unroll
-        for (int k = 0; (1 << k) < T; ++k) {  // bits >= 10 pair whole tiles
-            if (LOG2N > 10 + k) {
+                for (int u = 0; u < G; ++u)
 #pragma unroll
-                for (int t = 0; t < T; ++t)
-                    if (!(t & (1 << k)) && (t | (1 << k)) < T) {
+                    for (int r = 0; r < 16; ++r)
+                        if (!(r & 4))
+                            bfly(acc[u][r], acc[u][r + 4]);
+            }
+            if (LOG2N > 9) {  // bit 9 = register bit 3
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            bfly(acc[t][r], acc[t | (1 << k)][r]);
+                for (int u = 0; u < G; ++u)
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        bfly(acc[u][r], acc[u][r + 8]);
+            }
+#pragma unroll
+            for (int k = 0; (1 << k) < G; ++k) {  // bits >= 10 pair whole tiles
+                if (LOG2N > 10 + k) {
+#pragma unroll
+                    for (int u = 0; u < G; ++u)
+                        if (!(u & (1 << k)) && (u | (1 << k)) < G) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                bfly(acc[u][r], acc[u | (1 << k)][r]);
+                        }
+                }
+            }
+
+            // element = (lane & 31) + 32 h + 64 iota; this group holds iota = 16 g0 .. as far as the row goes
+            constexpr int kGroupI = 16 * G;
+            const int first = 16 * g0;
+            const int count_i = (NI - first) < kGroupI ? (NI - first) : kGroupI;
+            if constexpr (kF32Out) {
+                float *dst = out + row * cols + lane + 64 * first;
+#pragma unroll
+                for (int i = 0; i < kGroupI; ++i)
+                    if (i < count_i)
+                        __builtin_nontemporal_store(__fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n), dst + 64 * i);
+            } else {
+                // Round (iota, iota + 1) to a bf16 pair, swap halves with lane ^ 1: an even lane then
+                // holds elements (l, l + 1) of iota, an odd lane elements (l - 1, l) of iota + 1.  A wave
+                // instruction stores 2 x 128 contiguous bytes.
+                uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * cols) + (m >> 1) + 16 * h +
+                                32 * (lane & 1) + 32 * first;
+#pragma unroll
+                for (int i = 0; i < kGroupI; i += 2) {
+                    if (i < count_i) {
+                        const float v0 = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
+                        const float v1 = __fmul_rn(acc[(i + 1) >> 4][reg_of_iota((i + 1) & 15)], inv_sqrt_n);
+                        const uint32_t own = pack_bf16_pair(v0, v1);
+                        const uint32_t other = (uint32_t)__builtin_amdgcn_ds_swizzle((int)own, (1 << 10) | 0x1f);
+                        __builtin_nontemporal_store(__builtin_amdgcn_perm(other, own, pair_sel), dst + 32 * i);
                     }
-            }
-        }
-
-        // element = (lane & 31) + 32 h + 64 iota.
-        if constexpr (kF32Out) {
-            float *dst = out + row * cols + lane;
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-                __builtin_nontemporal_store(__fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n), dst + 64 * i);
-        } else {
-            // Round (iota, iota + 1) to a bf16 pair, swap halves with lane ^ 1: an even lane then
-            // holds elements (l, l + 1) of iota, an odd lane elements (l - 1, l) of iota + 1.  A wave
-            // instruction stores 2 x 128 contiguous bytes.
-            uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * cols) + (m >> 1) + 16 * h +
-                            32 * (lane & 1);
-#pragma unroll
-            for (int i = 0; i < NI; i += 2) {
-                const float v0 = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
-                const float v1 = __fmul_rn(acc[(i + 1) >> 4][reg_of_iota((i + 1) & 15)], inv_sqrt_n);
-                const uint32_t own = pack_bf16_pair(v0, v1);
-                const uint32_t other = (uint32_t)__builtin_amdgcn_ds_swizzle((int)own, (1 << 10) | 0x1f);
-                __builtin_nontemporal_store(__builtin_amdgcn_perm(other, own, pair_sel), dst + 32 * i);
+                }
             }
         }
     }
