@@ -485,6 +485,241 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// Small-tile kernel for launches that would leave the kernel above with fewer workgroups than the
+// chip has slots (a prefill of a few thousand tokens): workgroup tile 128 x 128, four waves of
+// 64 x 64 (four 32 x 32 accumulator tiles each), 128 contraction elements per step, three LDS
+// stages of 16 KiB, three workgroups per CU.  Same layouts, transfers, widening and transposed
+// accumulator tiles as above; a 64 x 64 wave tile needs one widening per matrix instruction, so
+// the operands of a sub-step are widened during the sub-step before it, into the other of two
+// register sets.
+// ------------------------------------------------------------------------------------------
+
+constexpr int STM = 128, STN = 128;
+constexpr int kSmallStageBytes = (STM + STN) * kRowBytes;     // 16 KiB
+constexpr int kSmallParkBytes = 4 * 64 * 64 * 2;             // epilogue: four waves x 64 x 64 bf16
+static_assert(kSmallParkBytes <= kStages * kSmallStageBytes, "the epilogue parks in the stages");
+constexpr int kSmallLds = kStages * kSmallStageBytes + STN * 4;
+
+template <int BITS>
+__global__ __launch_bounds__(kTileThreads, 3) void lowbit_gemm_small_kernel(
+    const uint8_t *__restrict__ a_codes, const float *__restrict__ a_scales,
+    const uint8_t *__restrict__ b_codes, const float *__restrict__ b_scales, int M, int N, int K,
+    int tiles_m, int tiles_n, uint16_t *__restrict__ y, int64_t ld_y,
+    int32_t *__restrict__ acc_out)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    // workgroup -> tile: one contiguous run of tiles per XCD, eight tile-rows deep
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total)
+        return;
+    const int band = logical / (8 * tiles_n);
+    const int band_rows = min(8, tiles_m - band * 8);
+    const int in_band = logical - band * 8 * tiles_n;
+    const int tile_m = band * 8 + in_band % band_rows;
+    const int tile_n = in_band / band_rows;
+    const int m0 = tile_m * STM, n0 = tile_n * STN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lm = lane & 31, lh = lane >> 5;
+
+    // Staging as above: a wave's 64 lanes fill 16 tile rows x 64 bytes per transfer.  Four pieces per
+    // step and wave: rows 64 i + 16 wave .. + 16 of A (i < 2) and of B (i = 2, 3).
+    const int st_row = 16 * wave + (lane >> 2);
+    const int st_chunk = (lane & 3) ^ swz(st_row);
+    const int64_t row_bytes = (int64_t)K / 2;
+    uint32_t src_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = st_row + 64 * (i & 1);
+        const int64_t grow = i < 2 ? min(m0 + row, M - 1) : min(n0 + row, N - 1);
+        src_off[i] = (uint32_t)(grow * row_bytes + st_chunk * 16);
+    }
+
+    v16i acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0;
+
+    constexpr int kCarry = BITS == 4 ? 6 : 8;
+    uint32_t nibble_mask = BITS == 4 ? 0xf0f0f0f0u : 0xe0e0e0e0u;
+    asm volatile("" : "+v"(nibble_mask));
+
+    const int steps = K / TK;
+    const uint32_t smem_addr = lds_address(smem);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#define QUEST_SMALL_DMA(STAGE, I, STEP)                                                                 \
+    lds_dma16(((I) < 2 ? a_codes : b_codes) + src_off[I] + (int64_t)min((STEP), steps - 1) * kRowBytes, \
+              (STAGE) + ((I) < 2 ? 0 : STM * kRowBytes) + (64 * ((I)&1) + 16 * wave_u) * kRowBytes)
+
+    static_for<4>([&](auto i) { QUEST_SMALL_DMA(smem_addr, decltype(i)::value, 0); });
+    static_for<4>([&](auto i) { QUEST_SMALL_DMA(smem_addr + kSmallStageBytes, decltype(i)::value, 1); });
+    float *scale_lds = reinterpret_cast<float *>(smem + kStages * kSmallStageBytes);
+    if (tid < STN)
+        scale_lds[tid] = b_scales[min(n0 + tid, N - 1)];
+    float sa_reg[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+        sa_reg[i] = a_scales[min(m0 + wm * 64 + i * 32 + lm, M - 1)] * (1.0f / (float)(1 << kCarry));
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    const int x = swz(lm);
+    const int a_off = (wm * 64 + lm) * kRowBytes;
+    const int b_off = STM * kRowBytes + (wn * 64 + lm) * kRowBytes;
+    uint4 af[2][2], bf[2][2];   // packed fragments of the two sub-step pairs
+    auto load_frag = [&](const uint8_t *stage, int p, int f) {
+        const int off = ((2 * p + lh) ^ x) << 4;
+        if (f < 2)
+            af[p][f] = *reinterpret_cast<const uint4 *>(stage + a_off + f * 32 * kRowBytes + off);
+        else
+            bf[p][f - 2] = *reinterpret_cast<const uint4 *>(stage + b_off + (f - 2) * 32 * kRowBytes + off);
+    };
+    static_for<4>([&](auto f) { load_frag(smem, 0, decltype(f)::value); });
+
+    // widened operands of sub-step g in set g % 2
+    v4i wa[2][2], wb[2][2];
+    auto widen_a = [&](auto gc, auto ic) {
+        constexpr int g = decltype(gc)::value & 3, i = decltype(ic)::value;
+        constexpr int p = g >> 1, e = g & 1;
+        int w0, w1, w2, w3;
+        widen8<BITS>(e ? af[p][i].z : af[p][i].x, nibble_mask, w0, w1);
+        widen8<BITS>(e ? af[p][i].w : af[p][i].y, nibble_mask, w2, w3);
+        wa[g & 1][i] = v4i{w0, w1, w2, w3};
+    };
+    auto widen_b = [&](auto gc, auto jc) {
+        constexpr int g = decltype(gc)::value & 3, j = decltype(jc)::value;
+        constexpr int p = g >> 1, e = g & 1;
+        int w0, w1, w2, w3;
+        widen8<BITS>(e ? bf[p][j].z : bf[p][j].x, nibble_mask, w0, w1);
+        widen8<BITS>(e ? bf[p][j].w : bf[p][j].y, nibble_mask, w2, w3);
+        wb[g & 1][j] = v4i{w0, w1, w2, w3};
+    };
+    static_for<2>([&](auto f) {
+        widen_a(std::integral_constant<int, 0>{}, f);
+        widen_b(std::integral_constant<int, 0>{}, f);
+    });
+
+    // Main loop: 16 MFMAs per step and wave.
+    //   MFMA k: sub-step g = k / 4, A fragment (k % 4) / 2, B fragment k % 2; after it one operand of
+    //           sub-step g + 1 is widened (B0, A0, B1, A1)
+    //   k = 0, 2, 4, 6   start the transfers of step + 2 into the stage that was read in step - 1
+    //   k = 0..3         load the packed fragments of pair 1 (first widened after k = 4)
+    //   k = 7            wait for this wave's transfers of step + 1 (all but the four newest), barrier
+    //   k = 8..11        load the packed fragments of pair 0 of step + 1 (first widened after k = 12)
+    int stage_cur = 0, stage_one = kSmallStageBytes, stage_two = 2 * kSmallStageBytes;
+    for (int step = 0; step < steps; ++step) {
+        const uint8_t *cur = smem + stage_cur;
+        const uint8_t *one = smem + stage_one;
+        static_for<16>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            constexpr int g = k >> 2, s = k & 3, i = s >> 1, j = s & 1;
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[g & 1][j], wa[g & 1][i], acc[i][j], 0, 0, 0);
+            if constexpr (s == 0)
+                widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
+            if constexpr (s == 1)
+                widen_a(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
+            if constexpr (s == 2)
+                widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 1>{});
+            if constexpr (s == 3)
+                widen_a(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 1>{});
+            if constexpr (k < 8 && (k & 1) == 0)
+                QUEST_SMALL_DMA(smem_addr + stage_two, k / 2, step + 2);
+            if constexpr (k < 4)
+                load_frag(cur, 1, k);
+            if constexpr (k == 7) {
+                wait_vmcnt<4>();
+                __builtin_amdgcn_s_barrier();
+            }
+            if constexpr (k >= 8 && k < 12)
+                load_frag(one, 0, k - 8);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        const int t = stage_cur;
+        stage_cur = stage_one;
+        stage_one = stage_two;
+        stage_two = t;
+    }
+    wait_vmcnt<0>();
+#undef QUEST_SMALL_DMA
+
+    // Epilogue as above, on a 64 x 64 block per wave.
+    __syncthreads();
+
+    if (acc_out) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * 64 + i * 32 + lm;
+                    const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    if (m < M && n < N)
+                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> kCarry;
+                }
+    }
+    if (!y)
+        return;
+
+    uint8_t *park = smem + wave * (64 * 128);
+    float4 sb_reg[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            sb_reg[j][q] = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + j * 32 + 8 * q + 4 * lh);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = i * 32 + lm;
+        const float sa = sa_reg[i];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = j * 32 + 8 * q + 4 * lh;
+                const float4 sb = sb_reg[j][q];
+                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
+                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
+                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
+                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
+                const int chunk = (col >> 3) ^ (row & 7);
+                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
+                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+            }
+        }
+    }
+    uint16_t *y_base = y + (int64_t)(m0 + wm * 64) * ld_y + n0 + wn * 64;
+    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
+                           (n0 + wn * 64 + 64 <= N);
+#pragma unroll 4
+    for (int pass = 0; pass < 8; ++pass) {
+        const int row = pass * 8 + (lane >> 3);
+        const int c = lane & 7;
+        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
+        if (m0 + wm * 64 + row >= M)
+            continue;
+        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
+        if (vector_ok) {
+            *reinterpret_cast<uint4 *>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n0 + wn * 64 + c * 8 + e < N)
+                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Wide kernel for b = 4 and long contractions (K >= 4096).  Workgroup tile 256 x 256, eight waves of
 // 128 x 64 (two per SIMD), 256 contraction elements per step, two LDS stages of 64 KiB, one
 // workgroup per CU.  The codes of a tile step have to come through the CU's vector-memory path
@@ -774,7 +1009,7 @@ hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
     if (args.M == 0 || args.N == 0)
         return hipSuccess;
     GemmArgs a = args;
-    if (a.bits <= 2 && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
+    if (a.bits <= 2 && (a.K % TK) == 0 && a.M >= 128 && a.N >= 128) {
         int device = 0;
         char *memory = nullptr;
         hipError_t err = hipGetDevice(&device);
@@ -813,6 +1048,27 @@ hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
                                a.acc_out);
         else
             hipLaunchKernelGGL(lowbit_gemm_wide_kernel<3>, grid, block, kWideLds, stream, a.a_codes, a.a_scales,
+                               a.b_codes, a.b_scales, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y,
+                               a.acc_out);
+        return hipGetLastError();
+    }
+    // fewer 256 x 128 tiles than three quarters of the chip's slots (two per CU): 128 x 128 tiles
+    const int64_t big_tiles = ((a.M + TM - 1) / TM) * ((a.N + TN - 1) / TN);
+    if ((a.bits == 4 || a.bits == 3) && (a.K % TK) == 0 && a.M >= 128 && a.N >= 128 && big_tiles < 384) {
+        const int tiles_m = (int)((a.M + STM - 1) / STM), tiles_n = (int)((a.N + STN - 1) / STN);
+        const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_small_kernel<4>), kSmallLds);
+        if (err == hipSuccess)
+            err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_small_kernel<3>), kSmallLds);
+        if (err != hipSuccess)
+            return err;
+        const dim3 grid((unsigned)(per_xcd * 8)), block(kTileThreads);
+        if (a.bits == 4)
+            hipLaunchKernelGGL(lowbit_gemm_small_kernel<4>, grid, block, kSmallLds, stream, a.a_codes, a.a_scales,
+                               a.b_codes, a.b_scales, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y,
+                               a.acc_out);
+        else
+            hipLaunchKernelGGL(lowbit_gemm_small_kernel<3>, grid, block, kSmallLds, stream, a.a_codes, a.a_scales,
                                a.b_codes, a.b_scales, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, y, a.ld_y,
                                a.acc_out);
         return hipGetLastError();

@@ -309,6 +309,39 @@ def test_gemm_full_size_sampled_rows():
     assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.25
 
 
+@pytest.mark.parametrize("M,N,K,bits", [(4000, 4100, 384, 3),      # 256 x 128 tiles, ragged edges
+                                        (4090, 3100, 4096, 3), (4090, 3100, 4352, 4),   # 256 x 256 tiles
+                                        (3000, 1100, 640, 4), (3000, 1100, 640, 3)])    # 128 x 128 tiles
+def test_gemm_kernel_variants_sampled_rows(M, N, K, bits):
+    """Every tile size of the matmul at b = 3 and b = 4, ragged last tiles, random codes with extreme
+    rows: accumulators of sampled rows (first, last, rows around tile edges) against the oracle."""
+    rng = np.random.default_rng(M + N + K + bits)
+    L = 1 << bits
+    ka = rng.integers(-L // 2, L // 2, size=(M, K), dtype=np.int32)
+    kb = rng.integers(-L // 2, L // 2, size=(N, K), dtype=np.int32)
+    ka[0] = L // 2 - 1
+    kb[0] = L // 2 - 1
+    kb[N - 1] = -L // 2
+    from oracle.quest_oracle import _load, _ptr
+    a_codes = np.empty((M, K // 2), dtype=np.uint8)
+    b_codes = np.empty((N, K // 2), dtype=np.uint8)
+    _load().qo_pack_codes(_ptr(ka), M, K, bits, _ptr(a_codes))
+    _load().qo_pack_codes(_ptr(kb), N, K, bits, _ptr(b_codes))
+    sa = (rng.random(M) + 0.5).astype(np.float32)
+    sb = ((rng.random(N) + 0.5) * 0.01).astype(np.float32)
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    acc = torch.empty(M, N, dtype=torch.int32, device=DEV)
+    q.quest_lowbit_gemm(to_device(a_codes), to_device(sa), to_device(b_codes), to_device(sb), K, bits, y=y, acc_out=acc)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, M - 257, M - 129, M - 2, M - 1],
+                                     rng.choice(M, size=24, replace=False)]))
+    ref_acc = qo.gemm_odd(2 * ka[rows] + 1, 2 * kb + 1)
+    pick = torch.from_numpy(rows).to(DEV)
+    assert np.array_equal(acc[pick].cpu().numpy().astype(np.int64), ref_acc)
+    assert ref_acc[0, 0] == (L - 1) ** 2 * K and ref_acc[0, N - 1] == -(L - 1) ** 2 * K
+    check_gemm_output(y[pick], ref_acc, sa[rows], sb)
+
+
 FP4_GEMM_CASES = [(256, 512, 512), (130, 200, 1024), (1, 1, 128), (257, 129, 2048), (64, 640, 5632),
                   (700, 600, 512), (513, 1025, 1024), (4000, 4100, 384),
                   # long contractions, whole and ragged tiles
