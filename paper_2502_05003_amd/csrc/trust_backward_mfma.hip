@@ -260,7 +260,7 @@ void launch(const BackwardArgs &a, hipStream_t stream)
 // elements with a Hadamard block of at most 32, or 128, 256 (11008 only), 512, 1024, 2048, 4096 where
 // it divides the row, and for the other widths of the paper's model family (640, 768, 1280, 1664,
 // 1792, 2816, 3584, 4608) with a block of at most 32 or their widest one; fp32 out (a weight
-// gradient for an fp32 optimizer) for rows of 512 .. 5632 with their widest block.
+// gradient for an fp32 optimizer) for all of these row lengths with their widest block.
 bool launch_trust_backward_mfma(const BackwardArgs &a, hipStream_t stream)
 {
     if (a.g_dtype != QUEST_BF16 || (a.cols % 128) != 0)
@@ -274,7 +274,9 @@ bool launch_trust_backward_mfma(const BackwardArgs &a, hipStream_t stream)
         return true;                               \
     }
         QUEST_F32_OUT_CASE(4, 9) QUEST_F32_OUT_CASE(8, 10) QUEST_F32_OUT_CASE(16, 11) QUEST_F32_OUT_CASE(32, 12)
-        QUEST_F32_OUT_CASE(44, 9)
+        QUEST_F32_OUT_CASE(44, 9) QUEST_F32_OUT_CASE(86, 8)
+        QUEST_F32_OUT_CASE(5, 7) QUEST_F32_OUT_CASE(6, 8) QUEST_F32_OUT_CASE(10, 8) QUEST_F32_OUT_CASE(13, 7)
+        QUEST_F32_OUT_CASE(14, 8) QUEST_F32_OUT_CASE(22, 8) QUEST_F32_OUT_CASE(28, 9) QUEST_F32_OUT_CASE(36, 9)
 #undef QUEST_F32_OUT_CASE
         return false;
     }

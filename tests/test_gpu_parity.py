@@ -420,6 +420,8 @@ BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16")
               (37, 640, 128, "bf16", "bf16"), (37, 768, 256, "bf16", "bf16"), (37, 1280, 256, "bf16", "bf16"),
               (37, 1664, 128, "bf16", "bf16"), (37, 1792, 256, "bf16", "bf16"), (37, 2816, 256, "bf16", "bf16"),
               (37, 3584, 512, "bf16", "bf16"), (37, 4608, 512, "bf16", "bf16"), (9, 1664, 16, "bf16", "bf16"),
+              (37, 640, 128, "bf16", "f32"), (37, 1664, 128, "bf16", "f32"), (37, 2816, 256, "bf16", "f32"),
+              (37, 4608, 512, "bf16", "f32"), (21, 11008, 256, "bf16", "f32"),
               # blocks that span two of a row's four tiles, and one of them
               (33, 4096, 2048, "bf16", "bf16"), (33, 4096, 1024, "bf16", "bf16"), (33, 4096, 128, "bf16", "bf16")]
 
