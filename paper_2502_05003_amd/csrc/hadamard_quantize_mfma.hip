@@ -163,7 +163,7 @@ struct TransposePlan {
 template <int U, bool HOLD_ALL, bool F32>
 constexpr int hq_waves_per_eu()
 {
-    return (HOLD_ALL && (U > 32 || (F32 && U == 32))) ? 2 : U > 40 ? 3 : QUEST_HQ_WAVES_PER_EU;
+    return (HOLD_ALL && (U > 32 || (F32 && U >= 24))) ? 2 : U > 40 ? 3 : QUEST_HQ_WAVES_PER_EU;
 }
 
 template <int U, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4, typename In = uint16_t,
@@ -661,7 +661,8 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
 //     hidden and MLP widths of the paper's model family (640, 768, 1280, 1664, 1792, 2816, 3584,
 //     4608) with a block of at most 32 or their widest one;
 //   bf16 rows, b = 1, 2, 3, 8 and the E2M1 grid: rows of 1024 .. 5632 with their widest block;
-//   fp32 rows and the AbsMax scale, b = 4: rows of 512 .. 5632 with their widest block.
+//   fp32 rows and the AbsMax scale, b = 4: rows of 512 .. 5632 with their widest block; fp32 rows
+//     also for the other model widths up to 4608.
 bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream)
 {
     if ((a.cols % 128) != 0)
@@ -684,6 +685,16 @@ bool launch_hadamard_quantize_mfma(const QuantizeArgs &a, hipStream_t stream)
         QUEST_HOLD_CASE(4, 9) QUEST_HOLD_CASE(8, 10) QUEST_HOLD_CASE(16, 11) QUEST_HOLD_CASE(32, 12)
         QUEST_HOLD_CASE(44, 9)
 #undef QUEST_HOLD_CASE
+        if (a.dtype == QUEST_F32 && a.mode == kQuantRms) {   // fp32 master weights of the smaller models
+#define QUEST_F32_CASE(U_, L_)                                           \
+    if (u == U_ && l == L_) {                                            \
+        launch<U_, L_, false, 4, float, false>(a, stream);               \
+        return true;                                                     \
+    }
+            QUEST_F32_CASE(5, 7) QUEST_F32_CASE(6, 8) QUEST_F32_CASE(10, 8) QUEST_F32_CASE(13, 7)
+            QUEST_F32_CASE(14, 8) QUEST_F32_CASE(22, 8) QUEST_F32_CASE(28, 9) QUEST_F32_CASE(36, 9)
+#undef QUEST_F32_CASE
+        }
         return false;
     }
     if (a.bits != 4) {   // the other widths of the Eq. 1 grid

@@ -67,6 +67,8 @@ QUANT_CASES = [
     (37, 640, 128, 4, "bf16"), (37, 768, 256, 4, "bf16"), (37, 1280, 256, 4, "bf16"), (37, 1664, 128, 4, "bf16"),
     (37, 1792, 256, 4, "bf16"), (37, 2816, 256, 4, "bf16"), (37, 3584, 512, 4, "bf16"), (37, 4608, 512, 4, "bf16"),
     (9, 640, 1, 4, "bf16"), (9, 1664, 32, 4, "bf16"), (9, 2816, 8, 4, "bf16"), (9, 4608, 1, 4, "bf16"),
+    (37, 640, 128, 4, "f32"), (37, 768, 256, 4, "f32"), (37, 1280, 256, 4, "f32"), (37, 1664, 128, 4, "f32"),
+    (37, 1792, 256, 4, "f32"), (37, 2816, 256, 4, "f32"), (37, 3584, 512, 4, "f32"), (37, 4608, 512, 4, "f32"),
     # blocks that span two of a row's four tiles, and one of them
     (33, 4096, 2048, 4, "bf16"), (33, 4096, 1024, 4, "bf16"), (33, 4096, 512, 4, "bf16"),
 ]
