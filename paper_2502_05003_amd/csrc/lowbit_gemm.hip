@@ -240,6 +240,87 @@ __device__ __forceinline__ void widen8(uint32_t w, uint32_t field_mask, int &eve
     even = (int)__builtin_amdgcn_bitop3_b32(w << (8 - BITS), field_mask, forced, 0x6A);
 }
 
+// Epilogue shared by the tile kernels.  Each 32 x 32 accumulator tile is the transpose of an output
+// tile: lane l holds output row l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) +
+// r % 4, i.e. runs of four consecutive columns.  A wave owns a block of 32 AF rows by 64 columns at
+// (row0, col0): it writes the raw accumulators if asked to, converts the block to bf16
+// (float(acc) * s_a, then * s_b), parks it in its own LDS (128-byte rows, 16-byte chunks swizzled
+// by row) and writes it out as 128-byte row segments.  CARRY: log2 of the factor the products carry
+// (sa_reg already holds s_a / 2^CARRY).  Every wave of the workgroup must be done with the LDS
+// that `park` points into.
+template <int AF, int CARRY>
+__device__ __forceinline__ void store_wave_block(const v16i (&acc)[AF][2], const float (&sa_reg)[AF],
+                                                 const float *scale_lds_wave, uint8_t *park, int row0, int col0,
+                                                 int M, int N, uint16_t *__restrict__ y, int64_t ld_y,
+                                                 int32_t *__restrict__ acc_out, int lane)
+{
+    const int lm = lane & 31, lh = lane >> 5;
+    if (acc_out) {
+#pragma unroll
+        for (int i = 0; i < AF; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = row0 + i * 32 + lm;
+                    const int n = col0 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    if (m < M && n < N)
+                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> CARRY;   // exact: a multiple of 2^CARRY
+                }
+    }
+    if (!y)
+        return;
+    // the weight scales of this lane's columns, read once (the park writes below would otherwise keep
+    // the compiler from re-using them across the row blocks)
+    float4 sb_reg[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            sb_reg[j][q] = *reinterpret_cast<const float4 *>(scale_lds_wave + j * 32 + 8 * q + 4 * lh);
+#pragma unroll
+    for (int i = 0; i < AF; ++i) {
+        const int row = i * 32 + lm;   // row within the wave's block
+        const float sa = sa_reg[i];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = j * 32 + 8 * q + 4 * lh;   // first of four consecutive columns
+                const float4 sb = sb_reg[j][q];
+                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
+                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
+                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
+                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
+                const int chunk = (col >> 3) ^ (row & 7);
+                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
+                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+            }
+        }
+    }
+    // each pass: 8 rows of 128 bytes, lane l takes 16-byte chunk l % 8 of row l / 8
+    uint16_t *y_base = y + (int64_t)row0 * ld_y + col0;
+    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) && (col0 + 64 <= N);
+#pragma unroll 4
+    for (int pass = 0; pass < 4 * AF; ++pass) {
+        const int row = pass * 8 + (lane >> 3);
+        const int c = lane & 7;
+        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
+        if (row0 + row >= M)
+            continue;
+        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
+        if (vector_ok) {
+            *reinterpret_cast<uint4 *>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (col0 + c * 8 + e < N)
+                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
 template <int BITS>
 __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     const uint8_t *__restrict__ a_codes, const float *__restrict__ a_scales,
@@ -409,79 +490,10 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     wait_vmcnt<0>();   // all transfers landed before the stages are reused
 #undef QUEST_DMA
 
-    // Epilogue.  Each accumulator tile is the transpose of an output tile: lane l holds output row
-    // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
-    // consecutive columns.  Each wave converts its 128 x 64 block to bf16, parks it in its own
-    // 16 KiB of LDS (16-byte chunks swizzled by row) and writes it out as 128-byte row segments.
+    // Epilogue: each wave's 128 x 64 block (see store_wave_block), parked in the stages.
     __syncthreads();   // every wave is done with the stages
-
-    if (acc_out) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * 128 + i * 32 + lm;
-                    const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (m < M && n < N)
-                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> kCarry;   // exact: a multiple of 2^kCarry
-                }
-    }
-    if (!y)
-        return;
-
-    uint8_t *park = smem + wave * (128 * 128);
-    // the weight scales of this lane's columns, read once (the park writes below would otherwise keep
-    // the compiler from re-using them across the four row blocks)
-    float4 sb_reg[2][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            sb_reg[j][q] = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + j * 32 + 8 * q + 4 * lh);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = i * 32 + lm;   // row within the wave's block
-        const float sa = sa_reg[i];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = j * 32 + 8 * q + 4 * lh;   // first of four consecutive columns
-                const float4 sb = sb_reg[j][q];
-                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
-                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
-                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
-                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
-                const int chunk = (col >> 3) ^ (row & 7);
-                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
-                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-            }
-        }
-    }
-    // each pass: 8 rows of 128 bytes, lane l takes 16-byte chunk l % 8 of row l / 8
-    uint16_t *y_base = y + (int64_t)(m0 + wm * 128) * ld_y + n0 + wn * 64;
-    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
-                           (n0 + wn * 64 + 64 <= N);
-#pragma unroll 4
-    for (int pass = 0; pass < 16; ++pass) {
-        const int row = pass * 8 + (lane >> 3);
-        const int c = lane & 7;
-        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
-        if (m0 + wm * 128 + row >= M)
-            continue;
-        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
-        if (vector_ok) {
-            *reinterpret_cast<uint4 *>(dst) = v;
-        } else {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (n0 + wn * 64 + c * 8 + e < N)
-                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-        }
-    }
+    store_wave_block<4, kCarry>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (128 * 128), m0 + wm * 128,
+                                n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -650,73 +662,10 @@ __global__ __launch_bounds__(kTileThreads, 3) void lowbit_gemm_small_kernel(
     wait_vmcnt<0>();
 #undef QUEST_SMALL_DMA
 
-    // Epilogue as above, on a 64 x 64 block per wave.
+    // Epilogue: each wave's 64 x 64 block (see store_wave_block), parked in the stages.
     __syncthreads();
-
-    if (acc_out) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * 64 + i * 32 + lm;
-                    const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (m < M && n < N)
-                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> kCarry;
-                }
-    }
-    if (!y)
-        return;
-
-    uint8_t *park = smem + wave * (64 * 128);
-    float4 sb_reg[2][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            sb_reg[j][q] = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + j * 32 + 8 * q + 4 * lh);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = i * 32 + lm;
-        const float sa = sa_reg[i];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = j * 32 + 8 * q + 4 * lh;
-                const float4 sb = sb_reg[j][q];
-                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
-                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
-                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
-                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
-                const int chunk = (col >> 3) ^ (row & 7);
-                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
-                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-            }
-        }
-    }
-    uint16_t *y_base = y + (int64_t)(m0 + wm * 64) * ld_y + n0 + wn * 64;
-    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
-                           (n0 + wn * 64 + 64 <= N);
-#pragma unroll 4
-    for (int pass = 0; pass < 8; ++pass) {
-        const int row = pass * 8 + (lane >> 3);
-        const int c = lane & 7;
-        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
-        if (m0 + wm * 64 + row >= M)
-            continue;
-        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
-        if (vector_ok) {
-            *reinterpret_cast<uint4 *>(dst) = v;
-        } else {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (n0 + wn * 64 + c * 8 + e < N)
-                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-        }
-    }
+    store_wave_block<2, kCarry>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (64 * 128), m0 + wm * 64,
+                                n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -888,79 +837,10 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     }
 #undef QUEST_WIDE_DMA
 
-    // Epilogue.  Each accumulator tile is the transpose of an output tile: lane l holds output row
-    // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
-    // consecutive columns.  Each wave converts its 128 x 64 block to bf16, parks it in its own
-    // 16 KiB of LDS (16-byte chunks swizzled by row) and writes it out as 128-byte row segments.
+    // Epilogue: each wave's 128 x 64 block (see store_wave_block), parked in the stages.
     __syncthreads();   // every wave is done with the stages
-
-    if (acc_out) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * 128 + i * 32 + lm;
-                    const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (m < M && n < N)
-                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> kCarry;   // exact: a multiple of 2^kCarry
-                }
-    }
-    if (!y)
-        return;
-
-    uint8_t *park = smem + wave * (128 * 128);
-    // the weight scales of this lane's columns, read once (the park writes below would otherwise keep
-    // the compiler from re-using them across the four row blocks)
-    float4 sb_reg[2][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            sb_reg[j][q] = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + j * 32 + 8 * q + 4 * lh);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = i * 32 + lm;   // row within the wave's block
-        const float sa = sa_reg[i];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = j * 32 + 8 * q + 4 * lh;   // first of four consecutive columns
-                const float4 sb = sb_reg[j][q];
-                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
-                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
-                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
-                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
-                const int chunk = (col >> 3) ^ (row & 7);
-                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
-                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-            }
-        }
-    }
-    // each pass: 8 rows of 128 bytes, lane l takes 16-byte chunk l % 8 of row l / 8
-    uint16_t *y_base = y + (int64_t)(m0 + wm * 128) * ld_y + n0 + wn * 64;
-    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
-                           (n0 + wn * 64 + 64 <= N);
-#pragma unroll 4
-    for (int pass = 0; pass < 16; ++pass) {
-        const int row = pass * 8 + (lane >> 3);
-        const int c = lane & 7;
-        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
-        if (m0 + wm * 128 + row >= M)
-            continue;
-        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
-        if (vector_ok) {
-            *reinterpret_cast<uint4 *>(dst) = v;
-        } else {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (n0 + wn * 64 + c * 8 + e < N)
-                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-        }
-    }
+    store_wave_block<4, kCarry>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (128 * 128), m0 + wm * 128,
+                                n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
 }
 
 // ------------------------------------------------------------------------------------------
