@@ -29,13 +29,12 @@
 // fp32 rows, the sum of squares is gathered while the tiles stream in).  An fp32 input is cut into
 // three bf16 pieces, x = hi + mid + lo exactly (8 + 8 + 8 significant bits), each of which goes
 // through the same exact +-1 product; the fp32 MFMA would be sixteen times slower.
-#include "quest_device.h"
+#include "hadamard_tile.h"
 #include "quest_internal.h"
 
 namespace quest {
 namespace {
 
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
@@ -56,22 +55,6 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kRowsPerBlock = kThreads / 64;
-
-// In-lane element index iota = b6 + 2 b7 + 4 b8 + 8 b9 + 16 tile (bN = index bit N of the
-// element) -> accumulator register within its tile, after the half-wave swap:
-// b7 = r & 1, b6 = (r >> 1) & 1, b8 = (r >> 2) & 1, b9 = r >> 3.
-__host__ __device__ constexpr int reg_of_iota(int iota)
-{
-    return ((iota >> 1) & 1) | ((iota & 1) << 1) | (((iota >> 2) & 1) << 2) |
-           (((iota >> 3) & 1) << 3);
-}
-
-__device__ __forceinline__ void bfly(float &a, float &b)
-{
-    const float t = a;
-    a = t + b;
-    b = t - b;
-}
 
 __device__ __forceinline__ void store_word(uint32_t *p, uint32_t v)
 {
@@ -197,26 +180,7 @@ void hq_mfma_kernel(
 
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
     v8bf bmat[2];
-    {
-        const int nb = log2n < 5 ? log2n : 5;
-        const int low = (1 << nb) - 1;
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            uint32_t w[4];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int q = 16 * h + 8 * s + e;
-                uint32_t v = 0;
-                if ((q >> nb) == (m >> nb))
-                    v = (__builtin_popcount(q & m & low) & 1) ? 0xBF80u : 0x3F80u;
-                if (e & 1)
-                    w[e >> 1] |= v << 16;
-                else
-                    w[e >> 1] = v;
-            }
-            __builtin_memcpy(&bmat[s], w, 16);
-        }
-    }
+    hadamard_operand(log2n, m, h, bmat);
     // fp32 rows: the middle piece is carried with its sign flipped (see below) and meets -H
     v8bf bneg[2];
     if constexpr (kF32) {
@@ -245,11 +209,7 @@ void hq_mfma_kernel(
     if (WITH_MASK)
         bit_plan.init(lane);
 
-    // sqrt(n) and 1 / sqrt(n), correctly rounded: powers of two, times sqrt(2) for odd log2(n)
-    const float inv_sqrt_n = (log2n & 1) ? 0.70710678118654752440f / (float)(1 << (log2n >> 1))
-                                         : 1.0f / (float)(1 << (log2n >> 1));
-    const float sqrt_n = (log2n & 1) ? 1.41421356237309504880f * (float)(1 << (log2n >> 1))
-                                     : (float)(1 << (log2n >> 1));
+    const float inv_sqrt_n = inv_sqrt_pow2(log2n), sqrt_n = sqrt_pow2(log2n);
     const int code_word = ((lane >> 3) & 3) + 4 * h + 8 * (lane & 7);
 
     // Raw inputs of one bf16 row: two 16-byte pieces per tile and lane.
@@ -423,66 +383,7 @@ void hq_mfma_kernel(
                 }
             }
 
-            if (LOG2N > 5) {  // bit 5 = register bit 0
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 2)
-                        bfly(acc[u][r], acc[u][r + 1]);
-            }
-            if (LOG2N > 6) {  // bit 6 = register bit 1
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (!(r & 2))
-                            bfly(acc[u][r], acc[u][r + 2]);
-            }
-            // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
-#pragma unroll
-            for (int u = 0; u < G; ++u)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[u][r]),
-                                                                     __float_as_uint(acc[u][r + 1]),
-                                                                     false, false);
-                    acc[u][r] = __uint_as_float(sw[0]);
-                    acc[u][r + 1] = __uint_as_float(sw[1]);
-                }
-            if (LOG2N > 7) {
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 2)
-                        bfly(acc[u][r], acc[u][r + 1]);
-            }
-            if (LOG2N > 8) {  // bit 8 = register bit 2
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (!(r & 4))
-                            bfly(acc[u][r], acc[u][r + 4]);
-            }
-            if (LOG2N > 9) {  // bit 9 = register bit 3
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 8; ++r)
-                        bfly(acc[u][r], acc[u][r + 8]);
-            }
-#pragma unroll
-            for (int k = 0; (1 << k) < G; ++k) {  // bits >= 10 pair whole tiles (then G = T)
-                if (LOG2N > 10 + k) {
-#pragma unroll
-                    for (int u = 0; u < G; ++u)
-                        if (!(u & (1 << k)) && (u | (1 << k)) < G) {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                bfly(acc[u][r], acc[u | (1 << k)][r]);
-                        }
-                }
-            }
+            tile_stages<LOG2N, G>(acc);
 
             if constexpr (kHoldAll) {   // the whole row is transformed: now its scale can be fixed
                 float raw_max = 0.0f;

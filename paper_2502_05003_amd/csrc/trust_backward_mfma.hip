@@ -11,13 +11,12 @@
 //     and one exchange with the neighbouring lane turns those into pairs of adjacent elements, so
 //     that a wave stores 256 contiguous bytes per instruction;
 //   * fp32 outputs are stored as they are, 64 consecutive floats per wave instruction.
-#include "quest_device.h"
+#include "hadamard_tile.h"
 #include "quest_internal.h"
 
 namespace quest {
 namespace {
 
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
@@ -28,21 +27,6 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kRowsPerBlock = kThreads / 64;
-
-// in-lane element index iota = b6 + 2 b7 + 4 b8 + 8 b9 + 16 tile -> accumulator register in its tile
-// (after the half-wave swap: b7 = r & 1, b6 = (r >> 1) & 1, b8 = (r >> 2) & 1, b9 = r >> 3)
-__host__ __device__ constexpr int reg_of_iota(int iota)
-{
-    return ((iota >> 1) & 1) | ((iota & 1) << 1) | (((iota >> 2) & 1) << 2) |
-           (((iota >> 3) & 1) << 3);
-}
-
-__device__ __forceinline__ void bfly(float &a, float &b)
-{
-    const float t = a;
-    a = t + b;
-    b = t - b;
-}
 
 __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi)
 {
@@ -81,28 +65,8 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
 
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
     v8bf bmat[2];
-    {
-        const int nb = log2n < 5 ? log2n : 5;
-        const int low = (1 << nb) - 1;
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            uint32_t w[4];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int q = 16 * h + 8 * s + e;
-                uint32_t v = 0;
-                if ((q >> nb) == (m >> nb))
-                    v = (__builtin_popcount(q & m & low) & 1) ? 0xBF80u : 0x3F80u;
-                if (e & 1)
-                    w[e >> 1] |= v << 16;
-                else
-                    w[e >> 1] = v;
-            }
-            __builtin_memcpy(&bmat[s], w, 16);
-        }
-    }
-    const float inv_sqrt_n = (log2n & 1) ? 0.70710678118654752440f / (float)(1 << (log2n >> 1))
-                                         : 1.0f / (float)(1 << (log2n >> 1));
+    hadamard_operand(log2n, m, h, bmat);
+    const float inv_sqrt_n = inv_sqrt_pow2(log2n);
     // exchange with lane ^ 1: even lanes keep the low halves, odd lanes the high halves
     const uint32_t pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
 
@@ -145,66 +109,7 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
                     acc[u][r] = z[r];
             }
 
-            if (LOG2N > 5) {  // bit 5 = register bit 0
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 2)
-                        bfly(acc[u][r], acc[u][r + 1]);
-            }
-            if (LOG2N > 6) {  // bit 6 = register bit 1
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (!(r & 2))
-                            bfly(acc[u][r], acc[u][r + 2]);
-            }
-            // bit 7 is the half-wave index: swap it with register bit 0 (h then holds bit 5)
-#pragma unroll
-            for (int u = 0; u < G; ++u)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[u][r]),
-                                                                     __float_as_uint(acc[u][r + 1]),
-                                                                     false, false);
-                    acc[u][r] = __uint_as_float(sw[0]);
-                    acc[u][r + 1] = __uint_as_float(sw[1]);
-                }
-            if (LOG2N > 7) {
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 2)
-                        bfly(acc[u][r], acc[u][r + 1]);
-            }
-            if (LOG2N > 8) {  // bit 8 = register bit 2
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (!(r & 4))
-                            bfly(acc[u][r], acc[u][r + 4]);
-            }
-            if (LOG2N > 9) {  // bit 9 = register bit 3
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int r = 0; r < 8; ++r)
-                        bfly(acc[u][r], acc[u][r + 8]);
-            }
-#pragma unroll
-            for (int k = 0; (1 << k) < G; ++k) {  // bits >= 10 pair whole tiles
-                if (LOG2N > 10 + k) {
-#pragma unroll
-                    for (int u = 0; u < G; ++u)
-                        if (!(u & (1 << k)) && (u | (1 << k)) < G) {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                bfly(acc[u][r], acc[u | (1 << k)][r]);
-                        }
-                }
-            }
+            tile_stages<LOG2N, G>(acc);
 
             // element = (lane & 31) + 32 h + 64 iota; this group holds iota = 16 g0 .. as far as the row goes
             constexpr int kGroupI = 16 * G;
