@@ -11,40 +11,15 @@
 // (lane l: row l % 32, elements 32 (l / 32) .. + 32 of the 64-element sub-step), so a 16-byte LDS
 // read is an operand.
 #include <algorithm>
-#include <utility>
 
-#include "quest_device.h"
+#include "gemm_tile.h"
 #include "quest_internal.h"
 
 namespace quest {
 namespace {
 
-// compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>)
-template <int... Is, typename F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
-
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-
-// two floats -> packed bf16 pair (round to nearest even), low half = first
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-    v2bf p;
-    p[0] = (__bf16)lo;
-    p[1] = (__bf16)hi;
-    uint32_t u;
-    __builtin_memcpy(&u, &p, 4);
-    return u;
-}
 
 constexpr int TM = 256, TN = 128, TK = 128;
 constexpr int kTileThreads = 256;
@@ -198,79 +173,10 @@ __global__ __launch_bounds__(kTileThreads, 2) void fp4_gemm_tile_kernel(
     wait_vmcnt<0>();   // all transfers landed before the stages are reused
 #undef QUEST_DMA
 
-    // Epilogue.  Each accumulator tile is the transpose of an output tile: lane l holds output row
-    // l % 32 and, in register r, output column 8 (r / 4) + 4 (l / 32) + r % 4, i.e. runs of four
-    // consecutive columns.  Each wave converts its 128 x 64 block to bf16, parks it in its own
-    // 16 KiB of LDS (16-byte chunks swizzled by row) and writes it out as 128-byte row segments.
+    // Epilogue: each wave's 128 x 64 block (see store_wave_block), parked in the stages.
     __syncthreads();   // every wave is done with the stages
-
-    if (acc_out) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * 128 + i * 32 + lm;
-                    const int n = n0 + wn * 64 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (m < M && n < N)
-                        acc_out[(int64_t)m * N + n] = acc[i][j][r];
-                }
-    }
-    if (!y)
-        return;
-
-    uint8_t *park = smem + wave * (128 * 128);
-    // the weight scales of this lane's columns, read once (the park writes below would otherwise keep
-    // the compiler from re-using them across the four row blocks)
-    float4 sb_reg[2][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            sb_reg[j][q] = *reinterpret_cast<const float4 *>(scale_lds + wn * 64 + j * 32 + 8 * q + 4 * lh);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = i * 32 + lm;   // row within the wave's block
-        const float sa = sa_reg[i];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = j * 32 + 8 * q + 4 * lh;   // first of four consecutive columns
-                const float4 sb = sb_reg[j][q];
-                const float v0 = __fmul_rn(__fmul_rn(acc[i][j][4 * q + 0], sa), sb.x);
-                const float v1 = __fmul_rn(__fmul_rn(acc[i][j][4 * q + 1], sa), sb.y);
-                const float v2 = __fmul_rn(__fmul_rn(acc[i][j][4 * q + 2], sa), sb.z);
-                const float v3 = __fmul_rn(__fmul_rn(acc[i][j][4 * q + 3], sa), sb.w);
-                const int chunk = (col >> 3) ^ (row & 7);
-                *reinterpret_cast<uint2 *>(park + row * 128 + chunk * 16 + (col & 4) * 2) =
-                    make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-            }
-        }
-    }
-    // each pass: 8 rows of 128 bytes, lane l takes 16-byte chunk l % 8 of row l / 8
-    uint16_t *y_base = y + (int64_t)(m0 + wm * 128) * ld_y + n0 + wn * 64;
-    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
-                           (n0 + wn * 64 + 64 <= N);
-#pragma unroll 4
-    for (int pass = 0; pass < 16; ++pass) {
-        const int row = pass * 8 + (lane >> 3);
-        const int c = lane & 7;
-        const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((c ^ (row & 7)) << 4));
-        if (m0 + wm * 128 + row >= M)
-            continue;
-        uint16_t *dst = y_base + (int64_t)row * ld_y + c * 8;
-        if (vector_ok) {
-            *reinterpret_cast<uint4 *>(dst) = v;
-        } else {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (n0 + wn * 64 + c * 8 + e < N)
-                    dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-        }
-    }
+    store_wave_block<4, 0>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (128 * 128), m0 + wm * 128,
+                           n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
 }
 
 }  // namespace

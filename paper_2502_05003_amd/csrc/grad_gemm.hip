@@ -9,7 +9,7 @@
 #include <numeric>
 #include <utility>
 
-#include "quest_device.h"
+#include "gemm_tile.h"
 #include "quest_internal.h"
 
 namespace quest {
@@ -141,29 +141,6 @@ constexpr ReadOp kReadsPlain[12] = {{false, 0, 0}, {false, 0, 1}, {true, 0, -1},
                                     {false, 1, 1}, {false, 2, 0}, {false, 2, 1}, {false, 3, 0},
                                     {false, 3, 1}, {true, 1, -1}, {true, 2, -1}, {true, 3, -1}};
 
-__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
-{
-    typedef __bf16 v2bf16 __attribute__((ext_vector_type(2)));
-    v2bf16 p;
-    p[0] = (__bf16)lo;
-    p[1] = (__bf16)hi;
-    uint32_t u;
-    __builtin_memcpy(&u, &p, 4);
-    return u;
-}
-
-// compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>)
-template <int... Is, typename F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
-
 // Expands packed codes to bf16(fp32(s * u)), u = 2 c - (L - 1): eight elements per thread.
 // levels = 0 stands for E2M1 codes (Sec. 4.4): u is then the signed E2M1 value of the code.
 __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__restrict__ codes,
@@ -199,8 +176,8 @@ __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__rest
             v[e] = __fmul_rn(s, __fmaf_rn((float)c, 2.0f, offset));
         }
     }
-    *reinterpret_cast<uint4 *>(qhat + g * 8) = make_uint4(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]),
-                                                          pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7]));
+    *reinterpret_cast<uint4 *>(qhat + g * 8) = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]),
+                                                          pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
 }
 
 // Work is counted in (tile, step) units: tile t owns the units [t * steps, (t + 1) * steps) and
@@ -488,8 +465,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
                 const int col = j * 32 + 8 * q + 4 * lh;
                 const int chunk = (col >> 3) ^ (row & 15);
                 *reinterpret_cast<uint2 *>(park + row * 256 + chunk * 16 + (col & 4) * 2) =
-                    make_uint2(pack2_bf16(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1]),
-                               pack2_bf16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+                    make_uint2(pack_bf16(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1]),
+                               pack_bf16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
             }
         }
     }
@@ -547,7 +524,7 @@ __global__ __launch_bounds__(256) void grad_gemm_fixup_kernel(const float4 *__re
     for (int q = 0; q < 4; ++q) {
         const int col = 8 * q + 4 * lh;
         *reinterpret_cast<uint2 *>(park + lm * 64 + col * 2) =
-            make_uint2(pack2_bf16(sum[q].x, sum[q].y), pack2_bf16(sum[q].z, sum[q].w));
+            make_uint2(pack_bf16(sum[q].x, sum[q].y), pack_bf16(sum[q].z, sum[q].w));
     }
     __syncthreads();
     int r0, k0;
