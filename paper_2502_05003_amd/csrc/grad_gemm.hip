@@ -240,6 +240,10 @@ __device__ __forceinline__ void tile_origin(int tile, int tiles_r, int tiles_k, 
  * R and K need not be whole tiles: the transfers of an edge tile fetch the last rows or columns
  * that exist in place of those that do not (results of those positions are never stored).
  */
+#ifndef QUEST_GG_SPREAD_MODES
+#define QUEST_GG_SPREAD_MODES 5   // bit m: MODE m spreads its transfers over the whole step
+#endif
+
 template <int MODE, int STAGES>
 __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     const uint16_t *__restrict__ dy, int64_t ld_dy, const uint16_t *__restrict__ qhat, int64_t ld_right,
@@ -385,15 +389,23 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     };
     constexpr int kReads = MODE == 1 ? 16 : MODE == 0 ? 12 : 8;
 
-    // Ring of STAGES stages: while step s is multiplied out of stage s % STAGES, the transfers of
-    // steps s + 1 .. s + STAGES - 2 are in flight or done and, from the middle of the step on, those
-    // of step s + STAGES - 1 go into the stage that step s - 1 has left.
-    static_for<STAGES - 1>([&](auto sc) {
+    // Ring of STAGES stages: while step s is multiplied out of stage s % STAGES, the transfers of the
+    // next steps are in flight or done.  Two ways to refill:
+    //   late   the transfers of step s + STAGES - 1 go into the stage that step s - 1 has left, which is
+    //          free once every wave has passed this step's barrier: second half of the step only;
+    //   spread the transfers of step s + STAGES - 2 go into the stage that step s - 2 has left, free
+    //          since the previous step's barrier: one transfer every fourth matrix instruction, all
+    //          through the step, at the price of one step less of look-ahead.
+    // Spreading is 1-3 % faster when the left operand is in row form (G_x: 320 instead of 328 us on
+    // one box, 334 instead of 338 on another) and 0-1 % slower when both operands are in column form.
+    constexpr bool kSpread = QUEST_GG_SPREAD_MODES & (1 << MODE);
+    constexpr int kAhead = kSpread ? STAGES - 2 : STAGES - 1;   // steps in flight beyond the current one
+    static_for<kAhead>([&](auto sc) {
         static_for<8>([&](auto pc) {
             transfer(pc, smem_addr + decltype(sc)::value * kGStage, s_begin + decltype(sc)::value);
         });
     });
-    wait_vmcnt<8 * (STAGES - 2)>();
+    wait_vmcnt<8 * (kAhead - 1)>();
     __builtin_amdgcn_s_barrier();
     static_for<kReads>([&](auto nc) { load_frag(nc, smem, std::integral_constant<int, 0>{}); });
 
@@ -403,31 +415,36 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
         const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
         const int prv = cur == 0 ? STAGES - 1 : cur - 1;
         const uint8_t *nxt_stage = smem + nxt * kGStage;
-        const uint32_t refill = smem_addr + prv * kGStage;
+        const uint32_t refill = smem_addr + (kSpread ? (cur + kAhead) % STAGES : prv) * kGStage;
         // 32 matrix instructions; each is followed by one slice of the other work, pinned in place:
         //    0..15  fragment reads of the step's second k-step
-        //   15      transfers of step + 1 have landed (all but the newest STAGES - 3 groups), barrier
+        //   15      transfers of step + 1 have landed (all but the newer groups), barrier
         //   16..31  fragment reads of the next step's first k-step
-        //   16, 18, .. 30  transfers of step + STAGES - 1 (spread out: a wave issues in order, and a
-        //           transfer that finds the memory pipeline's queue full holds up the MFMAs behind it)
+        //   16, 18, .. 30 (late) or 0, 4, .. 28 (spread)  transfers of a later step (never back to back:
+        //           a wave issues in order, and a transfer that finds the memory pipeline's queue full
+        //           holds up the MFMAs behind it)
         static_for<32>([&](auto kc) {
             constexpr int k = decltype(kc)::value;
             constexpr int ks = k >> 4, i = (k >> 2) & 3, j = k & 3;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 __builtin_shufflevector(rf[ks][j][0], rf[ks][j][1], 0, 1, 2, 3, 4, 5, 6, 7),
                 __builtin_shufflevector(lf[ks][i][0], lf[ks][i][1], 0, 1, 2, 3, 4, 5, 6, 7), acc[i][j], 0, 0, 0);
+            if constexpr (kSpread && (k & 3) == 0)
+                transfer(std::integral_constant<int, k / 4>{}, refill, step + kAhead);
             if constexpr (k < 16) {
                 if constexpr (k < kReads)
                     load_frag(std::integral_constant<int, k>{}, cur_stage, std::integral_constant<int, 1>{});
                 if constexpr (k == 15) {
-                    wait_vmcnt<8 * (STAGES - 3)>();
+                    // all transfers of step + 1 have landed: what may still be in flight are the groups of
+                    // the steps after it and, when spread, the four transfers this step has issued so far
+                    wait_vmcnt<8 * (kAhead - 2) + (kSpread ? 4 : 0)>();
                     __builtin_amdgcn_s_barrier();
                 }
             } else {
                 if constexpr (k - 16 < kReads)
                     load_frag(std::integral_constant<int, k - 16>{}, nxt_stage, std::integral_constant<int, 0>{});
-                if constexpr ((k & 1) == 0)
-                    transfer(std::integral_constant<int, (k - 16) / 2>{}, refill, step + STAGES - 1);
+                if constexpr (!kSpread && (k & 1) == 0)
+                    transfer(std::integral_constant<int, (k - 16) / 2>{}, refill, step + kAhead);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
