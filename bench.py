@@ -256,6 +256,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain streaming kernel of known size (reads and writes 1 GiB each), "
                          "the yardstick for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the step from HIP graphs (one per buffer set, captured after the timed "
+                         "region) and report that step time as ms_per_step_graph: the same kernels without "
+                         "event pairs and host launch gaps")
     ap.add_argument("--library-gemm", action="store_true",
                     help="also time the vendor library (torch.matmul bf16, torch._int_mm int8) on this "
                          "workload's three matrix products, operands already in the library's own format: "
@@ -431,6 +435,24 @@ def main():
         torch.cuda.synchronize()
         # what a plain streaming kernel reaches on this machine, next to the 8 TB/s of the datasheet
         result["streaming_kernel_GBps"] = 3 * 2.0 * (1 << 30) / (time.perf_counter() - t0) / 1e9
+    if args.graph:
+        capture_stream = torch.cuda.Stream()
+        graphs = []
+        for b in sets:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(capture_stream):
+                with torch.cuda.graph(g, stream=capture_stream):
+                    for _, launch in step_kernels(q, b, cfg, args.grid == "fp4"):
+                        launch()
+            graphs.append(g)
+        for i in range(args.warmup):
+            graphs[i % n_sets].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % n_sets].replay()
+        torch.cuda.synchronize()
+        result["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / args.steps
     if args.library_gemm:
         result["library_gemm_us"] = library_gemm_us(torch, dev, M, N, K)
     if not args.no_cpu_baseline and args.grid == "int4":   # the oracle leg times the headline (integer-grid) path

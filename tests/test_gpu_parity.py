@@ -712,3 +712,58 @@ def test_full_linear_forward_backward_small():
     for got, ref in ((dx, ref_dx), (dw, ref_dw)):
         err = np.linalg.norm(to_host_f64(got) - ref) / np.linalg.norm(ref)
         assert err < 5e-3
+
+
+def test_whole_step_replayed_from_a_graph_matches_eager_launches():
+    """The step's seven calls captured into one HIP graph (after an eager step has set the kernels'
+    LDS limits and grown the library's scratch memory) and replayed on new input contents, with eager
+    work and synchronisations between the replays: every replay must reproduce, bit for bit, what the
+    same calls give when launched one by one.  Shapes that split tiles (second launch, scratch slots)."""
+    M, N, K, bits, n = 768, 8192, 512, 4, 512
+    dev = torch.device(DEV)
+
+    def buffers():
+        u8, f32, b16 = torch.uint8, torch.float32, torch.bfloat16
+        return dict(xc=torch.empty(M, K // 2, dtype=u8, device=dev), xs=torch.empty(M, dtype=f32, device=dev),
+                    xm=torch.empty(M, K // 8, dtype=u8, device=dev), wc=torch.empty(N, K // 2, dtype=u8, device=dev),
+                    ws=torch.empty(N, dtype=f32, device=dev), wm=torch.empty(N, K // 8, dtype=u8, device=dev),
+                    y=torch.empty(M, N, dtype=b16, device=dev), gx=torch.empty(M, K, dtype=b16, device=dev),
+                    gw=torch.empty(N, K, dtype=b16, device=dev), dx=torch.empty(M, K, dtype=b16, device=dev),
+                    dw=torch.empty(N, K, dtype=b16, device=dev))
+
+    x = torch.empty(M, K, dtype=torch.bfloat16, device=dev)
+    w = torch.empty(N, K, dtype=torch.bfloat16, device=dev)
+    dy = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
+
+    def step(b):
+        q.quest_hadamard_quantize(x, n, bits, codes=b["xc"], scales=b["xs"], mask=b["xm"])
+        q.quest_hadamard_quantize(w, n, bits, codes=b["wc"], scales=b["ws"], mask=b["wm"])
+        q.quest_lowbit_gemm(b["xc"], b["xs"], b["wc"], b["ws"], K, bits, y=b["y"])
+        q.quest_grad_gemm(0, dy, b["wc"], b["ws"], bits, M, N, K, out=b["gx"])
+        q.quest_grad_gemm(1, dy, b["xc"], b["xs"], bits, M, N, K, out=b["gw"])
+        q.quest_trust_backward(b["gx"], b["xm"], n, out=b["dx"])
+        q.quest_trust_backward(b["gw"], b["wm"], n, out=b["dw"])
+
+    def fill(seed):
+        x.copy_(to_device(synth.outlier_activations(M, K, 0.01, 20.0, seed, "bf16")).view(torch.bfloat16))
+        w.copy_(to_device(synth.gaussian(N, K, 0.02, seed + 1, "bf16")).view(torch.bfloat16))
+        dy.copy_(to_device(synth.upstream_gradient(M, N, seed + 2, "bf16")).view(torch.bfloat16))
+
+    eager, captured = buffers(), buffers()
+    fill(0)
+    step(eager)                       # sets function attributes, grows the scratch memory
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            step(captured)
+    torch.cuda.synchronize()
+    for seed in (10, 20, 30):
+        fill(seed)
+        step(eager)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in eager:
+            assert torch.equal(eager[name].view(torch.uint8), captured[name].view(torch.uint8)), (seed, name)
