@@ -83,8 +83,8 @@ quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t r
                                      uint8_t *mask, float *xh_out, void *stream);
 
 /*
- * The comparison quantizer of Sec. 4.1 ("AbsMax scaling instead of proper distribution
- * matching"), and with had_block = 1 the no-transform ablation of Sec. 4.3: everything as in
+ * The comparison quantizer of Sec. 4.1 (scale taken from the row's largest magnitude instead of
+ * a fit to the value distribution), and with had_block = 1 the no-transform ablation of Sec. 4.3: everything as in
  * quest_hadamard_quantize, except that the grid spans the row's largest magnitude,
  *   a = max_j |x_h[j]|,  k = clamp(floor(x_h (L - 1) / (2 a)), -L/2, L/2 - 1),  scales[r] = a / (L - 1).
  * Nothing is clipped, so every mask bit is 1 (the mask is still written when given).  A zero row

@@ -72,7 +72,7 @@ def untrusted_fraction(alpha: float, bits: int, outer_trust: float = 1.0) -> flo
 # ------------------------------------------------------------------ FP4 grid (Sec. 4.4, "The FP4 Format")
 
 # Magnitudes of the 4-bit floating-point format with 2 exponent and 1 mantissa bit (E2M1),
-# in code order; the grid "scaled to fit the same [-1, 1] interval" is FP4_MAGNITUDES / 6.
+# in code order; divided by the largest one they span [-1, 1] like the integer grid (Sec. 4.4).
 FP4_MAGNITUDES = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)
 
 
@@ -95,8 +95,8 @@ def gaussian_mse_fp4(alpha: float) -> float:
 
 
 def alpha_star_fp4() -> float:
-    """argmin over alpha of gaussian_mse_fp4: the paper's alpha*_FP4 ("replacing the rounding
-    operation in the original definition")."""
+    """argmin over alpha of gaussian_mse_fp4: the paper's alpha*_FP4, i.e. the definition of alpha*
+    with the rounding step swapped for rounding to this grid (Sec. 4.4)."""
     result = minimize_scalar(gaussian_mse_fp4, bounds=(0.05, 8.0), method="bounded", options={"xatol": 1e-10})
     return float(result.x)
 

@@ -219,8 +219,9 @@ void qo_project(const double *xh, int64_t rows, int64_t cols, int bits, double a
 }
 
 /*
- * AbsMax projection: the comparison quantizer of Sec. 4.1 (the QAT extension of a rotation-based
- * PTQ method, "AbsMax scaling instead of proper distribution matching").  The paper gives no
+ * AbsMax projection: the comparison quantizer of Sec. 4.1 (the training-time extension of a
+ * rotation-based post-training method, whose scale is the row's largest magnitude rather than a
+ * fit to the value distribution).  The paper gives no
  * formula; the reading taken here keeps everything of the projection above and replaces the
  * clip alpha * rms by the row's largest magnitude a = max_j |x_h[j]|:
  *   D    = 2 a / (L - 1),  k = clamp(floor(x_h / D), -L/2, L/2 - 1)
@@ -438,6 +439,24 @@ int64_t qo_gemm_odd(const int32_t *ux, const int32_t *uw, int64_t M, int64_t N, 
                 worst = mag;
         }
     return worst;
+}
+
+/*
+ * FP4 variant of the forward matmul (Sec. 4.4 "The FP4 Format", Algorithm 1's product):
+ * acc[m, n] = sum_k v_a[m, k] * v_b[n, k] over the signed E2M1 values of the codes, in double.
+ * Every value is a multiple of 1/2 with |v| <= 6, so every product is a multiple of 1/4 and the
+ * sum is exact in double for any K the library accepts.
+ */
+void qo_gemm_fp4(const double *va, const double *vb, int64_t M, int64_t N, int64_t K, double *acc)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double sum = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                sum += va[m * K + k] * vb[n * K + k];
+            acc[m * N + n] = sum;
+        }
 }
 
 /* y[m, n] = acc[m, n] * s_x[m] * s_w[n]  ( = sum_k xhat[m,k] what[n,k] since xhat = s u ). */

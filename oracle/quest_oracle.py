@@ -67,6 +67,7 @@ def _load():
         lib.qo_unpack_mask.argtypes = [_p, _c_i64, _c_i64, _p]
         lib.qo_gemm_odd.argtypes = [_p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_gemm_odd.restype = _c_i64
+        lib.qo_gemm_fp4.argtypes = [_p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_dequant.argtypes = [_p, _p, _p, _c_i64, _c_i64, _p]
         lib.qo_trust_backward.argtypes = [_p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_grad_input.argtypes = [_p, _p, _p, _c_i64, _c_i64, _c_i64, _p]
@@ -247,7 +248,15 @@ def hadamard_quantize_fp4(x: np.ndarray, n: int, alpha: float | None = None, den
 
 def gemm_fp4(va: np.ndarray, vb: np.ndarray) -> np.ndarray:
     """acc[m, n] = sum_k v_a[m, k] v_b[n, k] of signed E2M1 values: multiples of 1/4, exact in double."""
-    return _c(va, np.float64) @ _c(vb, np.float64).T
+    va = _c(va, np.float64)
+    vb = _c(vb, np.float64)
+    M, K = va.shape
+    N, K2 = vb.shape
+    if K != K2:
+        raise ValueError("contraction lengths differ")
+    acc = np.empty((M, N), dtype=np.float64)
+    _load().qo_gemm_fp4(_ptr(va), _ptr(vb), M, N, K, _ptr(acc))
+    return acc
 
 
 def hadamard_quantize(x: np.ndarray, n: int, bits: int, alpha: float | None = None,

@@ -107,3 +107,29 @@ def test_zero_row_scale_invariance_and_gemm_exactness():
     va = qo.unpack_fp4(p.codes, 64)
     acc = qo.gemm_fp4(va, va)
     assert acc[1, 1] == np.sum(va[1] ** 2) and np.all(acc * 4 == np.rint(acc * 4))
+
+
+def test_gemm_fp4_is_the_plain_sum_of_products():
+    """The FP4 accumulator oracle against Python loops on a tiny case, and against the integer
+    product on doubled values: 2 v is an integer, so acc = sum (2 v_a)(2 v_b) / 4 exactly."""
+    rng = np.random.default_rng(4)
+    code_a = rng.integers(0, 16, size=(5, 24), dtype=np.uint8)
+    code_b = rng.integers(0, 16, size=(7, 24), dtype=np.uint8)
+    va = np.where(code_a & 8, -1.0, 1.0) * MAG[code_a & 7]
+    vb = np.where(code_b & 8, -1.0, 1.0) * MAG[code_b & 7]
+    acc = qo.gemm_fp4(va, vb)
+    assert acc.shape == (5, 7)
+    for m in range(5):
+        for n in range(7):
+            total = 0.0
+            for k in range(24):
+                total += float(va[m, k]) * float(vb[n, k])
+            assert acc[m, n] == total
+    # a transposed operand, a dropped term or a wrong sign would break one of these
+    assert not np.array_equal(acc, qo.gemm_fp4(va, -vb)) and np.array_equal(acc, -qo.gemm_fp4(va, -vb))
+    va_big = np.where(rng.integers(0, 2, size=(33, 512)), -1.0, 1.0) * MAG[rng.integers(0, 8, size=(33, 512))]
+    vb_big = np.where(rng.integers(0, 2, size=(17, 512)), -1.0, 1.0) * MAG[rng.integers(0, 8, size=(17, 512))]
+    doubled = qo.gemm_odd((2 * va_big).astype(np.int32), (2 * vb_big).astype(np.int32))
+    assert np.array_equal(qo.gemm_fp4(va_big, vb_big) * 4.0, doubled.astype(np.float64))
+    one_hot = np.zeros((1, 512)); one_hot[0, 37] = 1.0
+    assert np.array_equal(qo.gemm_fp4(one_hot, vb_big)[0], vb_big[:, 37])
