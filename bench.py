@@ -64,7 +64,7 @@ def algorithmic_bytes_backward(rows, cols):
 class BufferSet:
     """One complete set of device buffers for a step (rotated so that caches cannot serve re-use)."""
 
-    def __init__(self, torch, dev, x_bits, w_bits, dy_bits, cfg):
+    def __init__(self, torch, dev, x_bits, w_bits, dy_bits, cfg, q, fp4=False):
         import numpy as np
         M, N, K = cfg["M"], cfg["N"], cfg["K"]
 
@@ -84,6 +84,12 @@ class BufferSet:
         self.g_w = torch.empty(N, K, dtype=b16, device=dev)
         self.dx = torch.empty(M, K, dtype=b16, device=dev)
         self.dw = torch.empty(N, K, dtype=b16, device=dev)
+        # scratch of the calls that need it (the library allocates nothing): sized by its host queries
+        grad_query = q.quest_grad_gemm_fp4_workspace_bytes if fp4 else q.quest_grad_gemm_workspace_bytes
+        self.ws_gx = torch.empty(max(grad_query(0, M, N, K), 16), dtype=u8, device=dev)
+        self.ws_gw = torch.empty(max(grad_query(1, M, N, K), 16), dtype=u8, device=dev)
+        self.ws_gemm = torch.empty(max(q.quest_lowbit_gemm_workspace_bytes(M, N, K, cfg["bits"]), 16), dtype=u8,
+                                   device=dev)
 
 
 def step_kernels(q, b, cfg, fp4=False):
@@ -96,8 +102,10 @@ def step_kernels(q, b, cfg, fp4=False):
             ("quantize_w", lambda: q.quest_hadamard_quantize_fp4(b.w, n, codes=b.w_codes, scales=b.w_scales,
                                                                  mask=b.w_mask)),
             ("lowbit_gemm", lambda: q.quest_lowbit_gemm_fp4(b.x_codes, b.x_scales, b.w_codes, b.w_scales, K, y=b.y)),
-            ("grad_gemm_x", lambda: q.quest_grad_gemm_fp4(0, b.dy, b.w_codes, b.w_scales, M, N, K, out=b.g_x)),
-            ("grad_gemm_w", lambda: q.quest_grad_gemm_fp4(1, b.dy, b.x_codes, b.x_scales, M, N, K, out=b.g_w)),
+            ("grad_gemm_x", lambda: q.quest_grad_gemm_fp4(0, b.dy, b.w_codes, b.w_scales, M, N, K, out=b.g_x,
+                                                          workspace=b.ws_gx)),
+            ("grad_gemm_w", lambda: q.quest_grad_gemm_fp4(1, b.dy, b.x_codes, b.x_scales, M, N, K, out=b.g_w,
+                                                          workspace=b.ws_gw)),
             ("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx)),
             ("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw)),
         ]
@@ -107,11 +115,11 @@ def step_kernels(q, b, cfg, fp4=False):
         ("quantize_w", lambda: q.quest_hadamard_quantize(b.w, n, bits, codes=b.w_codes,
                                                          scales=b.w_scales, mask=b.w_mask)),
         ("lowbit_gemm", lambda: q.quest_lowbit_gemm(b.x_codes, b.x_scales, b.w_codes, b.w_scales,
-                                                    K, bits, y=b.y)),
+                                                    K, bits, y=b.y, workspace=b.ws_gemm)),
         ("grad_gemm_x", lambda: q.quest_grad_gemm(0, b.dy, b.w_codes, b.w_scales, bits, M, N, K,
-                                                  out=b.g_x)),
+                                                  out=b.g_x, workspace=b.ws_gx)),
         ("grad_gemm_w", lambda: q.quest_grad_gemm(1, b.dy, b.x_codes, b.x_scales, bits, M, N, K,
-                                                  out=b.g_w)),
+                                                  out=b.g_w, workspace=b.ws_gw)),
         ("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx)),
         ("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw)),
     ]
@@ -299,7 +307,8 @@ def main():
     cb = q.quest_container_bits(cfg["bits"])
     dy_bits = synth.upstream_gradient(M, N, seed=0)
     n_sets = 3   # ~0.7 GiB per set: > 1 GiB of other traffic between two uses of any buffer
-    sets = [BufferSet(torch, dev, x_bits, w_bits, dy_bits, cfg) for _ in range(n_sets)]
+    q.quest_init()
+    sets = [BufferSet(torch, dev, x_bits, w_bits, dy_bits, cfg, q, args.grid == "fp4") for _ in range(n_sets)]
     torch.cuda.synchronize()
 
     if args.only:

@@ -15,12 +15,19 @@
  *
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer unless the comment says "host".  The caller owns
- *     all buffers; the library allocates nothing, frees nothing and never synchronises (the one
- *     exception, the device memory it keeps for the gradient matmuls and for 1- and 2-bit
- *     matmuls, is described at quest_grad_gemm): a call validates its
- *     arguments on the host and enqueues kernels on `stream` (a hipStream_t passed as void*,
- *     NULL = the default stream).
- *   - Errors are return codes.  On any code other than QUEST_OK nothing was launched.
+ *     all buffers, scratch included; the library allocates nothing, frees nothing and never
+ *     synchronises: a call validates its arguments on the host and enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).  Every enqueue call may be
+ *     captured into a HIP graph (call quest_init first, so that no kernel attribute has to change
+ *     during capture); calls on different streams may overlap as long as they share no output or
+ *     workspace.
+ *   - Scratch memory: an entry point that needs it takes `workspace` / `workspace_bytes`; the host
+ *     function <entry point>_workspace_bytes(...) gives the size for a shape (0: none needed, -1:
+ *     the shape is not supported).  The workspace must be 16-byte aligned and must not be used by
+ *     anything else until the call's kernels have finished; its contents afterwards are undefined.
+ *   - Errors are return codes.  A validation error (every code but QUEST_ERR_LAUNCH) means nothing
+ *     was launched.  QUEST_ERR_LAUNCH means the HIP runtime refused a launch; an entry point that
+ *     enqueues several kernels may have enqueued the earlier ones, and its outputs are undefined.
  *   - Outputs must not alias inputs.
  *   - "bf16" is the upper half of an IEEE binary32, stored as uint16_t.
  *   - Code container width cb(b): 1 -> 1, 2 -> 2, 3 -> 4, 4 -> 4, 8 -> 8 bits.  Element j of a row
@@ -46,7 +53,7 @@ typedef enum {
     QUEST_ERR_ALIGN = 5,   /* pointer or leading dimension not 16-byte aligned */
     QUEST_ERR_DTYPE = 6,   /* unknown quest_dtype */
     QUEST_ERR_LAUNCH = 7,  /* the HIP runtime refused the launch */
-    QUEST_ERR_ARG = 8      /* any other invalid argument (e.g. non-finite alpha) */
+    QUEST_ERR_ARG = 8      /* any other invalid argument (non-finite alpha, workspace missing or too small) */
 } quest_status;
 
 typedef enum { QUEST_F32 = 0, QUEST_BF16 = 1 } quest_dtype;
@@ -122,18 +129,26 @@ float quest_alpha_star_fp4(void);
  *   a_codes  [M, K*cb/8] activation codes, a_scales [M];  b_codes [N, K*cb/8] weight codes,
  *            b_scales [N]; both operands K-contiguous (row-major weight), produced by
  *            quest_hadamard_quantize with the same had_block and the same bits
- *   bits     1, 2, 3 or 4 (u fits a signed byte); K: multiple of 64, 64 <= K <= 65536
+ *   bits     1, 2, 3 or 4 (u fits a signed byte); K: multiple of 64, 64 <= K <= 65536;
+ *            M, N <= 2^22 and max(M, N) * K / 2 < 2^32 (QUEST_ERR_SHAPE otherwise)
  *   y        out bf16 [M, ld_y], ld_y >= N (row stride in elements);  may be NULL if acc_out is given
  *   acc_out  out int32 [M, N] raw accumulators, or NULL (NULL in production)
+ *   workspace, workspace_bytes   scratch for bits = 1 or 2 with M, N >= 128 and K a multiple of 128:
+ *            both operands are first re-coded as 4-bit codes of the same odd integers
+ *            ((M + N) * K / 2 bytes, see quest_lowbit_gemm_workspace_bytes) and multiplied by the
+ *            4-bit kernels.  NULL is allowed: the narrow containers are then multiplied directly by
+ *            a slower kernel, with the same result.  Given but too small: QUEST_ERR_ARG.  Unused
+ *            (may be NULL, 0) for bits = 3 or 4.
  * M = 0 or N = 0 is a no-op.  Code pointers must be 16-byte aligned.
- * bits = 1 or 2 with M >= 512, N >= 256 and K a multiple of 128: both operands are first re-coded
- * as 4-bit codes of the same odd integers, into the library-owned device memory described at
- * quest_grad_gemm (same consequences), and multiplied by the 4-bit kernel.
  */
 quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,
                                const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
-                               int32_t bits, void *y, int64_t ld_y, int32_t *acc_out,
-                               void *stream);
+                               int32_t bits, void *y, int64_t ld_y, int32_t *acc_out, void *workspace,
+                               int64_t workspace_bytes, void *stream);
+
+/* Host: scratch bytes the fast path of quest_lowbit_gemm uses for this shape (0: none; -1: the
+ * shape or bit width is not accepted). */
+int64_t quest_lowbit_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int32_t bits);
 
 /*
  * The matmul of Algorithm 1 for the FP4 variant (Sec. 4.4), run on the E2M1 codes by the FP4 matrix
@@ -167,30 +182,34 @@ quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint
  *   which = 0:  out[M, K] = dy[M, N] * what_h[N, K]      (q = weight codes [N, K*cb/8], scales [N])
  *   which = 1:  out[N, K] = dy[M, N]^T * xhat_h[M, K]    (q = activation codes [M, K*cb/8], scales [M])
  *   dy bf16 [M, N] row-major, out bf16, fp32 accumulation.  bits in {1,2,3,4}.
- *   M, N, K multiples of 64.
- * Device memory: when the output is at least 128 x 128 the call first expands the packed
- * operand to bf16 and, if the tiles do not fill the GPU's compute units evenly, sums partial tiles
- * in a second pass.  Both live in memory the library owns: one buffer per device, allocated
- * (hipMalloc) or grown on the first call that needs the size and kept until the process ends.
- * Consequences: calls on one device must not overlap (issue them to one stream); a call that has
- * to grow the buffer synchronises the device and cannot be captured into a graph; an allocation
- * failure is reported as QUEST_ERR_LAUNCH.  The entry points that use this memory say so; all
- * others allocate nothing.
+ *   M, N, K multiples of 64, each at most 2^22.
+ *   workspace, workspace_bytes   scratch of quest_grad_gemm_workspace_bytes(which, M, N, K) bytes:
+ *            when the output is at least 128 x 128 the call first expands the packed operand to bf16
+ *            and, if the tiles do not fill the GPU's compute units evenly, leaves partial tiles there
+ *            that a second pass sums in a fixed order.  Missing or too small: QUEST_ERR_ARG.  Smaller
+ *            outputs need none (the query returns 0).
  */
 quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_codes,
                              const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,
-                             void *out, void *stream);
+                             void *out, void *workspace, int64_t workspace_bytes, void *stream);
+
+/* Host: scratch bytes quest_grad_gemm needs for this shape on the current device (it depends on the
+ * device's number of compute units; 256 are assumed when no device is available).  -1: shape not
+ * accepted. */
+int64_t quest_grad_gemm_workspace_bytes(int32_t which, int64_t M, int64_t N, int64_t K);
 
 /*
  * quest_grad_gemm for operands quantized by quest_hadamard_quantize_fp4: the code-packed operand's
  * value is bf16(s * v), v the signed E2M1 value of its code (the backward pass of the FP4 variant,
  * Sec. 4.4, is Algorithm 2 unchanged).  which = 0 or 1 as there.  M, N, K multiples of 64 and the
- * output at least 128 x 128 (QUEST_ERR_SHAPE otherwise).  Uses the library-owned device memory
- * described at quest_grad_gemm.
+ * output at least 128 x 128 (QUEST_ERR_SHAPE otherwise).  Workspace as for quest_grad_gemm, sized by
+ * quest_grad_gemm_fp4_workspace_bytes.
  */
 quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q_codes,
                                  const float *q_scales, int64_t M, int64_t N, int64_t K, void *out,
-                                 void *stream);
+                                 void *workspace, int64_t workspace_bytes, void *stream);
+
+int64_t quest_grad_gemm_fp4_workspace_bytes(int32_t which, int64_t M, int64_t N, int64_t K);
 
 /*
  * Weight-only forward product (Sec. 4.4 "Weight-only quantization": 16-bit activations against
@@ -201,11 +220,20 @@ quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q
  *   w_codes  [N, K*cb/8], w_scales [N] from either quantizer entry point;  bits in {1,2,3,4}
  *   y        out bf16 [M, N] row-major, fp32 accumulation on the bf16 matrix cores
  * M, N, K multiples of 64, M and N at least 128, M*N < 2^31 (QUEST_ERR_SHAPE otherwise).
- * Uses the same library-owned device memory as quest_grad_gemm, with the same consequences.
+ * Workspace as for quest_grad_gemm, sized by quest_weight_only_gemm_workspace_bytes.
  */
 quest_status quest_weight_only_gemm(const void *x, const uint8_t *w_codes, const float *w_scales,
                                     int32_t bits, int64_t M, int64_t N, int64_t K, void *y,
-                                    void *stream);
+                                    void *workspace, int64_t workspace_bytes, void *stream);
+
+int64_t quest_weight_only_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * Host: optional set-up for the current device (call once per device, from any thread, before
+ * capturing graphs): raises the dynamic-LDS limit of every kernel that needs it, which the enqueue
+ * calls otherwise do on first use.  Allocates nothing.  QUEST_ERR_LAUNCH if the runtime refuses.
+ */
+quest_status quest_init(void);
 
 /* Host: the built-in Gaussian-MSE-optimal clip alpha*(bits) (Sec. 3.1); 0 for unsupported bits. */
 float quest_alpha_star(int32_t bits);

@@ -17,8 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
 EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
-           "quest_lowbit_gemm", "quest_lowbit_gemm_fp4", "quest_trust_backward",
-           "quest_grad_gemm", "quest_grad_gemm_fp4", "quest_weight_only_gemm", "quest_alpha_star", "quest_container_bits", "quest_status_string")
+           "quest_lowbit_gemm", "quest_lowbit_gemm_workspace_bytes", "quest_lowbit_gemm_fp4", "quest_trust_backward",
+           "quest_grad_gemm", "quest_grad_gemm_workspace_bytes", "quest_grad_gemm_fp4",
+           "quest_grad_gemm_fp4_workspace_bytes", "quest_weight_only_gemm", "quest_weight_only_gemm_workspace_bytes",
+           "quest_init", "quest_alpha_star", "quest_container_bits", "quest_status_string")
 
 _i64, _i32, _f32, _p = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 _lib = None
@@ -46,14 +48,23 @@ def load():
         lib.quest_hadamard_quantize_fp4.restype = ctypes.c_int
         lib.quest_alpha_star_fp4.argtypes = []
         lib.quest_alpha_star_fp4.restype = _f32
-        lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p]
+        lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p, _i64, _p]
+        lib.quest_lowbit_gemm_workspace_bytes.argtypes = [_i64, _i64, _i64, _i32]
+        lib.quest_lowbit_gemm_workspace_bytes.restype = _i64
         lib.quest_lowbit_gemm_fp4.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _p, _i64, _p, _p]
         lib.quest_lowbit_gemm_fp4.restype = ctypes.c_int
         lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
-        lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
-        lib.quest_weight_only_gemm.argtypes = [_p, _p, _p, _i32, _i64, _i64, _i64, _p, _p]
-        lib.quest_grad_gemm_fp4.argtypes = [_i32, _p, _p, _p, _i64, _i64, _i64, _p, _p]
+        lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p, _i64, _p]
+        lib.quest_weight_only_gemm.argtypes = [_p, _p, _p, _i32, _i64, _i64, _i64, _p, _p, _i64, _p]
+        lib.quest_grad_gemm_fp4.argtypes = [_i32, _p, _p, _p, _i64, _i64, _i64, _p, _p, _i64, _p]
         lib.quest_grad_gemm_fp4.restype = ctypes.c_int
+        for name in ("quest_grad_gemm_workspace_bytes", "quest_grad_gemm_fp4_workspace_bytes"):
+            getattr(lib, name).argtypes = [_i32, _i64, _i64, _i64]
+            getattr(lib, name).restype = _i64
+        lib.quest_weight_only_gemm_workspace_bytes.argtypes = [_i64, _i64, _i64]
+        lib.quest_weight_only_gemm_workspace_bytes.restype = _i64
+        lib.quest_init.argtypes = []
+        lib.quest_init.restype = ctypes.c_int
         for name in ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_lowbit_gemm",
                      "quest_trust_backward", "quest_grad_gemm", "quest_weight_only_gemm"):
             getattr(lib, name).restype = ctypes.c_int
@@ -138,14 +149,28 @@ def quest_alpha_star_fp4() -> float:
     return float(load().quest_alpha_star_fp4())
 
 
+def _bytes(t: torch.Tensor | None) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def quest_init() -> None:
+    """Optional per-device set-up (kernel attributes); call before capturing graphs."""
+    _check(load().quest_init(), "quest_init")
+
+
+def quest_lowbit_gemm_workspace_bytes(M: int, N: int, K: int, bits: int) -> int:
+    return int(load().quest_lowbit_gemm_workspace_bytes(M, N, K, bits))
+
+
 def quest_lowbit_gemm(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: torch.Tensor,
                       b_scales: torch.Tensor, K: int, bits: int, *, y: torch.Tensor | None,
-                      acc_out: torch.Tensor | None = None) -> None:
+                      acc_out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> None:
     """y[M, N] (bf16) and/or acc_out[M, N] (int32) from packed codes [M, K*cb/8] and [N, K*cb/8]."""
     M, N = a_codes.shape[0], b_codes.shape[0]
     ld_y = y.stride(0) if y is not None else N
     _check(load().quest_lowbit_gemm(_ptr(a_codes), _ptr(a_scales), M, _ptr(b_codes), _ptr(b_scales),
-                                    N, K, bits, _ptr(y), ld_y, _ptr(acc_out), _stream()),
+                                    N, K, bits, _ptr(y), ld_y, _ptr(acc_out), _ptr(workspace),
+                                    _bytes(workspace), _stream()),
            "quest_lowbit_gemm")
 
 
@@ -169,27 +194,41 @@ def quest_trust_backward(g: torch.Tensor, mask: torch.Tensor | None, had_block: 
            "quest_trust_backward")
 
 
+def quest_grad_gemm_workspace_bytes(which: int, M: int, N: int, K: int) -> int:
+    return int(load().quest_grad_gemm_workspace_bytes(which, M, N, K))
+
+
 def quest_grad_gemm(which: int, dy: torch.Tensor, q_codes: torch.Tensor, q_scales: torch.Tensor,
-                    bits: int, M: int, N: int, K: int, *, out: torch.Tensor) -> None:
+                    bits: int, M: int, N: int, K: int, *, out: torch.Tensor,
+                    workspace: torch.Tensor | None = None) -> None:
     """which = 0: out[M, K] = dy what_h;  which = 1: out[N, K] = dy^T xhat_h (bf16)."""
     _check(load().quest_grad_gemm(which, _ptr(dy), _ptr(q_codes), _ptr(q_scales), bits, M, N, K,
-                                  _ptr(out), _stream()),
+                                  _ptr(out), _ptr(workspace), _bytes(workspace), _stream()),
            "quest_grad_gemm")
 
 
+def quest_grad_gemm_fp4_workspace_bytes(which: int, M: int, N: int, K: int) -> int:
+    return int(load().quest_grad_gemm_fp4_workspace_bytes(which, M, N, K))
+
+
 def quest_grad_gemm_fp4(which: int, dy: torch.Tensor, q_codes: torch.Tensor, q_scales: torch.Tensor,
-                        M: int, N: int, K: int, *, out: torch.Tensor) -> None:
+                        M: int, N: int, K: int, *, out: torch.Tensor,
+                        workspace: torch.Tensor | None = None) -> None:
     """quest_grad_gemm for E2M1 codes (operands from quest_hadamard_quantize_fp4)."""
     _check(load().quest_grad_gemm_fp4(which, _ptr(dy), _ptr(q_codes), _ptr(q_scales), M, N, K, _ptr(out),
-                                      _stream()),
+                                      _ptr(workspace), _bytes(workspace), _stream()),
            "quest_grad_gemm_fp4")
 
 
+def quest_weight_only_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load().quest_weight_only_gemm_workspace_bytes(M, N, K))
+
+
 def quest_weight_only_gemm(x: torch.Tensor, w_codes: torch.Tensor, w_scales: torch.Tensor, bits: int,
-                           *, y: torch.Tensor) -> None:
+                           *, y: torch.Tensor, workspace: torch.Tensor | None = None) -> None:
     """y[M, N] (bf16) = x[M, K] (bf16) times the transposed weights given as packed codes [N, K*cb/8]."""
     M, K = x.shape
     N = w_codes.shape[0]
     _check(load().quest_weight_only_gemm(_ptr(x), _ptr(w_codes), _ptr(w_scales), bits, M, N, K, _ptr(y),
-                                         _stream()),
+                                         _ptr(workspace), _bytes(workspace), _stream()),
            "quest_weight_only_gemm")

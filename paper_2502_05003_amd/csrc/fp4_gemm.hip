@@ -181,11 +181,16 @@ __global__ __launch_bounds__(kTileThreads, 2) void fp4_gemm_tile_kernel(
 
 }  // namespace
 
+hipError_t prepare_fp4_gemm_kernels()
+{
+    return allow_dynamic_lds(reinterpret_cast<const void *>(fp4_gemm_tile_kernel), kTileLds);
+}
+
 hipError_t launch_fp4_gemm(const Fp4GemmArgs &a, hipStream_t stream)
 {
     if (a.M == 0 || a.N == 0)
         return hipSuccess;
-    const hipError_t attr_err = allow_dynamic_lds(reinterpret_cast<const void *>(fp4_gemm_tile_kernel), kTileLds);
+    const hipError_t attr_err = prepare_fp4_gemm_kernels();
     if (attr_err != hipSuccess)
         return attr_err;
     const int tiles_m = (int)((a.M + TM - 1) / TM), tiles_n = (int)((a.N + TN - 1) / TN);

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(
 
 // ------------------------------------------------------------------------------------------
 // Main path.  The code-packed operand is first expanded once to bf16(s u), [C, K] row-major, in
-// library-owned device memory (every 256 x 256 output tile would otherwise repeat that work for the
+// the caller's workspace (every 256 x 256 output tile would otherwise repeat that work for the
 // whole contraction); the matmul itself is then a plain bf16 x bf16 contraction whose main loop
 // holds nothing but matrix instructions, LDS reads and global -> LDS transfers.
 //
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__rest
 // evenly the launcher hands every CU the same number of units instead; a workgroup then computes
 // one segment per tile its range touches, and a segment that is not a whole tile leaves its fp32
 // accumulators in partial-tile slot 2 b (segment continues a tile) or 2 b + 1 (segment starts one)
-// for grad_gemm_fixup_kernel to add up.  A slot is [wave][accumulator quad 0..63][lane] float4.
+// of the workspace for grad_gemm_fixup_kernel to add up.  A slot is [wave][accumulator quad 0..63][lane] float4.
 //
 // Workgroups that are phase_period apart in that order walk through their tiles at the same
 // contraction position all the time, and with the tiles numbered along the longer side of the tile
@@ -559,6 +559,90 @@ __global__ __launch_bounds__(256) void grad_gemm_fixup_kernel(const float4 *__re
 
 }  // namespace
 
+namespace {
+
+constexpr int kStages = 5;
+constexpr int kLds = kStages * kGStage;
+
+// How a call is carried out: which kernels, how the tiles are dealt out, what scratch it needs.
+struct GradGemmPlan {
+    bool covered;      // some kernel handles the shape
+    bool tile_path;    // the 256 x 256 tile kernels (else the small-shape kernel, no scratch)
+    bool split;        // tiles split over the CUs, partial tiles summed by the fix-up kernel
+    int tiles_r, tiles_k, steps, blocks, per_block, phase_period;
+    int64_t out_rows, out_cols, contraction, q_rows, ld_left;
+    size_t expanded_bytes, partial_bytes;
+};
+
+GradGemmPlan plan_grad_gemm(int which, bool fp4, int64_t M, int64_t N, int64_t K, int cus)
+{
+    GradGemmPlan p = {};
+    // which = 0: out[M, K] = dy what;  1: out[N, K] = dy^T xhat;  2: out[M, N] = x what^T (weight-only)
+    p.out_rows = which == 1 ? N : M;
+    p.out_cols = which == 2 ? N : K;
+    p.contraction = which == 0 ? N : which == 1 ? M : K;
+    p.q_rows = which == 1 ? M : N;          // rows of the code-packed operand [q_rows, K]
+    p.ld_left = which == 2 ? K : N;
+    // the tile kernels: edge tiles may be partial (every size is a multiple of 64), offsets are 32-bit
+    p.tile_path = p.out_rows >= GT / 2 && p.out_cols >= GT / 2 && (p.contraction % GC) == 0 &&
+                  p.out_rows * p.out_cols < ((int64_t)1 << 31) &&
+                  std::max(M, N) * std::max(K, N) < ((int64_t)1 << 30);
+    p.covered = p.tile_path || !(which == 2 || fp4);   // only the tile kernels know these two forms
+    if (!p.tile_path)
+        return p;
+    p.tiles_r = (int)((p.out_rows + GT - 1) / GT);
+    p.tiles_k = (int)((p.out_cols + GT - 1) / GT);
+    p.steps = (int)(p.contraction / GC);
+    const int tiles = p.tiles_r * p.tiles_k;
+    // One workgroup per CU at a time.  When rounds of whole tiles would leave CUs idle, every CU
+    // can get the same share of (tile, step) units instead, the split tiles being summed by a
+    // second, small kernel.  That pays when the steps saved outweigh the partial tiles written
+    // and read back (two 256 KiB slots per workgroup at most, one per tile at least).
+    const int rounds = cus > 0 ? (tiles + cus - 1) / cus : 0;
+    const int64_t units = (int64_t)tiles * p.steps;
+    // measured on this kernel: 0.6 us per step, 0.08 us per partial tile written and read, 10 us for the second launch
+    const double whole_cost = 0.6 * rounds * p.steps;
+    const double split_cost = cus > 0 ? 0.6 * (double)((units + cus - 1) / cus) + 0.08 * (cus + tiles) + 10.0 : 0.0;
+    p.split = cus >= 8 && split_cost < whole_cost && units >= 4 * (int64_t)cus;
+    p.blocks = (tiles + 7) / 8 * 8;
+    p.per_block = p.steps;
+    p.phase_period = 0;
+    if (p.split) {
+        p.blocks = cus;
+        p.per_block = (int)((units + p.blocks - 1) / p.blocks);
+        // workgroups b and b + period are at the same contraction position at all times
+        const int period = p.steps / std::gcd(p.per_block, p.steps);
+        p.phase_period = (period % 8 == 0 && p.blocks % period == 0) ? period : 8;
+        if (p.blocks % p.phase_period != 0)
+            p.phase_period = p.blocks;
+    }
+    p.expanded_bytes = ((size_t)p.q_rows * K * 2 + 255) / 256 * 256;
+    p.partial_bytes = p.split ? (size_t)2 * p.blocks * kSlotQuads * sizeof(float4) : 0;
+    return p;
+}
+
+}  // namespace
+
+int64_t grad_gemm_workspace_bytes(int which, bool fp4, int64_t M, int64_t N, int64_t K, int cus)
+{
+    if (M == 0 || N == 0 || K == 0)
+        return 0;
+    const GradGemmPlan p = plan_grad_gemm(which, fp4, M, N, K, cus);
+    if (!p.covered)
+        return -1;
+    return p.tile_path ? (int64_t)(p.expanded_bytes + p.partial_bytes) : 0;
+}
+
+hipError_t prepare_grad_gemm_kernels()
+{
+    hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<0, kStages>), kLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<1, kStages>), kLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<2, kStages>), kLds);
+    return err;
+}
+
 hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
 {
     if (a.M == 0 || a.N == 0 || a.K == 0)
@@ -566,73 +650,29 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
     const int levels = a.fp4 ? 0 : 1 << a.bits;
     const auto *dy = static_cast<const uint16_t *>(a.dy);
     auto *out = static_cast<uint16_t *>(a.out);
-    // which = 0: out[M, K] = dy what;  1: out[N, K] = dy^T xhat;  2: out[M, N] = x what^T (weight-only)
-    const int64_t out_rows = a.which == 1 ? a.N : a.M, out_cols = a.which == 2 ? a.N : a.K;
-    const int64_t contraction = a.which == 0 ? a.N : a.which == 1 ? a.M : a.K;
-    const int64_t q_rows = a.which == 1 ? a.M : a.N;          // rows of the code-packed operand [q_rows, K]
-    const int64_t ld_left = a.which == 2 ? a.K : a.N;
-    // the tile kernels: edge tiles may be partial (every size is a multiple of 64), offsets are 32-bit
-    const bool tile_path = out_rows >= GT / 2 && out_cols >= GT / 2 && (contraction % GC) == 0 &&
-                           out_rows * out_cols < ((int64_t)1 << 31) &&
-                           std::max(a.M, a.N) * std::max(a.K, a.N) < ((int64_t)1 << 30);
-    if ((a.which == 2 || a.fp4) && !tile_path)   // only the tile kernels know these forms
+    const GradGemmPlan p = plan_grad_gemm(a.which, a.fp4, a.M, a.N, a.K, device_compute_units());
+    if (!p.covered)
         return hipErrorInvalidValue;
-    if (tile_path) {
-        const int tiles_r = (int)((out_rows + GT - 1) / GT), tiles_k = (int)((out_cols + GT - 1) / GT);
-        const int tiles = tiles_r * tiles_k, steps = (int)(contraction / GC);
-        constexpr int kStages = 5;
-        constexpr int kLds = kStages * kGStage;
-        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<0, kStages>), kLds);
-        if (err == hipSuccess)
-            err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<1, kStages>), kLds);
-        if (err == hipSuccess)
-            err = allow_dynamic_lds(reinterpret_cast<const void *>(grad_gemm_tile_kernel<2, kStages>), kLds);
+    if (p.tile_path) {
+        if (a.workspace == nullptr || (size_t)a.workspace_bytes < p.expanded_bytes + p.partial_bytes)
+            return hipErrorInvalidValue;
+        hipError_t err = prepare_grad_gemm_kernels();
         if (err != hipSuccess)
             return err;
-        // One workgroup per CU at a time.  When rounds of whole tiles would leave CUs idle, every CU
-        // can get the same share of (tile, step) units instead, the split tiles being summed by a
-        // second, small kernel.  That pays when the steps saved outweigh the partial tiles written
-        // and read back (two 256 KiB slots per workgroup at most, one per tile at least).
-        int device = 0, cus = 0;
-        err = hipGetDevice(&device);
-        if (err == hipSuccess)
-            err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
-        if (err != hipSuccess)
-            return err;
-        cus = cus / 8 * 8;
-        const int rounds = cus > 0 ? (tiles + cus - 1) / cus : 0;
-        const int64_t units = (int64_t)tiles * steps;
-        // measured on this kernel: 0.6 us per step, 0.08 us per partial tile written and read, 10 us for the second launch
-        const double whole_cost = 0.6 * rounds * steps;
-        const double split_cost = cus > 0 ? 0.6 * (double)((units + cus - 1) / cus) + 0.08 * (cus + tiles) + 10.0 : 0.0;
-        const bool split = cus >= 8 && split_cost < whole_cost && units >= 4 * (int64_t)cus;
-        int blocks = (tiles + 7) / 8 * 8, per_block = steps, phase_period = 0;
-        if (split) {
-            blocks = cus;
-            per_block = (int)(((int64_t)tiles * steps + blocks - 1) / blocks);
-            // workgroups b and b + period are at the same contraction position at all times
-            const int period = steps / std::gcd(per_block, steps);
-            phase_period = (period % 8 == 0 && blocks % period == 0) ? period : 8;
-            if (blocks % phase_period != 0)
-                phase_period = blocks;
-        }
-        // library-owned device memory: the expanded operand, then the partial tiles
-        const size_t expanded_bytes = ((size_t)q_rows * a.K * 2 + 255) / 256 * 256;
-        const size_t partial_bytes = split ? (size_t)2 * blocks * kSlotQuads * sizeof(float4) : 0;
-        char *memory = nullptr;
-        err = library_memory(device, expanded_bytes + partial_bytes, &memory);
-        if (err != hipSuccess)
-            return err;
+        // the caller's scratch: the expanded operand, then the partial tiles
+        char *memory = static_cast<char *>(a.workspace);
         auto *qhat = reinterpret_cast<uint16_t *>(memory);
-        auto *partial = split ? reinterpret_cast<float4 *>(memory + expanded_bytes) : nullptr;
+        auto *partial = p.split ? reinterpret_cast<float4 *>(memory + p.expanded_bytes) : nullptr;
+        const int tiles_r = p.tiles_r, tiles_k = p.tiles_k, per_block = p.per_block, phase_period = p.phase_period;
+        const int64_t ld_left = p.ld_left, contraction = p.contraction, out_rows = p.out_rows, out_cols = p.out_cols;
 
-        const int64_t groups = q_rows * a.K / 8;
+        const int64_t groups = p.q_rows * a.K / 8;
         hipLaunchKernelGGL(expand_codes_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream,
                            a.q_codes, a.q_scales, levels, a.cb, (int)a.K, groups, qhat);
         err = hipGetLastError();
         if (err != hipSuccess)
             return err;
-        const dim3 grid((unsigned)blocks), block(kGemmThreads);
+        const dim3 grid((unsigned)p.blocks), block(kGemmThreads);
         if (a.which == 0)
             hipLaunchKernelGGL((grad_gemm_tile_kernel<0, kStages>), grid, block, kLds, stream, dy, ld_left, qhat,
                                a.K, (int)contraction, (int)out_rows, (int)out_cols, tiles_r, tiles_k, per_block,
@@ -646,9 +686,10 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
                                a.K, (int)contraction, (int)out_rows, (int)out_cols, tiles_r, tiles_k, per_block,
                                phase_period, out, partial);
         err = hipGetLastError();
-        if (err == hipSuccess && split) {
-            hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles * 16)), dim3(256), 0, stream, partial,
-                               steps, per_block, phase_period, (int)out_rows, (int)out_cols, tiles_r, tiles_k, out);
+        if (err == hipSuccess && p.split) {
+            hipLaunchKernelGGL(grad_gemm_fixup_kernel, dim3((unsigned)(tiles_r * tiles_k * 16)), dim3(256), 0, stream,
+                               partial, p.steps, per_block, phase_period, (int)out_rows, (int)out_cols, tiles_r,
+                               tiles_k, out);
             err = hipGetLastError();
         }
         return err;

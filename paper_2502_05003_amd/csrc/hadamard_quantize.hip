@@ -177,6 +177,17 @@ __global__ __launch_bounds__(kGenericThreads) void hq_generic_kernel(
 
 }  // namespace
 
+// the longest row the entry points accept, as padded fp32
+constexpr int kGenericMaxLds = (QUEST_MAX_COLS + (QUEST_MAX_COLS >> 5) + 1) * (int)sizeof(float);
+
+hipError_t prepare_quantize_kernels()
+{
+    hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(hq_generic_kernel<uint16_t>), kGenericMaxLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(hq_generic_kernel<float>), kGenericMaxLds);
+    return err;
+}
+
 hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
 {
     if (a.rows == 0)

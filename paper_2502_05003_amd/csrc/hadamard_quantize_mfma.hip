@@ -555,6 +555,14 @@ void launch(const QuantizeArgs &a, hipStream_t stream)
 
 }  // namespace
 
+// Makes the runtime load this file's code object now (a query of one kernel's attributes does), so
+// that the first launch, which may be under graph capture, does not.
+hipError_t prepare_quantize_mfma_kernels()
+{
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hq_mfma_kernel<16, 11, true>));
+}
+
 // Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
 // Covered (U = row length / 128):
 //   bf16 rows, b = 4: rows of 512, 1024, 2048, 4096, 5632 or 11008 elements with a Hadamard block of

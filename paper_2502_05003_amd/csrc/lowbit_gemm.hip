@@ -739,7 +739,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
 // ------------------------------------------------------------------------------------------
 // b = 1 and b = 2 on the tile kernels: the codes are first re-coded into nibbles that stand for the
 // same odd integers on the 4-bit grid (u = 2c - (L - 1) = 2(c + (16 - L) / 2) - 15), sixteen codes
-// per thread, into library-owned memory; the accumulators are unchanged.
+// per thread, into scratch memory the caller provides; the accumulators are unchanged.
 // ------------------------------------------------------------------------------------------
 template <int CB>
 __global__ __launch_bounds__(256) void recode_to_nibbles_kernel(const uint8_t *__restrict__ in,
@@ -777,21 +777,46 @@ hipError_t launch_recode(const uint8_t *in, uint8_t *out, int64_t rows, int64_t 
 
 }  // namespace
 
+// the 1- and 2-bit product takes the re-coding path when the tile kernels cover the shape
+static bool recode_path(int64_t M, int64_t N, int64_t K, int bits)
+{
+    return bits <= 2 && (K % TK) == 0 && M >= 128 && N >= 128;
+}
+
+int64_t lowbit_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits)
+{
+    return recode_path(M, N, K, bits) ? (M + N) * K / 2 : 0;
+}
+
+hipError_t prepare_lowbit_gemm_kernels()
+{
+    hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<4>), kWideLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<3>), kWideLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_small_kernel<4>), kSmallLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_small_kernel<3>), kSmallLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<4>), kTileLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<3>), kTileLds);
+    return err;
+}
+
 hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
 {
     if (args.M == 0 || args.N == 0)
         return hipSuccess;
     GemmArgs a = args;
-    if (a.bits <= 2 && (a.K % TK) == 0 && a.M >= 128 && a.N >= 128) {
-        int device = 0;
-        char *memory = nullptr;
-        hipError_t err = hipGetDevice(&device);
-        if (err == hipSuccess)
-            err = library_memory(device, (size_t)((a.M + a.N) * a.K / 2), &memory);
-        uint8_t *a_nibbles = reinterpret_cast<uint8_t *>(memory);
+    // 1 and 2 bits with scratch from the caller: re-code, then the 4-bit tile kernels.  Without
+    // scratch the general kernel below multiplies the narrow containers directly (slower).
+    if (recode_path(a.M, a.N, a.K, a.bits) && a.workspace != nullptr) {
+        if (a.workspace_bytes < lowbit_gemm_workspace_bytes(a.M, a.N, a.K, a.bits))
+            return hipErrorInvalidValue;
+        uint8_t *a_nibbles = static_cast<uint8_t *>(a.workspace);
         uint8_t *b_nibbles = a_nibbles + a.M * a.K / 2;
-        if (err == hipSuccess)
-            err = launch_recode(a.a_codes, a_nibbles, a.M, a.K, a.cb, stream);
+        hipError_t err = launch_recode(a.a_codes, a_nibbles, a.M, a.K, a.cb, stream);
         if (err == hipSuccess)
             err = launch_recode(a.b_codes, b_nibbles, a.N, a.K, a.cb, stream);
         if (err != hipSuccess)
@@ -809,9 +834,7 @@ hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
         wide_tiles >= 192) {
         const int tiles_m = (int)((a.M + WTM - 1) / WTM), tiles_n = (int)((a.N + WTN - 1) / WTN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<4>), kWideLds);
-        if (err == hipSuccess)
-            err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_wide_kernel<3>), kWideLds);
+        const hipError_t err = prepare_lowbit_gemm_kernels();
         if (err != hipSuccess)
             return err;
         const dim3 grid((unsigned)(per_xcd * 8)), block(kWideThreads);
@@ -830,9 +853,7 @@ hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
     if ((a.bits == 4 || a.bits == 3) && (a.K % TK) == 0 && a.M >= 128 && a.N >= 128 && big_tiles < 384) {
         const int tiles_m = (int)((a.M + STM - 1) / STM), tiles_n = (int)((a.N + STN - 1) / STN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_small_kernel<4>), kSmallLds);
-        if (err == hipSuccess)
-            err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_small_kernel<3>), kSmallLds);
+        const hipError_t err = prepare_lowbit_gemm_kernels();
         if (err != hipSuccess)
             return err;
         const dim3 grid((unsigned)(per_xcd * 8)), block(kTileThreads);
@@ -849,9 +870,7 @@ hipError_t launch_lowbit_gemm(const GemmArgs &args, hipStream_t stream)
     if ((a.bits == 4 || a.bits == 3) && (a.K % TK) == 0 && a.M >= 512 && a.N >= 256) {
         const int tiles_m = (int)((a.M + TM - 1) / TM), tiles_n = (int)((a.N + TN - 1) / TN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-        hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<4>), kTileLds);
-        if (err == hipSuccess)
-            err = allow_dynamic_lds(reinterpret_cast<const void *>(lowbit_gemm_tile_kernel<3>), kTileLds);
+        const hipError_t err = prepare_lowbit_gemm_kernels();
         if (err != hipSuccess)
             return err;
         const dim3 grid((unsigned)(per_xcd * 8)), block(kTileThreads);

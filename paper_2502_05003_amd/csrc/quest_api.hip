@@ -96,39 +96,26 @@ hipError_t allow_dynamic_lds(const void *kernel, int bytes)
     return err;
 }
 
-/*
- * Device memory the library owns (the expanded operand and the partial tiles of the gradient
- * matmuls, re-coded operands of the 1- and 2-bit matmul): one buffer per device, grown on demand
- * and kept until the process ends.  All launches that use it on a device share it, so they must
- * not overlap (they do not when issued to one stream).  Growing frees the old buffer after a
- * device synchronisation.
- */
-hipError_t library_memory(int device, size_t bytes, char **out_ptr)
+int device_compute_units()
 {
     constexpr int kMaxDevices = 64;
     static std::mutex guard;
-    static void *buffer[kMaxDevices] = {};
-    static size_t capacity[kMaxDevices] = {};
-    if (device < 0 || device >= kMaxDevices)
-        return hipErrorInvalidDevice;
-    std::lock_guard<std::mutex> lock(guard);
-    if (capacity[device] < bytes) {
-        if (buffer[device] != nullptr) {
-            hipError_t err = hipDeviceSynchronize();
-            if (err == hipSuccess)
-                err = hipFree(buffer[device]);
-            if (err != hipSuccess)
-                return err;
-            buffer[device] = nullptr;
-            capacity[device] = 0;
-        }
-        hipError_t err = hipMalloc(&buffer[device], bytes);
-        if (err != hipSuccess)
-            return err;
-        capacity[device] = bytes;
+    static int known[kMaxDevices] = {};
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) {
+        (void)hipGetLastError();   // host-only use: leave no sticky error behind
+        return 256;
     }
-    *out_ptr = static_cast<char *>(buffer[device]);
-    return hipSuccess;
+    std::lock_guard<std::mutex> lock(guard);
+    if (known[device] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 8) {
+            (void)hipGetLastError();
+            return 256;
+        }
+        known[device] = cus / 8 * 8;
+    }
+    return known[device];
 }
 
 }  // namespace quest
@@ -250,23 +237,29 @@ float quest_alpha_star_fp4(void)
     return (float)kAlphaStarFp4;
 }
 
-quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,
+namespace {
+
+quest_status lowbit_gemm_entry(const uint8_t *a_codes, const float *a_scales, int64_t M,
                                const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
-                               int32_t bits, void *y, int64_t ld_y, int32_t *acc_out,
-                               void *stream)
+                               int32_t bits, void *y, int64_t ld_y, int32_t *acc_out, void *workspace,
+                               int64_t workspace_bytes, void *stream)
 {
     if (!a_codes || !a_scales || !b_codes || !b_scales || (!y && !acc_out))
         return QUEST_ERR_NULL;
     if (bits < 1 || bits > 4)
         return QUEST_ERR_BITS;
+    // the tile kernels keep per-lane byte offsets into an operand (rows of K/2 bytes as nibbles) in 32 bits
     if (M < 0 || N < 0 || M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K < 64 ||
-        K > 65536 || (K & 63))
+        K > 65536 || (K & 63) || (M > N ? M : N) * (K / 2) >= (int64_t(1) << 32))
         return QUEST_ERR_SHAPE;
     if (y && ld_y < N)
         return QUEST_ERR_SHAPE;
     if (!aligned16(a_codes) || !aligned16(b_codes) || (y && !aligned16(y)) ||
-        (acc_out && !aligned16(acc_out)))
+        (acc_out && !aligned16(acc_out)) || (workspace && !aligned16(workspace)))
         return QUEST_ERR_ALIGN;
+    if (workspace_bytes < 0 ||
+        (workspace && workspace_bytes < quest::lowbit_gemm_workspace_bytes(M, N, K, bits)))
+        return QUEST_ERR_ARG;
 
     quest::GemmArgs args;
     args.a_codes = a_codes;
@@ -281,9 +274,30 @@ quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, in
     args.y = y;
     args.ld_y = ld_y;
     args.acc_out = acc_out;
+    args.workspace = workspace;
+    args.workspace_bytes = workspace_bytes;
     return quest::launch_lowbit_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUEST_OK
                : QUEST_ERR_LAUNCH;
+}
+
+}  // namespace
+
+int64_t quest_lowbit_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int32_t bits)
+{
+    if (bits < 1 || bits > 4 || M < 0 || N < 0 || M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K < 64 ||
+        K > 65536 || (K & 63) || (M > N ? M : N) * (K / 2) >= (int64_t(1) << 32))
+        return -1;
+    return quest::lowbit_gemm_workspace_bytes(M, N, K, bits);
+}
+
+quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, int64_t M,
+                               const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
+                               int32_t bits, void *y, int64_t ld_y, int32_t *acc_out, void *workspace,
+                               int64_t workspace_bytes, void *stream)
+{
+    return lowbit_gemm_entry(a_codes, a_scales, M, b_codes, b_scales, N, K, bits, y, ld_y, acc_out, workspace,
+                             workspace_bytes, stream);
 }
 
 quest_status quest_lowbit_gemm_fp4(const uint8_t *a_codes, const float *a_scales, int64_t M,
@@ -345,26 +359,42 @@ quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint
                : QUEST_ERR_LAUNCH;
 }
 
-quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_codes,
-                             const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,
-                             void *out, void *stream)
+namespace {
+
+// Shape rules shared by the three entry points on the bf16 tile kernels and by their size queries.
+// form: 0 / 1 = the gradient matmuls of Algorithm 2, 2 = the weight-only forward product.
+bool grad_family_shape_ok(int form, bool fp4, int64_t M, int64_t N, int64_t K)
 {
-    if (!dy || !q_codes || !q_scales || !out)
+    const int64_t limit = int64_t(1) << 22;
+    if (M < 0 || N < 0 || K < 0 || (M & 63) || (N & 63) || (K & 63) || M > limit || N > limit || K > limit)
+        return false;
+    if (M == 0 || N == 0 || K == 0)
+        return true;
+    return quest::grad_gemm_workspace_bytes(form, fp4, M, N, K, quest::device_compute_units()) >= 0;
+}
+
+quest_status grad_family_entry(int form, bool fp4, const void *left, const uint8_t *q_codes, const float *q_scales,
+                               int32_t bits, int64_t M, int64_t N, int64_t K, void *out, void *workspace,
+                               int64_t workspace_bytes, void *stream)
+{
+    if (!left || !q_codes || !q_scales || !out)
         return QUEST_ERR_NULL;
-    if (which != 0 && which != 1)
-        return QUEST_ERR_ARG;
     if (bits < 1 || bits > 4)
         return QUEST_ERR_BITS;
-    if (M < 0 || N < 0 || K < 0 || (M & 63) || (N & 63) || (K & 63) || M > (int64_t(1) << 22) ||
-        N > (int64_t(1) << 22) || K > (int64_t(1) << 22))
+    if (!grad_family_shape_ok(form, fp4, M, N, K))
         return QUEST_ERR_SHAPE;
-    if (!aligned16(dy) || !aligned16(q_codes) || !aligned16(out))
+    if (!aligned16(left) || !aligned16(q_codes) || !aligned16(out) || (workspace && !aligned16(workspace)))
         return QUEST_ERR_ALIGN;
+    const int64_t needed = (M == 0 || N == 0 || K == 0)
+                               ? 0
+                               : quest::grad_gemm_workspace_bytes(form, fp4, M, N, K, quest::device_compute_units());
+    if (workspace_bytes < 0 || (needed > 0 && (!workspace || workspace_bytes < needed)))
+        return QUEST_ERR_ARG;
 
     quest::GradGemmArgs args;
-    args.which = which;
-    args.fp4 = false;
-    args.dy = dy;
+    args.which = form;
+    args.fp4 = fp4;
+    args.dy = left;
     args.q_codes = q_codes;
     args.q_scales = q_scales;
     args.bits = bits;
@@ -373,76 +403,86 @@ quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_cod
     args.N = N;
     args.K = K;
     args.out = out;
+    args.workspace = workspace;
+    args.workspace_bytes = workspace_bytes;
     return quest::launch_grad_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUEST_OK
                : QUEST_ERR_LAUNCH;
+}
+
+}  // namespace
+
+int64_t quest_grad_gemm_workspace_bytes(int32_t which, int64_t M, int64_t N, int64_t K)
+{
+    if ((which != 0 && which != 1) || !grad_family_shape_ok(which, false, M, N, K))
+        return -1;
+    if (M == 0 || N == 0 || K == 0)
+        return 0;
+    return quest::grad_gemm_workspace_bytes(which, false, M, N, K, quest::device_compute_units());
+}
+
+quest_status quest_grad_gemm(int32_t which, const void *dy, const uint8_t *q_codes,
+                             const float *q_scales, int32_t bits, int64_t M, int64_t N, int64_t K,
+                             void *out, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (which != 0 && which != 1)
+        return QUEST_ERR_ARG;
+    return grad_family_entry(which, false, dy, q_codes, q_scales, bits, M, N, K, out, workspace, workspace_bytes,
+                             stream);
+}
+
+int64_t quest_grad_gemm_fp4_workspace_bytes(int32_t which, int64_t M, int64_t N, int64_t K)
+{
+    if ((which != 0 && which != 1) || !grad_family_shape_ok(which, true, M, N, K))
+        return -1;
+    if (M == 0 || N == 0 || K == 0)
+        return 0;
+    return quest::grad_gemm_workspace_bytes(which, true, M, N, K, quest::device_compute_units());
 }
 
 quest_status quest_grad_gemm_fp4(int32_t which, const void *dy, const uint8_t *q_codes,
                                  const float *q_scales, int64_t M, int64_t N, int64_t K, void *out,
-                                 void *stream)
+                                 void *workspace, int64_t workspace_bytes, void *stream)
 {
-    if (!dy || !q_codes || !q_scales || !out)
-        return QUEST_ERR_NULL;
     if (which != 0 && which != 1)
         return QUEST_ERR_ARG;
-    const int64_t out_rows = which == 0 ? M : N, contraction = which == 0 ? N : M;
-    const bool empty = M == 0 || N == 0 || K == 0;
-    if (M < 0 || N < 0 || K < 0 || (out_rows & 63) || (K & 63) || (contraction & 63) ||
-        (!empty && (out_rows < 128 || K < 128)) || M > (int64_t(1) << 22) || N > (int64_t(1) << 22) || K > (int64_t(1) << 22) ||
-        out_rows * K >= (int64_t(1) << 31) || (M > N ? M : N) * (K > N ? K : N) >= (int64_t(1) << 30))
-        return QUEST_ERR_SHAPE;
-    if (!aligned16(dy) || !aligned16(q_codes) || !aligned16(out))
-        return QUEST_ERR_ALIGN;
-    quest::GradGemmArgs args;
-    args.which = which;
-    args.fp4 = true;
-    args.dy = dy;
-    args.q_codes = q_codes;
-    args.q_scales = q_scales;
-    args.bits = 4;
-    args.cb = 4;
-    args.M = M;
-    args.N = N;
-    args.K = K;
-    args.out = out;
-    return quest::launch_grad_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? QUEST_OK
-               : QUEST_ERR_LAUNCH;
+    return grad_family_entry(which, true, dy, q_codes, q_scales, 4, M, N, K, out, workspace, workspace_bytes,
+                             stream);
+}
+
+int64_t quest_weight_only_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (!grad_family_shape_ok(2, false, M, N, K))
+        return -1;
+    if (M == 0 || N == 0 || K == 0)
+        return 0;
+    return quest::grad_gemm_workspace_bytes(2, false, M, N, K, quest::device_compute_units());
 }
 
 quest_status quest_weight_only_gemm(const void *x, const uint8_t *w_codes, const float *w_scales,
                                     int32_t bits, int64_t M, int64_t N, int64_t K, void *y,
-                                    void *stream)
+                                    void *workspace, int64_t workspace_bytes, void *stream)
 {
-    if (!x || !w_codes || !w_scales || !y)
-        return QUEST_ERR_NULL;
-    if (bits < 1 || bits > 4)
-        return QUEST_ERR_BITS;
-    const bool empty = M == 0 || N == 0 || K == 0;
-    if (M < 0 || N < 0 || K < 0 || (M & 63) || (N & 63) || (K & 63) || (!empty && (M < 128 || N < 128)) ||
-        M > (int64_t(1) << 22) ||
-        N > (int64_t(1) << 22) || K > (int64_t(1) << 22) || M * N >= (int64_t(1) << 31) ||
-        (M > N ? M : N) * (K > N ? K : N) >= (int64_t(1) << 30))
-        return QUEST_ERR_SHAPE;
-    if (!aligned16(x) || !aligned16(w_codes) || !aligned16(y))
-        return QUEST_ERR_ALIGN;
+    return grad_family_entry(2, false, x, w_codes, w_scales, bits, M, N, K, y, workspace, workspace_bytes,
+                             stream);
+}
 
-    quest::GradGemmArgs args;
-    args.which = 2;
-    args.fp4 = false;
-    args.dy = x;
-    args.q_codes = w_codes;
-    args.q_scales = w_scales;
-    args.bits = bits;
-    args.cb = container_bits(bits);
-    args.M = M;
-    args.N = N;
-    args.K = K;
-    args.out = y;
-    return quest::launch_grad_gemm(args, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? QUEST_OK
-               : QUEST_ERR_LAUNCH;
+quest_status quest_init(void)
+{
+    hipError_t err = quest::prepare_quantize_kernels();
+    if (err == hipSuccess)
+        err = quest::prepare_quantize_mfma_kernels();
+    if (err == hipSuccess)
+        err = quest::prepare_trust_backward_mfma_kernels();
+    if (err == hipSuccess)
+        err = quest::prepare_lowbit_gemm_kernels();
+    if (err == hipSuccess)
+        err = quest::prepare_fp4_gemm_kernels();
+    if (err == hipSuccess)
+        err = quest::prepare_trust_backward_kernels();
+    if (err == hipSuccess)
+        err = quest::prepare_grad_gemm_kernels();
+    return err == hipSuccess ? QUEST_OK : QUEST_ERR_LAUNCH;
 }
 
 }  // extern "C"

@@ -42,9 +42,14 @@ struct GemmArgs {
     void *y;          // bf16, may be null
     int64_t ld_y;
     int32_t *acc_out; // may be null
+    void *workspace;  // caller's scratch for the re-coded operands of 1- and 2-bit products; may be null
+    int64_t workspace_bytes;
 };
 
 hipError_t launch_lowbit_gemm(const GemmArgs &a, hipStream_t stream);
+// Scratch the fast path of a 1- or 2-bit product needs (both operands re-coded as nibbles); 0 when the
+// shape or the bit width does not take that path.
+int64_t lowbit_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
 
 struct Fp4GemmArgs {
     const uint8_t *a_codes;
@@ -82,13 +87,31 @@ struct GradGemmArgs {
     bool fp4;          // the codes are E2M1 codes (bits = cb = 4)
     int64_t M, N, K;
     void *out;
+    void *workspace;   // caller's scratch: the expanded operand, then the partial tiles
+    int64_t workspace_bytes;
 };
 
+// hipErrorInvalidValue: the shape is not one the kernels cover, or the workspace is too small
+// (the entry points check both beforehand with grad_gemm_workspace_bytes).
 hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream);
+// Scratch bytes a call with these arguments needs on a device with `cus` compute units (0 for the
+// small-shape kernel, which dequantizes in place); -1 when no kernel covers the shape.
+int64_t grad_gemm_workspace_bytes(int which, bool fp4, int64_t M, int64_t N, int64_t K, int cus);
 
-// Library-owned device memory of at least `bytes` on `device` (one buffer per device, grown on
-// demand with hipMalloc after a device synchronisation, never shrunk): users on one device share it.
-hipError_t library_memory(int device, size_t bytes, char **out_ptr);
+// Compute units of the current device, rounded down to a multiple of eight (one per XCD); 256, the
+// MI355X's count, when no device can be asked (host-only use of the size queries).
+int device_compute_units();
+
+// Each family's kernels get their dynamic LDS limits on the current device, and the code objects of
+// the files without such kernels are loaded (what quest_init does, so that no enqueue call has to
+// change a kernel attribute or load code later).
+hipError_t prepare_quantize_kernels();
+hipError_t prepare_quantize_mfma_kernels();
+hipError_t prepare_trust_backward_mfma_kernels();
+hipError_t prepare_lowbit_gemm_kernels();
+hipError_t prepare_fp4_gemm_kernels();
+hipError_t prepare_trust_backward_kernels();
+hipError_t prepare_grad_gemm_kernels();
 
 // Raise the dynamic LDS limit of `kernel` to `bytes` on the current device.  The attribute is set
 // once per (kernel, device, size) and remembered; safe to call from several host threads.

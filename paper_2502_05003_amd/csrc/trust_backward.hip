@@ -74,6 +74,19 @@ hipError_t launch_generic(const BackwardArgs &a, hipStream_t stream)
 
 }  // namespace
 
+hipError_t prepare_trust_backward_kernels()
+{
+    constexpr int kMaxLds = (QUEST_MAX_COLS + (QUEST_MAX_COLS >> 5) + 1) * (int)sizeof(float);
+    hipError_t err = allow_dynamic_lds(reinterpret_cast<const void *>(tb_generic_kernel<uint16_t, uint16_t>), kMaxLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(tb_generic_kernel<uint16_t, float>), kMaxLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(tb_generic_kernel<float, uint16_t>), kMaxLds);
+    if (err == hipSuccess)
+        err = allow_dynamic_lds(reinterpret_cast<const void *>(tb_generic_kernel<float, float>), kMaxLds);
+    return err;
+}
+
 hipError_t launch_trust_backward(const BackwardArgs &a, hipStream_t stream)
 {
     if (a.rows == 0)

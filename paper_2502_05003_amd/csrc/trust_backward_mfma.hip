@@ -160,6 +160,14 @@ void launch(const BackwardArgs &a, hipStream_t stream)
 
 }  // namespace
 
+// Makes the runtime load this file's code object now (a query of one kernel's attributes does), so
+// that the first launch, which may be under graph capture, does not.
+hipError_t prepare_trust_backward_mfma_kernels()
+{
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(tb_mfma_kernel<16, 11, true, uint16_t>));
+}
+
 // Launches the matrix-core kernel if it covers the call; returns false (nothing launched) otherwise.
 // Covered (U = row length / 128): bf16 in; bf16 out for rows of 512, 1024, 2048, 4096, 5632 or 11008
 // elements with a Hadamard block of at most 32, or 128, 256 (11008 only), 512, 1024, 2048, 4096 where

@@ -18,6 +18,25 @@ def to_device(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(a).to(DEV)
 
 
+def _scratch(nbytes: int):
+    """Caller-owned scratch of at least `nbytes` (None when the call needs none); filled with a pattern."""
+    assert nbytes >= 0, "the library does not accept this shape"
+    return torch.full((nbytes,), 0xC3, dtype=torch.uint8, device=DEV) if nbytes else None
+
+
+def grad_ws(which: int, M: int, N: int, K: int, fp4: bool = False):
+    query = q.quest_grad_gemm_fp4_workspace_bytes if fp4 else q.quest_grad_gemm_workspace_bytes
+    return _scratch(query(which, M, N, K))
+
+
+def weight_only_ws(M: int, N: int, K: int):
+    return _scratch(q.quest_weight_only_gemm_workspace_bytes(M, N, K))
+
+
+def lowbit_ws(M: int, N: int, K: int, bits: int):
+    return _scratch(q.quest_lowbit_gemm_workspace_bytes(M, N, K, bits))
+
+
 def to_host_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 

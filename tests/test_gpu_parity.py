@@ -10,7 +10,7 @@ from paper_2502_05003_amd import binding as q
 from paper_2502_05003_amd import synth
 
 from gpu_util import (BF16_HALF_ULP, DEV, check_gemm_output, compare_quantizer, compare_quantizer_fp4, gpu_quantize,
-                      to_device, to_host_f64)
+                      grad_ws, lowbit_ws, to_device, to_host_f64, weight_only_ws)
 
 pytestmark = pytest.mark.gpu
 
@@ -257,8 +257,12 @@ GEMM_CASES = [(256, 512, 512, 4), (130, 200, 1024, 4), (1, 1, 64, 4), (257, 129,
               (4000, 4100, 384, 1), (512, 256, 128, 2)]
 
 
-@pytest.mark.parametrize("M,N,K,bits", GEMM_CASES)
-def test_gemm_accumulators_exact_and_output_close(M, N, K, bits):
+# every case with caller scratch where the call can use it; the 1- and 2-bit cases that can, also without
+GEMM_RUNS = [(*c, True) for c in GEMM_CASES] + [(*c, False) for c in GEMM_CASES if c[3] <= 2 and min(c[0], c[1]) >= 128]
+
+
+@pytest.mark.parametrize("M,N,K,bits,scratch", GEMM_RUNS)
+def test_gemm_accumulators_exact_and_output_close(M, N, K, bits, scratch):
     rng = np.random.default_rng(M * 7 + N * 3 + K + bits)
     L = 1 << bits
     cb = qo.container_bits(bits)
@@ -278,7 +282,7 @@ def test_gemm_accumulators_exact_and_output_close(M, N, K, bits):
     y = torch.full((M, N + 2), 7.0, dtype=torch.bfloat16, device=DEV)   # ld_y > N
     acc = torch.empty(M, N, dtype=torch.int32, device=DEV)
     q.quest_lowbit_gemm(to_device(a_codes), to_device(sa), to_device(b_codes), to_device(sb), K, bits,
-                        y=y[:, :N], acc_out=acc)
+                        y=y[:, :N], acc_out=acc, workspace=lowbit_ws(M, N, K, bits) if scratch else None)
     torch.cuda.synchronize()
     ref_acc = qo.gemm_odd(2 * ka + 1, 2 * kb + 1)
     got_acc = acc.cpu().numpy().astype(np.int64)
@@ -484,7 +488,7 @@ def test_grad_gemm_matches_oracle(which, M, N, K):
     gq = gpu_quantize(src, n, bits, want_xh=False)
     rows_out = M if which == 0 else N
     out = torch.empty(rows_out, K, dtype=torch.bfloat16, device=DEV)
-    q.quest_grad_gemm(which, to_device(dy), gq["dev"]["codes"], gq["dev"]["scales"], bits, M, N, K, out=out)
+    q.quest_grad_gemm(which, to_device(dy), gq["dev"]["codes"], gq["dev"]["scales"], bits, M, N, K, out=out, workspace=grad_ws(which, M, N, K))
     torch.cuda.synchronize()
     u = qo.unpack_odd(gq["codes"], K, bits)
     s = gq["scales"].astype(np.float64)
@@ -517,8 +521,8 @@ def test_grad_gemm_full_size_sampled_rows():
     dyd = to_device(dy)
     g_x = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
     g_w = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
-    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x)
-    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w)
+    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x, workspace=grad_ws(0, M, N, K))
+    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w, workspace=grad_ws(1, M, N, K))
     torch.cuda.synchronize()
     assert torch.isfinite(g_x.float()).all() and torch.isfinite(g_w.float()).all()
     rng = np.random.default_rng(1)
@@ -566,8 +570,8 @@ def test_down_projection_full_size():
     dyd = to_device(dy)
     g_x = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
     g_w = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
-    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x)
-    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w)
+    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x, workspace=grad_ws(0, M, N, K))
+    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w, workspace=grad_ws(1, M, N, K))
     dx = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
     q.quest_trust_backward(g_x, gx["dev"]["mask"], n, out=dx)
     torch.cuda.synchronize()
@@ -618,7 +622,7 @@ def test_weight_only_gemm_matches_oracle(M, N, K, bits):
     xh = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
     q.quest_trust_backward(to_device(x), None, n, out=xh)
     y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
-    q.quest_weight_only_gemm(xh, gw["dev"]["codes"], gw["dev"]["scales"], bits, y=y)
+    q.quest_weight_only_gemm(xh, gw["dev"]["codes"], gw["dev"]["scales"], bits, y=y, workspace=weight_only_ws(M, N, K))
     torch.cuda.synchronize()
     xh_host = to_host_f64(xh)
     ref_xh = qo.hadamard(qo.widen(x), n)
@@ -648,11 +652,12 @@ def test_split_tiles_are_summed_in_a_fixed_order():
     outs = []
     for rep in range(3):
         out = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
-        q.quest_grad_gemm(1, dy, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=out)
-        if rep == 0:   # a call of another shape in between re-uses (and here regrows) the library's memory
+        q.quest_grad_gemm(1, dy, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=out, workspace=grad_ws(1, M, N, K))
+        if rep == 0:   # a call of another shape in between, with scratch of its own
             other = torch.empty(256, 256, dtype=torch.bfloat16, device=DEV)
             q.quest_grad_gemm(0, dy[:256, :256].contiguous(), gx["dev"]["codes"][:256, :128].contiguous(),
-                              gx["dev"]["scales"][:256].contiguous(), bits, 256, 256, 256, out=other)
+                              gx["dev"]["scales"][:256].contiguous(), bits, 256, 256, 256, out=other,
+                              workspace=grad_ws(0, 256, 256, 256))
         outs.append(out)
     torch.cuda.synchronize()
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[1], outs[2])
@@ -669,7 +674,8 @@ def test_fp4_grad_gemm_matches_oracle(which, M, N, K):
     dy = synth.upstream_gradient(M, N, 0, "bf16")
     gq = gpu_quantize(w if which == 0 else x, n, 4, want_xh=False, fp4=True)
     out = torch.empty(M if which == 0 else N, K, dtype=torch.bfloat16, device=DEV)
-    q.quest_grad_gemm_fp4(which, to_device(dy), gq["dev"]["codes"], gq["dev"]["scales"], M, N, K, out=out)
+    q.quest_grad_gemm_fp4(which, to_device(dy), gq["dev"]["codes"], gq["dev"]["scales"], M, N, K, out=out,
+                          workspace=grad_ws(which, M, N, K, fp4=True))
     torch.cuda.synchronize()
     v = qo.unpack_fp4(gq["codes"], K)
     u2 = np.rint(2.0 * v).astype(np.int32)                      # E2M1 values are multiples of 1/2
@@ -698,8 +704,8 @@ def test_full_linear_forward_backward_small():
     dyd = to_device(dy)
     g_x = torch.empty(M, K, dtype=torch.bfloat16, device=DEV)
     g_w = torch.empty(N, K, dtype=torch.bfloat16, device=DEV)
-    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x)
-    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w)
+    q.quest_grad_gemm(0, dyd, gw["dev"]["codes"], gw["dev"]["scales"], bits, M, N, K, out=g_x, workspace=grad_ws(0, M, N, K))
+    q.quest_grad_gemm(1, dyd, gx["dev"]["codes"], gx["dev"]["scales"], bits, M, N, K, out=g_w, workspace=grad_ws(1, M, N, K))
     dx = torch.empty(M, K, dtype=torch.float32, device=DEV)
     dw = torch.empty(N, K, dtype=torch.float32, device=DEV)
     q.quest_trust_backward(g_x, gx["dev"]["mask"], n, out=dx)
@@ -715,12 +721,14 @@ def test_full_linear_forward_backward_small():
 
 
 def test_whole_step_replayed_from_a_graph_matches_eager_launches():
-    """The step's seven calls captured into one HIP graph (after an eager step has set the kernels'
-    LDS limits and grown the library's scratch memory) and replayed on new input contents, with eager
-    work and synchronisations between the replays: every replay must reproduce, bit for bit, what the
-    same calls give when launched one by one.  Shapes that split tiles (second launch, scratch slots)."""
+    """The step's seven calls captured into one HIP graph with no eager call before the capture (only
+    quest_init), then a larger gradient matmul run eagerly with scratch of its own, then replays on
+    new input contents with eager work and synchronisations between them: every replay must
+    reproduce, bit for bit, what the same calls give when launched one by one.  Shapes that split
+    tiles (second launch, partial tiles in the caller's workspace)."""
     M, N, K, bits, n = 768, 8192, 512, 4, 512
     dev = torch.device(DEV)
+    q.quest_init()
 
     def buffers():
         u8, f32, b16 = torch.uint8, torch.float32, torch.bfloat16
@@ -735,12 +743,12 @@ def test_whole_step_replayed_from_a_graph_matches_eager_launches():
     w = torch.empty(N, K, dtype=torch.bfloat16, device=dev)
     dy = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
 
-    def step(b):
+    def step(b, scratch):
         q.quest_hadamard_quantize(x, n, bits, codes=b["xc"], scales=b["xs"], mask=b["xm"])
         q.quest_hadamard_quantize(w, n, bits, codes=b["wc"], scales=b["ws"], mask=b["wm"])
         q.quest_lowbit_gemm(b["xc"], b["xs"], b["wc"], b["ws"], K, bits, y=b["y"])
-        q.quest_grad_gemm(0, dy, b["wc"], b["ws"], bits, M, N, K, out=b["gx"])
-        q.quest_grad_gemm(1, dy, b["xc"], b["xs"], bits, M, N, K, out=b["gw"])
+        q.quest_grad_gemm(0, dy, b["wc"], b["ws"], bits, M, N, K, out=b["gx"], workspace=scratch[0])
+        q.quest_grad_gemm(1, dy, b["xc"], b["xs"], bits, M, N, K, out=b["gw"], workspace=scratch[1])
         q.quest_trust_backward(b["gx"], b["xm"], n, out=b["dx"])
         q.quest_trust_backward(b["gw"], b["wm"], n, out=b["dw"])
 
@@ -750,20 +758,56 @@ def test_whole_step_replayed_from_a_graph_matches_eager_launches():
         dy.copy_(to_device(synth.upstream_gradient(M, N, seed + 2, "bf16")).view(torch.bfloat16))
 
     eager, captured = buffers(), buffers()
+    eager_scratch = (grad_ws(0, M, N, K), grad_ws(1, M, N, K))
+    captured_scratch = (grad_ws(0, M, N, K), grad_ws(1, M, N, K))
     fill(0)
-    step(eager)                       # sets function attributes, grows the scratch memory
     torch.cuda.synchronize()
     stream = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(stream):
         with torch.cuda.graph(graph, stream=stream):
-            step(captured)
+            step(captured, captured_scratch)
+    torch.cuda.synchronize()
+    # a larger shape, eagerly, after the capture: it brings its own scratch and touches nothing of the graph's
+    M2, N2, K2 = 2048, 8192, 1024
+    big_codes = torch.zeros(M2, K2 // 2, dtype=torch.uint8, device=dev)
+    big_scales = torch.ones(M2, dtype=torch.float32, device=dev)
+    big_dy = torch.zeros(M2, N2, dtype=torch.bfloat16, device=dev)
+    big_out = torch.empty(N2, K2, dtype=torch.bfloat16, device=dev)
+    q.quest_grad_gemm(1, big_dy, big_codes, big_scales, bits, M2, N2, K2, out=big_out, workspace=grad_ws(1, M2, N2, K2))
     torch.cuda.synchronize()
     for seed in (10, 20, 30):
         fill(seed)
-        step(eager)
+        step(eager, eager_scratch)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         for name in eager:
             assert torch.equal(eager[name].view(torch.uint8), captured[name].view(torch.uint8)), (seed, name)
+
+
+def test_two_streams_with_two_workspaces_run_concurrently():
+    """Two weight-gradient matmuls (split tiles: expanded operand and partial tiles in scratch) issued to
+    two streams with a workspace each must give what each gives alone."""
+    M, N, K, bits = 8192, 768, 512, 4
+    dev = torch.device(DEV)
+    jobs = []
+    for seed in (1, 2):
+        gx = gpu_quantize(synth.gaussian(M, K, 1.0, seed, "bf16"), 512, bits, want_xh=False, want_mask=False)
+        jobs.append(dict(dy=to_device(synth.upstream_gradient(M, N, seed + 10, "bf16")), codes=gx["dev"]["codes"],
+                         scales=gx["dev"]["scales"], ws=grad_ws(1, M, N, K),
+                         alone=torch.empty(N, K, dtype=torch.bfloat16, device=dev),
+                         together=torch.empty(N, K, dtype=torch.bfloat16, device=dev)))
+    for j in jobs:
+        q.quest_grad_gemm(1, j["dy"], j["codes"], j["scales"], bits, M, N, K, out=j["alone"], workspace=j["ws"])
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(4):
+        for j, st in zip(jobs, streams):
+            with torch.cuda.stream(st):
+                q.quest_grad_gemm(1, j["dy"], j["codes"], j["scales"], bits, M, N, K, out=j["together"],
+                                  workspace=j["ws"])
+    torch.cuda.synchronize()
+    for j in jobs:
+        assert torch.equal(j["alone"], j["together"])
+    assert not torch.equal(jobs[0]["alone"], jobs[1]["alone"])

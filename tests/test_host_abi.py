@@ -61,13 +61,24 @@ def test_quantizer_rejects_bad_arguments(lib):
 
 
 def test_gemm_backward_and_grad_gemm_reject_bad_arguments(lib):
-    def gemm(a=FAKE, sa=FAKE, M=0, b=FAKE, sb=FAKE, N=0, K=512, bits=4, y=FAKE, ld=0, acc=None):
-        return lib.quest_lowbit_gemm(a, sa, M, b, sb, N, K, bits, y, ld, acc, None)
+    def gemm(a=FAKE, sa=FAKE, M=0, b=FAKE, sb=FAKE, N=0, K=512, bits=4, y=FAKE, ld=0, acc=None, ws=None, wsb=0):
+        return lib.quest_lowbit_gemm(a, sa, M, b, sb, N, K, bits, y, ld, acc, ws, wsb, None)
     assert gemm() == 0
     assert gemm(a=None) == 1 and gemm(y=None) == 1 and gemm(y=None, acc=FAKE) == 0
     assert gemm(bits=8) == 3 and gemm(bits=0) == 3
     assert gemm(K=96) == 2 and gemm(K=0) == 2 and gemm(M=-1) == 2 and gemm(N=8, ld=4) == 2
     assert gemm(a=ctypes.c_void_p(0x10004)) == 5
+    # per-lane operand offsets are 32-bit: max(M, N) * K / 2 must stay below 2^32 (a million tokens at K = 8192 do not)
+    assert gemm(M=1 << 20, N=1 << 20, K=8192, ld=1 << 20) == 2 and gemm(M=(1 << 20) - 64, N=64, K=8192, ld=64, y=None) == 1
+    assert q.quest_lowbit_gemm_workspace_bytes(1 << 20, 64, 8192, 4) == -1
+    # scratch for the 1- and 2-bit fast path: both operands as nibbles; too small is an argument error
+    assert q.quest_lowbit_gemm_workspace_bytes(512, 256, 1024, 2) == (512 + 256) * 512
+    assert q.quest_lowbit_gemm_workspace_bytes(512, 256, 1024, 4) == 0
+    assert q.quest_lowbit_gemm_workspace_bytes(64, 256, 1024, 1) == 0      # below the tile kernels' sizes
+    assert q.quest_lowbit_gemm_workspace_bytes(512, 256, 1024, 8) == -1
+    assert gemm(M=512, N=256, K=1024, bits=2, ld=256, ws=FAKE, wsb=(512 + 256) * 512 - 1) == 8
+    assert gemm(M=512, N=256, K=1024, bits=2, ld=256, ws=ctypes.c_void_p(0x10008), wsb=1 << 20) == 5
+    assert gemm(wsb=-1) == 8
 
     def back(g=FAKE, gd=1, mask=FAKE, rows=0, cols=512, n=512, out=FAKE, od=1):
         return lib.quest_trust_backward(g, gd, mask, rows, cols, n, out, od, None)
@@ -75,10 +86,19 @@ def test_gemm_backward_and_grad_gemm_reject_bad_arguments(lib):
     assert back(g=None) == 1 and back(out=None) == 1 and back(gd=3) == 6 and back(od=-1) == 6
     assert back(cols=20) == 2 and back(n=48) == 4 and back(out=ctypes.c_void_p(0x10002)) == 5
 
-    def grad(which=0, dy=FAKE, qc=FAKE, qs=FAKE, bits=4, M=0, N=0, K=0, out=FAKE):
-        return lib.quest_grad_gemm(which, dy, qc, qs, bits, M, N, K, out, None)
+    def grad(which=0, dy=FAKE, qc=FAKE, qs=FAKE, bits=4, M=0, N=0, K=0, out=FAKE, ws=None, wsb=0):
+        return lib.quest_grad_gemm(which, dy, qc, qs, bits, M, N, K, out, ws, wsb, None)
     assert grad() == 0
     assert grad(which=2) == 8 and grad(dy=None) == 1 and grad(bits=8) == 3 and grad(M=32) == 2
+    # scratch: the expanded operand (bf16), plus two 256 KiB partial-tile slots per compute unit when tiles are split
+    assert q.quest_grad_gemm_workspace_bytes(0, 64, 64, 64) == 0            # small-shape kernel: none
+    need = q.quest_grad_gemm_workspace_bytes(1, 8192, 768, 512)
+    assert need >= 8192 * 512 * 2 and need % 256 == 0
+    assert q.quest_grad_gemm_workspace_bytes(0, 512, 256, 512) == 256 * 512 * 2    # whole tiles only
+    assert q.quest_grad_gemm_workspace_bytes(2, 512, 256, 512) == -1 and q.quest_grad_gemm_workspace_bytes(0, 32, 64, 64) == -1
+    assert grad(which=1, M=8192, N=768, K=512) == 8                         # workspace missing
+    assert grad(which=1, M=8192, N=768, K=512, ws=FAKE, wsb=need - 1) == 8  # too small
+    assert grad(which=1, M=8192, N=768, K=512, ws=ctypes.c_void_p(0x10004), wsb=need) == 5
 
 
 def test_variant_entry_points_reject_bad_arguments(lib):
@@ -99,13 +119,19 @@ def test_variant_entry_points_reject_bad_arguments(lib):
     assert gemm4(K=64) == 2 and gemm4(K=192) == 2 and gemm4(K=131072) == 2 and gemm4(N=8, ld=4) == 2
     assert gemm4(b=ctypes.c_void_p(0x10004)) == 5
 
-    def grad4(which=0, dy=FAKE, qc=FAKE, qs=FAKE, M=0, N=0, K=0, out=FAKE):
-        return lib.quest_grad_gemm_fp4(which, dy, qc, qs, M, N, K, out, None)
+    def grad4(which=0, dy=FAKE, qc=FAKE, qs=FAKE, M=0, N=0, K=0, out=FAKE, ws=None, wsb=0):
+        return lib.quest_grad_gemm_fp4(which, dy, qc, qs, M, N, K, out, ws, wsb, None)
     assert grad4() == 0 and grad4(which=2) == 8 and grad4(qc=None) == 1
     assert grad4(M=64, N=256, K=256) == 2 and grad4(M=256, N=32, K=256) == 2 and grad4(M=256, N=256, K=64) == 2
+    assert q.quest_grad_gemm_fp4_workspace_bytes(0, 64, 256, 256) == -1
+    assert q.quest_grad_gemm_fp4_workspace_bytes(0, 512, 256, 512) == 256 * 512 * 2
+    assert grad4(M=512, N=256, K=512) == 8 and grad4(M=512, N=256, K=512, ws=FAKE, wsb=100) == 8
 
-    def wonly(x=FAKE, wc=FAKE, ws=FAKE, bits=4, M=0, N=0, K=0, y=FAKE):
-        return lib.quest_weight_only_gemm(x, wc, ws, bits, M, N, K, y, None)
+    def wonly(x=FAKE, wc=FAKE, ws=FAKE, bits=4, M=0, N=0, K=0, y=FAKE, scratch=None, sb=0):
+        return lib.quest_weight_only_gemm(x, wc, ws, bits, M, N, K, y, scratch, sb, None)
+    assert q.quest_weight_only_gemm_workspace_bytes(256, 256, 64) == 256 * 64 * 2
+    assert q.quest_weight_only_gemm_workspace_bytes(64, 256, 64) == -1
+    assert wonly(M=256, N=256, K=64) == 8
     assert wonly() == 0
     assert wonly(x=None) == 1 and wonly(bits=8) == 3
     assert wonly(M=64, N=256, K=64) == 2 and wonly(M=256, N=256, K=32) == 2 and wonly(M=256, N=192 + 8, K=64) == 2
