@@ -53,7 +53,8 @@ typedef enum {
     QUEST_ERR_ALIGN = 5,   /* pointer or leading dimension not 16-byte aligned */
     QUEST_ERR_DTYPE = 6,   /* unknown quest_dtype */
     QUEST_ERR_LAUNCH = 7,  /* the HIP runtime refused the launch */
-    QUEST_ERR_ARG = 8      /* any other invalid argument (non-finite alpha, workspace missing or too small) */
+    QUEST_ERR_ARG = 8,     /* any other invalid argument (non-finite alpha, workspace missing or too small) */
+    QUEST_ERR_SCRATCH = 9  /* quest_lowbit_gemm_static: the shape needs more than QUEST_STATIC_SCRATCH_BYTES */
 } quest_status;
 
 typedef enum { QUEST_F32 = 0, QUEST_BF16 = 1 } quest_dtype;
@@ -61,6 +62,7 @@ typedef enum { QUEST_F32 = 0, QUEST_BF16 = 1 } quest_dtype;
 /* Limits checked by the entry points. */
 #define QUEST_MAX_COLS 16384      /* longest row the quantizer / trust backward accept */
 #define QUEST_MAX_HAD_BLOCK 16384 /* largest Hadamard block */
+#define QUEST_STATIC_SCRATCH_BYTES (32 << 20) /* built-in scratch of quest_lowbit_gemm_static, per GPU */
 
 /*
  * Algorithm 1, one operand (call once for x, once for w):
@@ -149,6 +151,24 @@ quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, in
 /* Host: scratch bytes the fast path of quest_lowbit_gemm uses for this shape (0: none; -1: the
  * shape or bit width is not accepted). */
 int64_t quest_lowbit_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int32_t bits);
+
+/*
+ * quest_lowbit_gemm for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as quest_lowbit_gemm; the scratch of the 1- and 2-bit fast path is a buffer of
+ * QUEST_STATIC_SCRATCH_BYTES built into the library (one per GPU, held until the process ends), so
+ * the call allocates and frees nothing.  A shape whose scratch
+ * (quest_lowbit_gemm_workspace_bytes: (M + N) * K / 2 bytes) exceeds that size is rejected with
+ * QUEST_ERR_SCRATCH and nothing is launched; bits = 3 or 4 need no scratch and are never rejected
+ * for it.  All calls on one GPU share the buffer: calls that overlap in time on one GPU (two
+ * streams, or two host threads) race and must be serialised by the caller; calls on one stream are
+ * ordered.  The buffer keeps the last call's contents; every byte a call reads it has written before,
+ * so nothing needs clearing.  The buffer's address is looked up on the first call on a device (or
+ * by quest_init).
+ */
+quest_status quest_lowbit_gemm_static(const uint8_t *a_codes, const float *a_scales, int64_t M,
+                                      const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
+                                      int32_t bits, void *y, int64_t ld_y, int32_t *acc_out, void *stream);
 
 /*
  * The matmul of Algorithm 1 for the FP4 variant (Sec. 4.4), run on the E2M1 codes by the FP4 matrix

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
 EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
-           "quest_lowbit_gemm", "quest_lowbit_gemm_workspace_bytes", "quest_lowbit_gemm_fp4", "quest_trust_backward",
+           "quest_lowbit_gemm", "quest_lowbit_gemm_workspace_bytes", "quest_lowbit_gemm_static", "quest_lowbit_gemm_fp4", "quest_trust_backward",
            "quest_grad_gemm", "quest_grad_gemm_workspace_bytes", "quest_grad_gemm_fp4",
            "quest_grad_gemm_fp4_workspace_bytes", "quest_weight_only_gemm", "quest_weight_only_gemm_workspace_bytes",
            "quest_init", "quest_alpha_star", "quest_container_bits", "quest_status_string")
@@ -49,6 +49,8 @@ def load():
         lib.quest_alpha_star_fp4.argtypes = []
         lib.quest_alpha_star_fp4.restype = _f32
         lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p, _i64, _p]
+        lib.quest_lowbit_gemm_static.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p]
+        lib.quest_lowbit_gemm_static.restype = ctypes.c_int
         lib.quest_lowbit_gemm_workspace_bytes.argtypes = [_i64, _i64, _i64, _i32]
         lib.quest_lowbit_gemm_workspace_bytes.restype = _i64
         lib.quest_lowbit_gemm_fp4.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _p, _i64, _p, _p]
@@ -172,6 +174,17 @@ def quest_lowbit_gemm(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: to
                                     N, K, bits, _ptr(y), ld_y, _ptr(acc_out), _ptr(workspace),
                                     _bytes(workspace), _stream()),
            "quest_lowbit_gemm")
+
+
+def quest_lowbit_gemm_static(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: torch.Tensor,
+                             b_scales: torch.Tensor, K: int, bits: int, *, y: torch.Tensor | None,
+                             acc_out: torch.Tensor | None = None) -> None:
+    """quest_lowbit_gemm with the library's built-in scratch buffer (allocates nothing)."""
+    M, N = a_codes.shape[0], b_codes.shape[0]
+    ld_y = y.stride(0) if y is not None else N
+    _check(load().quest_lowbit_gemm_static(_ptr(a_codes), _ptr(a_scales), M, _ptr(b_codes), _ptr(b_scales),
+                                           N, K, bits, _ptr(y), ld_y, _ptr(acc_out), _stream()),
+           "quest_lowbit_gemm_static")
 
 
 def quest_lowbit_gemm_fp4(a_codes: torch.Tensor, a_scales: torch.Tensor, b_codes: torch.Tensor,

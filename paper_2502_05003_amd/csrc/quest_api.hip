@@ -120,6 +120,41 @@ int device_compute_units()
 
 }  // namespace quest
 
+// Scratch of quest_lowbit_gemm_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address it
+// yields (per device) is what kernels, copies and fills are given.
+static __device__ __align__(256) unsigned char scratch[QUEST_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t static_scratch_address(void **out_ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void *known[kMaxDevices] = {};
+    int device = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess)
+        return err;
+    if (device < 0 || device >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    if (known[device] == nullptr) {
+        void *ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess)
+            return err;
+        if (ptr == nullptr)
+            return hipErrorInvalidSymbol;
+        known[device] = ptr;
+    }
+    *out_ptr = known[device];
+    return hipSuccess;
+}
+
+}  // namespace
+
 extern "C" {
 
 float quest_alpha_star(int32_t bits)
@@ -144,6 +179,7 @@ const char *quest_status_string(quest_status status)
     case QUEST_ERR_DTYPE: return "unknown dtype";
     case QUEST_ERR_LAUNCH: return "the HIP runtime refused the launch";
     case QUEST_ERR_ARG: return "invalid argument";
+    case QUEST_ERR_SCRATCH: return "the call needs more scratch than the library's built-in buffer holds";
     default: return "unknown status";
     }
 }
@@ -298,6 +334,25 @@ quest_status quest_lowbit_gemm(const uint8_t *a_codes, const float *a_scales, in
 {
     return lowbit_gemm_entry(a_codes, a_scales, M, b_codes, b_scales, N, K, bits, y, ld_y, acc_out, workspace,
                              workspace_bytes, stream);
+}
+
+quest_status quest_lowbit_gemm_static(const uint8_t *a_codes, const float *a_scales, int64_t M,
+                                      const uint8_t *b_codes, const float *b_scales, int64_t N, int64_t K,
+                                      int32_t bits, void *y, int64_t ld_y, int32_t *acc_out, void *stream)
+{
+    // same validation as quest_lowbit_gemm, with no workspace; then the size against the built-in buffer
+    const int64_t needed = quest_lowbit_gemm_workspace_bytes(M, N, K, bits);
+    if (needed > QUEST_STATIC_SCRATCH_BYTES)
+        return QUEST_ERR_SCRATCH;
+    void *ptr = nullptr;
+    int64_t bytes = 0;
+    if (needed > 0 && a_codes && a_scales && b_codes && b_scales && (y || acc_out)) {
+        if (static_scratch_address(&ptr) != hipSuccess)
+            return QUEST_ERR_LAUNCH;
+        bytes = QUEST_STATIC_SCRATCH_BYTES;
+    }
+    return lowbit_gemm_entry(a_codes, a_scales, M, b_codes, b_scales, N, K, bits, y, ld_y, acc_out, ptr, bytes,
+                             stream);
 }
 
 quest_status quest_lowbit_gemm_fp4(const uint8_t *a_codes, const float *a_scales, int64_t M,
@@ -482,6 +537,9 @@ quest_status quest_init(void)
         err = quest::prepare_trust_backward_kernels();
     if (err == hipSuccess)
         err = quest::prepare_grad_gemm_kernels();
+    void *ptr = nullptr;
+    if (err == hipSuccess)
+        err = static_scratch_address(&ptr);
     return err == hipSuccess ? QUEST_OK : QUEST_ERR_LAUNCH;
 }
 

@@ -80,6 +80,14 @@ def test_gemm_backward_and_grad_gemm_reject_bad_arguments(lib):
     assert gemm(M=512, N=256, K=1024, bits=2, ld=256, ws=ctypes.c_void_p(0x10008), wsb=1 << 20) == 5
     assert gemm(wsb=-1) == 8
 
+    # the variant with the built-in scratch buffer: same checks, plus its size limit (32 MiB)
+    def static(a=FAKE, sa=FAKE, M=0, b=FAKE, sb=FAKE, N=0, K=512, bits=4, y=FAKE, ld=0, acc=None):
+        return lib.quest_lowbit_gemm_static(a, sa, M, b, sb, N, K, bits, y, ld, acc, None)
+    assert static() == 0 and static(a=None) == 1 and static(bits=7) == 3 and static(K=100) == 2
+    assert static(M=65536, N=8192, K=1024, bits=2, ld=8192) == 9          # (M + N) K / 2 = 36 MiB of scratch
+    assert static(M=65536, N=8192, K=1024, bits=4, ld=8192, a=None) == 1  # 4-bit codes need none: not rejected for it
+    assert "scratch" in q.status_string(9)
+
     def back(g=FAKE, gd=1, mask=FAKE, rows=0, cols=512, n=512, out=FAKE, od=1):
         return lib.quest_trust_backward(g, gd, mask, rows, cols, n, out, od, None)
     assert back() == 0 and back(mask=None) == 0
@@ -140,5 +148,5 @@ def test_variant_entry_points_reject_bad_arguments(lib):
 
 def test_status_strings(lib):
     assert q.status_string(0) == "ok"
-    assert len({q.status_string(s) for s in range(9)}) == 9
+    assert len({q.status_string(s) for s in range(10)}) == 10
     assert "unknown" in q.status_string(99)
