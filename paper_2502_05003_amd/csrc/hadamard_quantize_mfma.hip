@@ -10,8 +10,10 @@
 // four MFMA instructions per row instead of 160 vector instructions.
 //
 // Data flow, one wavefront per row of 128 * U elements:
+//   * bf16 rows of whole 512-element pieces are brought into a per-wave LDS buffer by global -> LDS
+//     transfers, the next row while the current one is worked on (other rows: direct loads);
 //   * the row is cut into tiles of 1024 elements seen as 32 x 32 matrices X[p][q] (element
-//     32 p + q); lane (m = l & 31, h = l >> 5) loads the 32 contiguous bytes of row p = m that
+//     32 p + q); lane (m = l & 31, h = l >> 5) takes the 32 contiguous bytes of row p = m that
 //     hold q = 16 h .. 16 h + 15, which is exactly its share of the MFMA A operand;
 //   * D = X . (I (x) H_min(n,32)) transforms index bits 0..4; lane m then holds column q' = m,
 //     register r holds p = 8 (r >> 2) + 4 h + (r & 3): bits 5, 6 in r & 3, bit 7 in h, bits 8, 9
@@ -39,30 +41,50 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-// Launch shape (overridable at build time for tuning experiments).
-#ifndef QUEST_HQ_MAX_BLOCKS
-#define QUEST_HQ_MAX_BLOCKS 1024
-#endif
-#ifndef QUEST_HQ_WAVES_PER_EU
-#define QUEST_HQ_WAVES_PER_EU 4
-#endif
-#ifndef QUEST_HQ_PREFETCH
-#define QUEST_HQ_PREFETCH 0
-#endif
-#ifndef QUEST_HQ_NONTEMPORAL
-#define QUEST_HQ_NONTEMPORAL 1
-#endif
+// Launch shape: four workgroups of four waves per compute unit (one wave per SIMD and workgroup),
+// each wave walking over its rows.  Two to six workgroups per compute unit time the same.
+constexpr int kBlocksPerCu = 4;
+constexpr int kWavesPerEu = 4;
 
 constexpr int kThreads = 256;
 constexpr int kRowsPerBlock = kThreads / 64;
 
+// Streaming stores: the outputs are not read again by this kernel.  The inline-assembly form is for
+// the code path that counts its own outstanding memory operations (see the row loop).
 __device__ __forceinline__ void store_word(uint32_t *p, uint32_t v)
 {
-#if QUEST_HQ_NONTEMPORAL
     __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
+}
+
+__device__ __forceinline__ void store_word_counted(uint32_t *p, uint32_t v)
+{
+    asm volatile("global_store_dword %0, %1, off nt" : : "v"(p), "v"(v) : "memory");
+}
+
+// 16 bytes per lane from global memory straight into LDS (lane l lands at lds_base + 16 l), streaming
+// (the input is read once).  Source = wave-uniform base + per-lane byte offset.
+__device__ __forceinline__ void lds_dma16_stream(const void *uniform_base, uint32_t lane_offset, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_base)
+                 : "memory");
+}
+
+// wait until at most n (0 .. 24; larger values wait as for 24) vector-memory operations are outstanding
+__device__ __forceinline__ void wait_vmcnt_upto(int n)
+{
+    switch (n) {
+#define QUEST_WAIT_CASE(N) case N: wait_vmcnt<N>(); break;
+    QUEST_WAIT_CASE(0) QUEST_WAIT_CASE(1) QUEST_WAIT_CASE(2) QUEST_WAIT_CASE(3) QUEST_WAIT_CASE(4)
+    QUEST_WAIT_CASE(5) QUEST_WAIT_CASE(6) QUEST_WAIT_CASE(7) QUEST_WAIT_CASE(8) QUEST_WAIT_CASE(9)
+    QUEST_WAIT_CASE(10) QUEST_WAIT_CASE(11) QUEST_WAIT_CASE(12) QUEST_WAIT_CASE(13) QUEST_WAIT_CASE(14)
+    QUEST_WAIT_CASE(15) QUEST_WAIT_CASE(16) QUEST_WAIT_CASE(17) QUEST_WAIT_CASE(18) QUEST_WAIT_CASE(19)
+    QUEST_WAIT_CASE(20) QUEST_WAIT_CASE(21) QUEST_WAIT_CASE(22) QUEST_WAIT_CASE(23)
+#undef QUEST_WAIT_CASE
+    default: wait_vmcnt<24>(); break;
+    }
+    asm volatile("" ::: "memory");   // the compiler keeps later LDS reads behind the wait
 }
 
 template <int XOR>
@@ -146,7 +168,7 @@ struct TransposePlan {
 template <int U, bool HOLD_ALL, bool F32>
 constexpr int hq_waves_per_eu()
 {
-    return (HOLD_ALL && (U > 32 || (F32 && U >= 24))) ? 2 : U > 40 ? 3 : QUEST_HQ_WAVES_PER_EU;
+    return (HOLD_ALL && (U > 32 || (F32 && U >= 24))) ? 2 : U > 40 ? 3 : kWavesPerEu;
 }
 
 template <int U, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4, typename In = uint16_t,
@@ -178,12 +200,43 @@ void hq_mfma_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
 
+    // bf16 rows made of whole 1 KiB pieces (512 elements) land in LDS first: each wave owns one row
+    // buffer, filled by global -> LDS transfers that need no registers while in flight.  The row
+    // after the one being worked on is requested as soon as the current one has been copied to
+    // registers, so its memory latency runs under this row's arithmetic.  Piece i is 16 tile rows of
+    // 64 bytes; lane l of a transfer lands at row l / 4, 16-byte slot l % 4, and fetches the chunk
+    // that belongs there: chunk c of tile row r sits in slot c ^ ((r >> 2) & 3), which makes the
+    // 128-bit operand reads below (sixteen lanes = sixteen consecutive tile rows) conflict-free.
+    constexpr bool kLdsRow = !kF32 && (U % 4) == 0 && U <= 44;
+    constexpr int kPieces = U / 4;
+    extern __shared__ __attribute__((aligned(16))) uint8_t row_buffers[];
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint8_t *my_buffer = row_buffers + wave_u * (256 * U);
+    const uint32_t my_buffer_addr = lds_address(row_buffers) + (uint32_t)wave_u * (256u * U);
+    const uint32_t piece_offset = (uint32_t)(64 * (lane >> 2) + 16 * ((lane & 3) ^ ((lane >> 4) & 3)));
+    auto request_row = [&](int64_t row) {
+        const char *base = reinterpret_cast<const char *>(reinterpret_cast<const uint16_t *>(x) + row * ld);
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i)
+            lds_dma16_stream(base + 1024 * i, piece_offset, my_buffer_addr + 1024 * i);
+    };
+    // the first row is requested before anything else is set up
+    const int64_t row_stride = (int64_t)gridDim.x * kRowsPerBlock;
+    int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave_u;
+    if constexpr (kLdsRow) {
+        if (row < rows)
+            request_row(row);
+    }
+
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
     v8bf bmat[2];
-    hadamard_operand(log2n, m, h, bmat);
+    hadamard_operand<(LOG2N > 5)>(log2n, m, h, bmat);
     // fp32 rows: the middle piece is carried with its sign flipped (see below) and meets -H
+    // bf16 rows of two tiles under one block of 2048: the stage that pairs the tiles is taken into the
+    // matrix instructions' accumulation, tile 0 +- tile 1 (the second tile meets -H for the difference)
+    constexpr bool kFold = !kHoldAll && T == 2 && LOG2N == 11;
     v8bf bneg[2];
-    if constexpr (kF32) {
+    if constexpr (kF32 || kFold) {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             uint32_t w[4];
@@ -224,36 +277,59 @@ void hq_mfma_kernel(
                 raw.a[t][0] = make_uint4(0, 0, 0, 0);
                 raw.a[t][1] = make_uint4(0, 0, 0, 0);
                 if (t < T - 1 || m < kTailRows) {
-#if QUEST_HQ_NONTEMPORAL
                     const v4u n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
                     const v4u n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
                     raw.a[t][0] = make_uint4(n0.x, n0.y, n0.z, n0.w);
                     raw.a[t][1] = make_uint4(n1.x, n1.y, n1.z, n1.w);
-#else
-                    raw.a[t][0] = *reinterpret_cast<const uint4 *>(src + 1024 * t);
-                    raw.a[t][1] = *reinterpret_cast<const uint4 *>(src + 1024 * t + 8);
-#endif
                 }
             }
         }
     };
 
-    const int64_t row_stride = (int64_t)gridDim.x * kRowsPerBlock;
-    int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave;
-#if QUEST_HQ_PREFETCH
-    RawRow next_raw;
-    if (row < rows)
-        load_row(row, next_raw);
-#endif
+    auto read_row = [&](RawRow &raw) {
+        if constexpr (!kF32) {
+            const int slot0 = (2 * h) ^ ((m >> 2) & 3), slot1 = (2 * h + 1) ^ ((m >> 2) & 3);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                raw.a[t][0] = make_uint4(0, 0, 0, 0);
+                raw.a[t][1] = make_uint4(0, 0, 0, 0);
+                if (t < T - 1 || m < kTailRows) {
+                    raw.a[t][0] = *reinterpret_cast<const uint4 *>(my_buffer + 2048 * t + 64 * m + 16 * slot0);
+                    raw.a[t][1] = *reinterpret_cast<const uint4 *>(my_buffer + 2048 * t + 64 * m + 16 * slot1);
+                }
+            }
+        }
+    };
+    // Stores of the LDS path are issued by hand and counted: when the next row's transfers are
+    // awaited, exactly the stores issued after them may still be outstanding (vector-memory
+    // operations of a wave complete in issue order).
+    // (A store is counted whether or not this lane takes part in it: every predicate below holds for
+    // some lane of every wave, so the instruction is always issued, and the count stays wave-uniform.)
+    int stores_issued = 0;
+    auto emit_if = [&](bool mine, uint32_t *p, uint32_t v) {
+        if constexpr (kLdsRow) {
+            if (mine)
+                store_word_counted(p, v);
+            ++stores_issued;
+        } else {
+            if (mine)
+                store_word(p, v);
+        }
+    };
+
+    int stores_after_request = 0;   // stores issued since the transfers of the row about to be read
     for (; row < rows; row += row_stride) {
-#if QUEST_HQ_PREFETCH
-        RawRow raw = next_raw;
-        if (row + row_stride < rows)
-            load_row(row + row_stride, next_raw);
-#else
         RawRow raw;
-        load_row(row, raw);
-#endif
+        if constexpr (kLdsRow) {
+            wait_vmcnt_upto(stores_after_request);   // this row has landed
+            read_row(raw);
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): the buffer has been read, it may be refilled
+            if (row + row_stride < rows)
+                request_row(row + row_stride);
+            stores_issued = 0;
+        } else {
+            load_row(row, raw);
+        }
         // Per-row constants in the un-normalised domain (x_h = raw / sqrt(n)).  The reciprocal and
         // the square root are the hardware approximations (1 ulp): the codes are decided on
         // raw * raw_to_cell, and a relative error of 1e-7 there is the size of one fp32 rounding.
@@ -265,7 +341,7 @@ void hq_mfma_kernel(
                 clip = __fmul_rn(raw_max, inv_sqrt_n);
                 trust_raw = raw_max;
             } else {
-                const float rms = __builtin_amdgcn_sqrtf(wave_sum(sumsq) * (1.0f / (float)cols));
+                const float rms = __builtin_amdgcn_sqrtf(wave_sum_dpp(sumsq) * (1.0f / (float)cols));
                 clip = alpha * rms;
                 trust_raw = trust_edge * rms * sqrt_n;
             }
@@ -274,8 +350,8 @@ void hq_mfma_kernel(
             // raw -> 2^(8-b) * (position in grid cells): the code ends up in the top b bits of a byte
             cell16 = inv_step * inv_sqrt_n * (float)(256 >> BITS);
             to_e2m1 = zero_row ? 0.0f : 6.0f * __builtin_amdgcn_rcpf(clip) * inv_sqrt_n;   // raw -> E2M1 units
-            if (lane == 0)
-                scales[row] = clip * (FP4 ? 1.0f / 6.0f : 1.0f / (float)(kLevels - 1));
+            emit_if(lane == 0, reinterpret_cast<uint32_t *>(scales + row),
+                    __float_as_uint(clip * (FP4 ? 1.0f / 6.0f : 1.0f / (float)(kLevels - 1))));
         };
         float sumsq = 0.0f;
         if constexpr (!kF32) {
@@ -366,6 +442,16 @@ void hq_mfma_kernel(
                         __builtin_memcpy(&p1, &hi[4], 16);
                         z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, bmat[0], z, 0, 0, 0);
                         z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, bmat[1], z, 0, 0, 0);
+                    } else if constexpr (kFold) {
+                        v8bf f0, f1, g0, g1;
+                        __builtin_memcpy(&f0, &raw.a[0][0], 16);
+                        __builtin_memcpy(&f1, &raw.a[0][1], 16);
+                        __builtin_memcpy(&g0, &raw.a[1][0], 16);
+                        __builtin_memcpy(&g1, &raw.a[1][1], 16);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g0, u == 0 ? bmat[0] : bneg[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g1, u == 0 ? bmat[1] : bneg[1], z, 0, 0, 0);
                     } else {
                         v8bf f0, f1;
                         __builtin_memcpy(&f0, &raw.a[t][0], 16);
@@ -383,7 +469,7 @@ void hq_mfma_kernel(
                 }
             }
 
-            tile_stages<LOG2N, G>(acc);
+            tile_stages<LOG2N, G, kFold>(acc);
 
             if constexpr (kHoldAll) {   // the whole row is transformed: now its scale can be fixed
                 float raw_max = 0.0f;
@@ -445,8 +531,8 @@ void hq_mfma_kernel(
                         // after the transpose this lane holds in-lane element 8 dd + lane % 8 of eight
                         // neighbouring lanes; where the row ends inside the dword's range it may not exist
                         const uint32_t word = nibble_plan.apply(packed);
-                        if (8 * dd + 8 <= count_i || 8 * dd + (lane & 7) < count_i)
-                            store_word(code_row + code_word + 64 * (2 * g0 + dd), word);
+                        emit_if(8 * dd + 8 <= count_i || 8 * dd + (lane & 7) < count_i,
+                                code_row + code_word + 64 * (2 * g0 + dd), word);
                     }
                 }
             } else if constexpr (CB == 8) {
@@ -458,7 +544,7 @@ void hq_mfma_kernel(
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
                             packed = __builtin_amdgcn_cvt_pk_u8_f32(__fmaf_rn(elem(4 * w + i), cell16, 127.5f), i, packed);
-                        store_word(code_row + (lane >> 2) + 16 * (lane & 3) + 64 * (4 * g0 + w),
+                        emit_if(true, code_row + (lane >> 2) + 16 * (lane & 3) + 64 * (4 * g0 + w),
                                    byte_plan.apply(packed));
                     }
                 }
@@ -479,8 +565,8 @@ void hq_mfma_kernel(
                             packed |= ((e >> 6) & 0x03030303u) << (2 * k);
                         }
                         packed = pair_plan.apply(packed);
-                        if ((lane & 15) < left)   // a half tile at the end of the row has 8 elements per lane
-                            store_word(code_row + (lane >> 4) + 4 * (lane & 15) + 64 * (g0 + t16), packed);
+                        // a half tile at the end of the row has 8 elements per lane
+                        emit_if((lane & 15) < left, code_row + (lane >> 4) + 4 * (lane & 15) + 64 * (g0 + t16), packed);
                     }
                 }
             } else {
@@ -500,8 +586,7 @@ void hq_mfma_kernel(
                         if (count < 32)
                             code &= (1u << count) - 1u;
                         code = bit_plan.apply(code);
-                        if (m < count)
-                            store_word(code_row + h + 2 * (m + 32 * (g0 / 2 + cc)), code);
+                        emit_if(m < count, code_row + h + 2 * (m + 32 * (g0 / 2 + cc)), code);
                     }
                 }
             }
@@ -527,12 +612,12 @@ void hq_mfma_kernel(
                         if (count < 32)
                             trusted &= (1u << count) - 1u;
                         trusted = bit_plan.apply(trusted);
-                        if (m < count)
-                            store_word(mask_row + h + 2 * (m + 32 * (g0 / 2 + cc)), trusted);
+                        emit_if(m < count, mask_row + h + 2 * (m + 32 * (g0 / 2 + cc)), trusted);
                     }
                 }
             }
         }
+        stores_after_request = stores_issued;
     }
 }
 
@@ -540,17 +625,20 @@ template <int U, int LOG2N, bool FP4 = false, int BITS = 4, typename In = uint16
 void launch(const QuantizeArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
-    const int64_t max_blocks = QUEST_HQ_MAX_BLOCKS;
+    const int64_t max_blocks = 256 * kBlocksPerCu;
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *x = static_cast<const In *>(a.x);
+    // one row buffer per wave for the rows that are staged through LDS (see the kernel), 45 KiB at most
+    constexpr bool kLdsRow = sizeof(In) == 2 && (U % 4) == 0 && U <= 44;
+    constexpr unsigned lds_bytes = kLdsRow ? kRowsPerBlock * 256 * U : 0;
     if (a.mask)
-        hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, true, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
-                           stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
-                           a.xh_out);
+        hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, true, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads),
+                           lds_bytes, stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales,
+                           a.mask, a.xh_out);
     else
-        hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, false, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads), 0,
-                           stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales, a.mask,
-                           a.xh_out);
+        hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, false, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads),
+                           lds_bytes, stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales,
+                           a.mask, a.xh_out);
 }
 
 }  // namespace

@@ -29,8 +29,25 @@ __device__ __forceinline__ void bfly(float &a, float &b)
 
 // B operand of the tile product D = X . (I (x) H_min(n,32)): rows q = 16 h + 8 s + e (s = which of
 // the two 32 x 32 x 16 instructions, e = element) of that matrix, column q' = m, as bf16 +-1 / 0.
+// FULL: the block is at least 32 wide, every entry is +-1: the signs of eight consecutive rows are
+// parity(base & m) ^ parity(e & m), the second factor one of eight byte patterns.
+template <bool FULL>
 __device__ __forceinline__ void hadamard_operand(int log2n, int m, int h, v8bf (&bmat)[2])
 {
+    if constexpr (FULL) {
+        const uint32_t pattern = ((m & 1) ? 0xAAu : 0u) ^ ((m & 2) ? 0xCCu : 0u) ^ ((m & 4) ? 0xF0u : 0u);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int base = 16 * h + 8 * s;
+            const uint32_t minus = (__builtin_popcount(base & m) & 1) ? pattern ^ 0xFFu : pattern;   // bit e: entry is -1
+            uint32_t w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                w[k] = 0x3F803F80u | ((minus << (15 - 2 * k)) & 0x8000u) | ((minus << (30 - 2 * k)) & 0x80000000u);
+            __builtin_memcpy(&bmat[s], w, 16);
+        }
+        return;
+    }
     const int nb = log2n < 5 ? log2n : 5;
     const int low = (1 << nb) - 1;
 #pragma unroll
@@ -65,8 +82,9 @@ __device__ __forceinline__ float sqrt_pow2(int log2n)
 // The stages on index bits 5 .. LOG2N - 1 of G tiles held as MFMA accumulators: bits 5, 6, 8, 9 are
 // register-to-register, bit 7 is the half-wave index and is swapped with register bit 0 first
 // (after which h holds bit 5; the swap is made for every block size so that the element order of
-// the registers does not depend on it), bits >= 10 pair whole tiles.
-template <int LOG2N, int G>
+// the registers does not depend on it), bits >= 10 pair whole tiles.  PAIRED: the stage on bit 10
+// (tile 2 j with tile 2 j + 1) has already been applied by the caller.
+template <int LOG2N, int G, bool PAIRED = false>
 __device__ __forceinline__ void tile_stages(float (&acc)[G][16])
 {
     if (LOG2N > 5) {  // bit 5 = register bit 0
@@ -116,7 +134,7 @@ __device__ __forceinline__ void tile_stages(float (&acc)[G][16])
                 bfly(acc[u][r], acc[u][r + 8]);
     }
 #pragma unroll
-    for (int k = 0; (1 << k) < G; ++k) {  // bits >= 10 pair whole tiles
+    for (int k = PAIRED ? 1 : 0; (1 << k) < G; ++k) {  // bits >= 10 pair whole tiles
         if (LOG2N > 10 + k) {
 #pragma unroll
             for (int u = 0; u < G; ++u)

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace quest {
 
 constexpr int kWave = 64;
@@ -106,6 +108,26 @@ __device__ __forceinline__ float wave_sum(float v)
     for (int off = 32; off > 0; off >>= 1)
         v += __shfl_xor(v, off, kWave);
     return v;
+}
+
+// Same sum through the data-parallel-primitive lane patterns (no LDS crossbar, no address
+// arithmetic): within quads, within rows of sixteen lanes by the two mirror patterns, then across the
+// four rows by the two row broadcasts, after which lane 63 holds the total.  The result is
+// wave-uniform.  The order of the additions differs from wave_sum's.
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    auto moved = [](float x, auto ctrl, auto row_mask) {
+        constexpr int kCtrl = decltype(ctrl)::value, kRows = decltype(row_mask)::value;
+        return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), kCtrl, kRows, 0xF, false));
+    };
+    using std::integral_constant;
+    v += moved(v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});    // quad_perm [1, 0, 3, 2]
+    v += moved(v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});    // quad_perm [2, 3, 0, 1]
+    v += moved(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});   // row_half_mirror
+    v += moved(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});   // row_mirror
+    v += moved(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});   // row_bcast:15 into rows 1, 3
+    v += moved(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});   // row_bcast:31 into rows 2, 3
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), 63));
 }
 
 /*

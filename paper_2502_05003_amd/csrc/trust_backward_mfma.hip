@@ -65,7 +65,7 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
 
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
     v8bf bmat[2];
-    hadamard_operand(log2n, m, h, bmat);
+    hadamard_operand<(LOG2N > 5)>(log2n, m, h, bmat);
     const float inv_sqrt_n = inv_sqrt_pow2(log2n);
     // exchange with lane ^ 1: even lanes keep the low halves, odd lanes the high halves
     const uint32_t pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
