@@ -254,7 +254,9 @@ GEMM_CASES = [(256, 512, 512, 4), (130, 200, 1024, 4), (1, 1, 64, 4), (257, 129,
               (700, 600, 512, 3), (768, 512, 5632, 3), (513, 1025, 1024, 3),
               # b = 1, 2 re-coded to nibbles for the tile kernels (and for the wide one at K = 5632)
               (700, 600, 512, 2), (513, 1025, 1024, 1), (768, 512, 5632, 2), (768, 512, 5632, 1),
-              (4000, 4100, 384, 1), (512, 256, 128, 2)]
+              (4000, 4100, 384, 1), (512, 256, 128, 2),
+              # more 256 x 128 tiles than the chip's workgroup slots, with a remainder and a ragged last tile row
+              (4090, 5000, 256, 4), (4090, 5000, 128, 3)]
 
 
 # every case with caller scratch where the call can use it; the 1- and 2-bit cases that can, also without
