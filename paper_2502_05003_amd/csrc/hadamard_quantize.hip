@@ -10,7 +10,9 @@ namespace {
 
 constexpr int kGenericThreads = 256;
 
-// Per-row constants of the projection, all in fp32 (the precision the codes are decided in).
+// Per-row constants of the projection, all in fp32 (the precision the codes are decided in), every
+// operation correctly rounded (sqrtf and the _rn division are; the _rn square-root intrinsic is the
+// hardware's approximation), so that an fp32 evaluation elsewhere reproduces them bit for bit.
 struct RowQuant {
     float inv_step;   // (L - 1) / (2 alpha rms): x_h * inv_step is the position in grid cells
     float trust_abs;  // trust_edge * rms
@@ -22,7 +24,7 @@ __device__ __forceinline__ RowQuant row_quant(float sumsq, int cols, int levels,
                                               float trust_edge)
 {
     RowQuant q;
-    const float rms = __fsqrt_rn(__fdiv_rn(sumsq, (float)cols));
+    const float rms = sqrtf(__fdiv_rn(sumsq, (float)cols));
     const float clip = __fmul_rn(alpha, rms);
     q.zero = !(rms > 0.0f);
     q.inv_step = q.zero ? 0.0f : __fdiv_rn((float)(levels - 1), __fmul_rn(2.0f, clip));
@@ -48,7 +50,7 @@ __device__ __forceinline__ RowQuant row_quant_absmax(float amax, int levels)
 __device__ __forceinline__ RowQuant row_quant_fp4(float sumsq, int cols, float alpha, float trust_edge)
 {
     RowQuant q;
-    const float rms = __fsqrt_rn(__fdiv_rn(sumsq, (float)cols));
+    const float rms = sqrtf(__fdiv_rn(sumsq, (float)cols));
     const float clip = __fmul_rn(alpha, rms);
     q.zero = !(rms > 0.0f);
     q.inv_step = q.zero ? 0.0f : __fdiv_rn(6.0f, clip);
