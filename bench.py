@@ -7,7 +7,15 @@ A step is one pass of the whole path over one batch of the 1.6B-model MLP up-pro
     two 16-bit gradient GEMMs, two trust-masked inverse transforms.
 Inputs are synthetic, seeded and resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--workload mlp_down_1p6b]
+After the timed region (never inside it) the same run also measures, unless --no-extra:
+  * a plain streaming kernel (what this machine's memory system gives a copy), so that every
+    bandwidth-bound kernel is also reported as a fraction of that;
+  * the forward-only 100M-model layer (X 8192x1024 with outlier channels, Hadamard blocks 128 and
+    1024) and the bit-width sweep b in {1,2,3,4,8} on heavy-tailed activations (quantizer-only
+    bandwidth and trust-mask density), the other two benchmark configurations of this build.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-extra]
+                    [--workload mlp_down_1p6b] [--grid fp4] [--bits b] [--graph] [--only KERNEL]
 """
 from __future__ import annotations
 
@@ -27,27 +35,26 @@ BF16_PEAK_TFLOPS = 2500.0    # dense bf16 MFMA
 FP4_PEAK_TOPS = 10100.0      # dense FP4 MFMA (--grid fp4)
 
 WORKLOAD = "mlp_up_1p6b"     # the headline: X 16384x2048, W 5632x2048, Hadamard block 2048, b = 4
-# down: X 16384x5632, W 2048x5632, block 512; the 7B pair: 4096 -> 11008 (block 4096) and back (block 256)
-WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b", "mlp_up_7b", "mlp_down_7b")
+WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b")   # down: X 16384x5632, W 2048x5632, block 512
 KERNELS = ("quantize_x", "quantize_w", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w",
            "trust_backward_x", "trust_backward_w")
 FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the forward (--only)
 
 
-# HBM-side traffic per launch on this workload, bytes, from rocprofv3 --pmc FETCH_SIZE and
-# --pmc WRITE_SIZE runs of this script (profiles/bench_step_mlp_up_1p6b_hbm_traffic.md): counter
-# value in KiB per dispatch times 1024, FETCH_SIZE also times 2.0 -- the factor by which it
-# under-reads the plain streaming kernel of --copy-calibration (2^30 bytes in, 2^30 out); WRITE_SIZE
-# reads that kernel exactly.  A gradient matmul is the sum over the kernels of its call.
+# HBM-side traffic per launch on the headline workload, MiB read and MiB written, copied from the
+# table in profiles/bench_step_mlp_up_1p6b_hbm_traffic.md (tests/test_repo_contract.py checks that
+# the two agree): rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script, counter value
+# in KiB per dispatch, FETCH_SIZE scaled by the factor by which it under-reads the streaming kernel
+# of known size that the same run launches.  A gradient matmul is the sum over the kernels of its call.
 MIB = 1 << 20
-MEASURED_TRAFFIC = {
-    "quantize_x": (2 * 32.1 + 20.1) * MIB,
-    "quantize_w": (2 * 11.0 + 6.9) * MIB,
-    "lowbit_gemm": (2 * 64.0 + 176.0) * MIB,
-    "grad_gemm_x": (2 * (2.9 + 273.0) + 22.0 + 88.5) * MIB,
-    "grad_gemm_w": (2 * (8.3 + 441.0 + 52.0) + 64.0 + 120.4 + 22.0) * MIB,
-    "trust_backward_x": (2 * 34.1 + 64.0) * MIB,
-    "trust_backward_w": (2 * 11.8 + 22.0) * MIB,
+MEASURED_TRAFFIC_MIB = {
+    "quantize_x": (64.2, 20.1),
+    "quantize_w": (22.0, 6.9),
+    "lowbit_gemm": (128.0, 176.0),
+    "grad_gemm_x": (551.8, 110.5),
+    "grad_gemm_w": (1002.6, 206.4),
+    "trust_backward_x": (68.2, 64.0),
+    "trust_backward_w": (23.6, 22.0),
 }
 
 
@@ -59,6 +66,11 @@ def algorithmic_bytes_quantize(rows, cols, cb=4, in_bytes=2):
 def algorithmic_bytes_backward(rows, cols):
     """bf16 gradient in + bitmap + bf16 out."""
     return rows * cols * 2 + rows * cols // 8 + rows * cols * 2
+
+
+def algorithmic_bytes_gemm(M, N, K, cb=4):
+    """packed codes of both operands + their scales + the bf16 output."""
+    return (M + N) * K * cb // 8 + 4 * (M + N) + 2 * M * N
 
 
 class BufferSet:
@@ -126,121 +138,172 @@ def step_kernels(q, b, cfg, fp4=False):
 
 
 def cpu_baseline(x_bits, w_bits, dy_bits, cfg):
-    """The oracle as it stands, timed on the host cores on a bounded sample of the same step."""
-    import numpy as np
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same step: once
+    on all cores and once, on a smaller sample, on a single thread."""
     from oracle import quest_oracle as qo
 
     M, N, K, n, bits = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"], cfg["bits"]
-    rows_q = M             # rows of X through HT + projection (W is done whole)
-    rows_g = 2048          # rows of X through the forward matmul and the backward pass
-    qo.threads()
-    t0 = time.perf_counter()
-    px = qo.hadamard_quantize(x_bits[:rows_q], n, bits)
-    pw = qo.hadamard_quantize(w_bits, n, bits)
-    ux, uw = qo.unpack_odd(px.codes[:rows_g], K, bits), qo.unpack_odd(pw.codes, K, bits)
-    acc = qo.gemm_odd(ux, uw)
-    qo.dequant(acc, px.scale[:rows_g], pw.scale)
-    dy = qo.widen(dy_bits[:rows_g])
-    gx = qo.grad_input(dy, uw, pw.scale)
-    qo.trust_backward(gx, px.trust[:rows_g], n)
-    gw = qo.grad_weight(dy, ux, px.scale[:rows_g])
-    qo.trust_backward(gw, pw.trust, n)
-    seconds = time.perf_counter() - t0
-    # the three matmuls dominate the step's operation count; the sample ran rows_g of M rows of each
-    ops = 6.0 * rows_g * N * K
-    return {"value": ops / seconds / 1e12, "unit": "TOPS", "cores": qo.threads(), "kind": "oracle",
-            "sample": (f"quantize {rows_q} of {M} X rows and all of W; forward matmul, both gradient "
-                       f"matmuls and both masked inverse transforms on {rows_g} of {M} token rows; "
-                       f"{seconds:.1f} s; value = 6*{rows_g}*N*K ops / time")}
 
-
-def library_gemm_us(torch, dev, M, N, K, reps=20):
-    """The vendor library on the step's three products, with ready-made operands: int8 codes for
-    the forward product (no widening from nibbles), bf16 matrices for the gradient products (no
-    expansion of codes).  Mean microseconds per call, launched back to back."""
-    a8 = torch.randint(-15, 16, (M, K), device=dev, dtype=torch.int8)
-    b8 = torch.randint(-15, 16, (N, K), device=dev, dtype=torch.int8)
-    dy = torch.randn(M, N, device=dev, dtype=torch.bfloat16)
-    w = torch.randn(N, K, device=dev, dtype=torch.bfloat16)
-    x = torch.randn(M, K, device=dev, dtype=torch.bfloat16)
-    cases = {"int8_forward": lambda: torch._int_mm(a8, b8.t()),
-             "bf16_grad_x": lambda: torch.matmul(dy, w),
-             "bf16_grad_w": lambda: torch.matmul(dy.t(), x)}
-    out = {}
-    for name, f in cases.items():
-        for _ in range(5):
-            f()
-        torch.cuda.synchronize()
+    def sample(rows_q, rows_g):
+        """Quantize rows_q rows of X and all of W; the three matmuls and both masked inverse
+        transforms on rows_g token rows.  Returns seconds."""
         t0 = time.perf_counter()
-        for _ in range(reps):
-            f()
-        torch.cuda.synchronize()
-        out[name] = (time.perf_counter() - t0) * 1e6 / reps
-    return out
+        px = qo.hadamard_quantize(x_bits[:rows_q], n, bits)
+        pw = qo.hadamard_quantize(w_bits, n, bits)
+        ux, uw = qo.unpack_odd(px.codes[:rows_g], K, bits), qo.unpack_odd(pw.codes, K, bits)
+        acc = qo.gemm_odd(ux, uw)
+        qo.dequant(acc, px.scale[:rows_g], pw.scale)
+        dy = qo.widen(dy_bits[:rows_g])
+        gx = qo.grad_input(dy, uw, pw.scale)
+        qo.trust_backward(gx, px.trust[:rows_g], n)
+        gw = qo.grad_weight(dy, ux, px.scale[:rows_g])
+        qo.trust_backward(gw, pw.trust, n)
+        return time.perf_counter() - t0
+
+    cores = qo.threads()
+    rows_g = 2048
+    seconds = sample(M, rows_g)
+    # the three matmuls dominate the step's operation count; the sample ran rows_g of M rows of each
+    result = {"value": 6.0 * rows_g * N * K / seconds / 1e12, "unit": "TOPS", "cores": cores, "kind": "oracle",
+              "sample": (f"quantize {M} of {M} X rows and all of W; forward matmul, both gradient "
+                         f"matmuls and both masked inverse transforms on {rows_g} of {M} token rows; "
+                         f"{seconds:.1f} s; value = 6*{rows_g}*N*K ops / time")}
+    rows_one = 128
+    qo.set_threads(1)
+    try:
+        seconds_one = sample(1024, rows_one)
+    finally:
+        qo.set_threads(cores)
+    result["single_thread"] = {"value": 6.0 * rows_one * N * K / seconds_one / 1e12, "unit": "TOPS", "cores": 1,
+                               "sample": (f"quantize 1024 of {M} X rows and all of W; the matmuls and inverse "
+                                          f"transforms on {rows_one} token rows; {seconds_one:.1f} s")}
+    return result
 
 
-# Linear layers of the 1.6B model the paper trained and of the proportionally scaled 7B model its
-# per-layer figure also shows (Sec. 5, "Runtime Results"): name, K (inputs), N (outputs).
-SWEEP_LAYERS = [("1.6B attention 2048->2048", 2048, 2048), ("1.6B up/gate 2048->5632", 2048, 5632),
-                ("1.6B down 5632->2048", 5632, 2048), ("7B attention 4096->4096", 4096, 4096),
-                ("7B up/gate 4096->11008", 4096, 11008), ("7B down 11008->4096", 11008, 4096)]
-
-
-def layer_sweep(torch, q, synth, dev, tokens, reps=10):
-    """Per-layer forward time of the 4-bit path against the 16-bit product (the paper's per-layer
-    speedup figure, Sec. 5): activations quantized per call with and without the Hadamard transform
-    (no mask: inference form), weights quantized beforehand, the vendor library's bf16 product as
-    the baseline.  Microseconds per launch, launched back to back over rotating buffer sets."""
-    # A millisecond of other GPU work goes first, so that the host has queued all timed launches
-    # before the first of them starts: short kernels are then timed back to back on the GPU, not
-    # at the rate the host can issue them.
-    filler = [torch.zeros(8192, 8192, dtype=torch.bfloat16, device=dev) for _ in range(3)]
-    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-
-    def timed(launches):
-        for f in launches:
-            f()
-        torch.cuda.synchronize()
-        torch.matmul(filler[0], filler[1], out=filler[2])
+def time_launches(torch, launches, batch=200, batches=5, warmup=20):
+    """Median over `batches` of the mean time per launch, microseconds: each batch is `batch`
+    launches back to back between one pair of HIP events on the current stream, rotating over
+    `launches` (one thunk per buffer set, so that more than a cache's worth of other data lies
+    between two uses of a buffer)."""
+    import numpy as np
+    for i in range(warmup):
+        launches[i % len(launches)]()
+    torch.cuda.synchronize()
+    samples = []
+    for _ in range(batches):
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         start.record()
-        for i in range(reps):
+        for i in range(batch):
             launches[i % len(launches)]()
         end.record()
         torch.cuda.synchronize()
-        return start.elapsed_time(end) * 1e3 / reps
+        samples.append(start.elapsed_time(end) * 1e3 / batch)
+    return float(np.median(samples))
 
-    out = []
-    for name, K, N in SWEEP_LAYERS:
-        n = K & -K                                  # widest power-of-two block that divides the row
-        n_sets = max(2, min(4, int(1.5e9 // (tokens * (K + N) * 2))))
-        w_bits = synth.gaussian(N, K, 0.02, seed=1)
-        w = torch.from_numpy(w_bits.view("int16")).to(dev).view(torch.bfloat16)
-        w_codes = torch.empty(N, K // 2, dtype=torch.uint8, device=dev)
-        w_scales = torch.empty(N, dtype=torch.float32, device=dev)
-        q.quest_hadamard_quantize(w, n, 4, codes=w_codes, scales=w_scales)
-        x_bits = synth.outlier_activations(tokens, K, 0.005, 50.0, seed=0)
-        xs = [torch.from_numpy(x_bits.view("int16")).to(dev).view(torch.bfloat16) for _ in range(n_sets)]
-        codes = [torch.empty(tokens, K // 2, dtype=torch.uint8, device=dev) for _ in range(n_sets)]
-        scales = [torch.empty(tokens, dtype=torch.float32, device=dev) for _ in range(n_sets)]
-        ys = [torch.empty(tokens, N, dtype=torch.bfloat16, device=dev) for _ in range(n_sets)]
 
-        def quantize(i, block):
-            return lambda: q.quest_hadamard_quantize(xs[i], block, 4, codes=codes[i], scales=scales[i])
+def streaming_rate(torch, dev):
+    """A plain streaming kernel, 2^30 bytes in and 2^30 bytes out per launch (one elementwise kernel
+    of the tensor library): GB/s of read + write.  Also the yardstick for the traffic counters."""
+    src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+    us = time_launches(torch, [lambda: torch.add(src, 1, out=dst)], batch=5, batches=5, warmup=2)
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2.0 * (1 << 30) / (us * 1e-6) / 1e9
 
-        t_q = timed([quantize(i, n) for i in range(n_sets)])
-        t_q_plain = timed([quantize(i, 1) for i in range(n_sets)])
-        for i in range(n_sets):
-            quantize(i, n)()
-        t_gemm = timed([(lambda i=i: q.quest_lowbit_gemm(codes[i], scales[i], w_codes, w_scales, K, 4, y=ys[i]))
-                        for i in range(n_sets)])
-        t_bf16 = timed([(lambda i=i: torch.matmul(xs[i], w.t(), out=ys[i])) for i in range(n_sets)])
-        out.append({"layer": name, "tokens": tokens, "K": K, "N": N, "had_block": n,
-                    "quantize_us": t_q, "quantize_no_transform_us": t_q_plain, "gemm_int4_us": t_gemm,
-                    "matmul_bf16_library_us": t_bf16,
-                    "speedup_with_transform": t_bf16 / (t_q + t_gemm),
-                    "speedup_without_transform": t_bf16 / (t_q_plain + t_gemm)})
-        del xs, codes, scales, ys, w, w_codes, w_scales
-        torch.cuda.empty_cache()
+
+def bf16_tensor(torch, bits, dev):
+    return torch.from_numpy(bits.view("int16")).to(dev).view(torch.bfloat16)
+
+
+def untrusted_fraction(torch, mask):
+    """Share of zero bits in a trust bitmap (elements outside the trust region)."""
+    table = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=mask.device)
+    ones = int(table[mask.reshape(-1).long()].sum().item())
+    return 1.0 - ones / (mask.numel() * 8)
+
+
+def relative_error(torch, q, x, codes, scales, n, bits):
+    """||xhat_h - x_h|| / ||x_h|| of a quantized operand: x_h from the library's own transform output,
+    xhat_h = s (2 c - (L - 1)) decoded from the packed 4-bit codes with tensor-library bit operations."""
+    assert bits == 4
+    rows, cols = x.shape
+    xh = torch.empty(rows, cols, dtype=torch.float32, device=x.device)
+    scratch_c, scratch_s = torch.empty_like(codes), torch.empty_like(scales)
+    q.quest_hadamard_quantize(x, n, bits, codes=scratch_c, scales=scratch_s, xh_out=xh)
+    lo = (codes & 0xF).to(torch.float32)
+    hi = (codes >> 4).to(torch.float32)
+    u = torch.stack((lo, hi), dim=2).reshape(rows, cols) * 2.0 - 15.0
+    xhat = u * scales[:, None]
+    return float(((xhat - xh).double().norm() / xh.double().norm()).item())
+
+
+def extra_config_100m(torch, q, synth, dev, streaming):
+    """Forward only, 100M-model MLP up-projection: quantizer at Hadamard blocks 128 and 1024, GEMM."""
+    x_bits, w_bits, cfg = synth.make_config("mlp_up_100m", seed=0)
+    M, N, K, bits = cfg["M"], cfg["N"], cfg["K"], cfg["bits"]
+    n_sets = 48                                       # 22 MB per set: > 1 GiB between two uses of a set
+    x0, w = bf16_tensor(torch, x_bits, dev), bf16_tensor(torch, w_bits, dev)
+    xs = [x0.clone() for _ in range(n_sets)]
+    codes = [torch.empty(M, K // 2, dtype=torch.uint8, device=dev) for _ in range(n_sets)]
+    scales = [torch.empty(M, dtype=torch.float32, device=dev) for _ in range(n_sets)]
+    masks = [torch.empty(M, K // 8, dtype=torch.uint8, device=dev) for _ in range(n_sets)]
+    w_codes = torch.empty(N, K // 2, dtype=torch.uint8, device=dev)
+    w_scales = torch.empty(N, dtype=torch.float32, device=dev)
+    out = {"workload": f"mlp_up_100m: X {M}x{K} bf16 N(0,1) with 1% of channels x20, W {N}x{K} bf16 N(0,0.02^2), "
+                       f"b={bits}, forward only", "quantize_x": {}}
+    nbytes = algorithmic_bytes_quantize(M, K)
+    for block in (128, 1024):
+        us = time_launches(torch, [(lambda i=i: q.quest_hadamard_quantize(xs[i], block, bits, codes=codes[i],
+                                                                          scales=scales[i], mask=masks[i]))
+                                   for i in range(n_sets)])
+        gbs = nbytes / (us * 1e-6) / 1e9
+        out["quantize_x"][f"block_{block}"] = {
+            "us": us, "GBps": gbs, "frac": gbs / HBM_PEAK_GBS, "frac_of_streaming": gbs / streaming,
+            "algorithmic": nbytes,
+            "relative_error": relative_error(torch, q, xs[0], codes[0], scales[0], block, bits)}
+    q.quest_hadamard_quantize(w, 1024, bits, codes=w_codes, scales=w_scales)
+    for i in range(n_sets):
+        q.quest_hadamard_quantize(xs[i], 1024, bits, codes=codes[i], scales=scales[i])
+    ys = [torch.empty(M, N, dtype=torch.bfloat16, device=dev) for _ in range(12)]   # 64 MiB each
+    us = time_launches(torch, [(lambda i=i: q.quest_lowbit_gemm(codes[i], scales[i], w_codes, w_scales, K, bits,
+                                                                y=ys[i])) for i in range(12)],
+                       batch=100)
+    tops = 2.0 * M * N * K / (us * 1e-6) / 1e12
+    out["lowbit_gemm"] = {"us": us, "TOPS": tops, "frac": tops / INT8_PEAK_TOPS, "ops": 2.0 * M * N * K}
+    return out
+
+
+def extra_config_bit_sweep(torch, q, synth, dev, streaming):
+    """Bit-width sweep on heavy-tailed activations: quantizer-only bandwidth and mask density per b."""
+    x_bits, w_bits, cfg = synth.make_config("bit_sweep_1p6b", seed=0)
+    M, N, K, n = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"]
+    n_sets = 12
+    x0, w0 = bf16_tensor(torch, x_bits, dev), bf16_tensor(torch, w_bits, dev)
+    xs = [x0.clone() for _ in range(n_sets)]
+    ws = [w0.clone() for _ in range(n_sets)]
+    out = {"workload": f"bit_sweep_1p6b: X {M}x{K} bf16 Student-t(nu=3) at unit RMS, W {N}x{K} bf16 N(0,0.02^2), "
+                       f"Hadamard block {n}, quantizer only", "bits": {}}
+    for bits in (1, 2, 3, 4, 8):
+        cb = q.quest_container_bits(bits)
+        entry = {}
+        for name, tensors, rows in (("x", xs, M), ("w", ws, N)):
+            codes = [torch.empty(rows, K * cb // 8, dtype=torch.uint8, device=dev) for _ in range(n_sets)]
+            scales = [torch.empty(rows, dtype=torch.float32, device=dev) for _ in range(n_sets)]
+            masks = [torch.empty(rows, K // 8, dtype=torch.uint8, device=dev) for _ in range(n_sets)]
+            us = time_launches(torch, [(lambda i=i: q.quest_hadamard_quantize(tensors[i], n, bits, codes=codes[i],
+                                                                              scales=scales[i], mask=masks[i]))
+                                       for i in range(n_sets)])
+            nbytes = algorithmic_bytes_quantize(rows, K, cb)
+            gbs = nbytes / (us * 1e-6) / 1e9
+            entry[name] = {"us": us, "GBps": gbs, "frac": gbs / HBM_PEAK_GBS, "frac_of_streaming": gbs / streaming,
+                           "algorithmic": nbytes, "untrusted_fraction": untrusted_fraction(torch, masks[0])}
+            if bits == 1 and name == "x":   # the narrower outer trust region of the 1-bit case (Sec. 3.3)
+                q.quest_hadamard_quantize(tensors[0], n, bits, 0.0, 0.30, codes=codes[0], scales=scales[0],
+                                          mask=masks[0])
+                entry[name]["untrusted_fraction_outer_trust_0.30"] = untrusted_fraction(torch, masks[0])
+            del codes, scales, masks
+        out["bits"][str(bits)] = entry
     return out
 
 
@@ -250,6 +313,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip what is measured after the timed region: the streaming kernel, the 100M-model "
+                         "forward layer and the bit-width sweep")
     ap.add_argument("--workload", choices=WORKLOADS, default=WORKLOAD,
                     help="layer shape; the default is the one the headline metric is quoted on")
     ap.add_argument("--grid", choices=("int4", "fp4"), default="int4",
@@ -261,22 +327,10 @@ def main():
     ap.add_argument("--only", choices=KERNELS + FP4_KERNELS, default=None,
                     help="profiling aid: launch just this kernel --warmup + --steps times back to back "
                          "(outputs of a whole step prepared once) and print its mean time; no benchmark line")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain streaming kernel of known size (reads and writes 1 GiB each), "
-                         "the yardstick for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from HIP graphs (one per buffer set, captured after the timed "
                          "region) and report that step time as ms_per_step_graph: the same kernels without "
                          "event pairs and host launch gaps")
-    ap.add_argument("--library-gemm", action="store_true",
-                    help="also time the vendor library (torch.matmul bf16, torch._int_mm int8) on this "
-                         "workload's three matrix products, operands already in the library's own format: "
-                         "context for the kernels' rooflines, not part of the step")
-    ap.add_argument("--layer-sweep", action="store_true",
-                    help="instead of the benchmark step: forward time of the 4-bit path per linear-layer "
-                         "shape of the 1.6B and 7B models against the library's bf16 product (the paper's "
-                         "per-layer speedup figure); prints one JSON line of its own")
-    ap.add_argument("--tokens", type=int, default=16384, help="rows of the activations in --layer-sweep")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (one MI355X per box); run with --gpus 1")
@@ -293,10 +347,6 @@ def main():
     q.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-
-    if args.layer_sweep:
-        print(json.dumps({"layer_sweep": layer_sweep(torch, q, synth, dev, args.tokens)}))
-        return
 
     x_bits, w_bits, cfg = synth.make_config(args.workload, seed=0)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
@@ -317,7 +367,7 @@ def main():
             for _, launch in step_kernels(q, b, cfg, args.grid == "fp4"):
                 launch()
         if args.only in FP4_KERNELS:
-            n, bits = cfg["had_block"], cfg["bits"]
+            n = cfg["had_block"]
             for b in sets:
                 q.quest_hadamard_quantize_fp4(b.x, n, codes=b.x_codes, scales=b.x_scales, mask=b.x_mask)
                 q.quest_hadamard_quantize_fp4(b.w, n, codes=b.w_codes, scales=b.w_scales, mask=b.w_mask)
@@ -385,36 +435,39 @@ def main():
     gemm_ops = 2.0 * M * N * K
     step_ops = 3.0 * gemm_ops
 
-    def traffic(name):   # measured for the headline workload only
+    streaming = None if args.no_extra else streaming_rate(torch, dev)
+
+    def traffic(name):   # measured for the headline workload only: bytes read + written beyond the L2s
         headline = args.workload == WORKLOAD and args.grid == "int4" and cfg["bits"] == 4
-        return MEASURED_TRAFFIC[name] if headline else None
+        return sum(MEASURED_TRAFFIC_MIB[name]) * MIB if headline else None
 
     def hbm(name, nbytes):
         gbs = nbytes / (ms[name] * 1e-3) / 1e9
         return {"kernel": name, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": gbs / HBM_PEAK_GBS, "traffic": traffic(name), "algorithmic": nbytes,
-                "ms": ms[name]}
+                "frac": gbs / HBM_PEAK_GBS, "frac_of_streaming": gbs / streaming if streaming else None,
+                "traffic": traffic(name), "algorithmic": nbytes, "ms": ms[name]}
 
-    def mfma(name, peak):
+    def mfma(name, peak, nbytes):
         t = gemm_ops / (ms[name] * 1e-3) / 1e12
         return {"kernel": name, "bound": "mfma", "achieved": t, "peak": peak,
-                "unit": "TFLOP/s" if peak == BF16_PEAK_TFLOPS else "TOPS", "frac": t / peak,
-                "traffic": traffic(name), "ms": ms[name]}
+                "unit": "TFLOP/s" if peak == BF16_PEAK_TFLOPS else "TOP/s", "frac": t / peak,
+                "traffic": traffic(name), "algorithmic": nbytes, "ms": ms[name]}
 
+    grad_x_bytes = 2 * M * N + N * K * cb // 8 + 4 * N + 2 * M * K     # dY + weight codes + scales + G_x
+    grad_w_bytes = 2 * M * N + M * K * cb // 8 + 4 * M + 2 * N * K     # dY + activation codes + scales + G_w
     rooflines = {
         "quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K, cb)),
         "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K, cb)),
-        "lowbit_gemm": mfma("lowbit_gemm", FP4_PEAK_TOPS if args.grid == "fp4" else INT8_PEAK_TOPS),
-        "grad_gemm_x": mfma("grad_gemm_x", BF16_PEAK_TFLOPS),
-        "grad_gemm_w": mfma("grad_gemm_w", BF16_PEAK_TFLOPS),
+        "lowbit_gemm": mfma("lowbit_gemm", FP4_PEAK_TOPS if args.grid == "fp4" else INT8_PEAK_TOPS,
+                            algorithmic_bytes_gemm(M, N, K, cb)),
+        "grad_gemm_x": mfma("grad_gemm_x", BF16_PEAK_TFLOPS, grad_x_bytes),
+        "grad_gemm_w": mfma("grad_gemm_w", BF16_PEAK_TFLOPS, grad_w_bytes),
         "trust_backward_x": hbm("trust_backward_x", algorithmic_bytes_backward(M, K)),
         "trust_backward_w": hbm("trust_backward_w", algorithmic_bytes_backward(N, K)),
     }
-    headline = dict(rooflines["lowbit_gemm"])
-    headline["unit"] = "TFLOP/s"   # integer multiply-adds counted as 2 ops each, in units of 1e12/s
 
     result = {
-        "metric": f"W{cfg['bits']}A{cfg['bits']} QuEST-linear TOPS at d={min(K, N) if args.workload.endswith('7b') else 2048} "
+        "metric": f"W{cfg['bits']}A{cfg['bits']} QuEST-linear TOPS at d=2048 "
                   "(forward + backward step; quantizer GB/s in kernels)",
         "value": step_ops / (ms_per_step * 1e-3) / 1e12,
         "unit": "TOPS",
@@ -430,20 +483,12 @@ def main():
         "quantizer_GBps": rooflines["quantize_x"]["achieved"],
         "gemm_TOPS": rooflines["lowbit_gemm"]["achieved"],
         "forward_TOPS": gemm_ops / ((ms["quantize_x"] + ms["quantize_w"] + ms["lowbit_gemm"]) * 1e-3) / 1e12,
-        "roofline": headline,
+        "roofline": dict(rooflines["lowbit_gemm"]),
         "kernels": rooflines,
     }
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
-        dst = torch.empty_like(src)
-        torch.add(src, 1, out=dst)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(3):
-            torch.add(src, 1, out=dst)   # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
-        torch.cuda.synchronize()
+    if streaming:
         # what a plain streaming kernel reaches on this machine, next to the 8 TB/s of the datasheet
-        result["streaming_kernel_GBps"] = 3 * 2.0 * (1 << 30) / (time.perf_counter() - t0) / 1e9
+        result["streaming_kernel_GBps"] = streaming
     if args.graph:
         capture_stream = torch.cuda.Stream()
         graphs = []
@@ -462,8 +507,12 @@ def main():
             graphs[i % n_sets].replay()
         torch.cuda.synchronize()
         result["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / args.steps
-    if args.library_gemm:
-        result["library_gemm_us"] = library_gemm_us(torch, dev, M, N, K)
+    if not args.no_extra:
+        del sets
+        torch.cuda.empty_cache()
+        result["forward_100m"] = extra_config_100m(torch, q, synth, dev, streaming)
+        torch.cuda.empty_cache()
+        result["bit_sweep"] = extra_config_bit_sweep(torch, q, synth, dev, streaming)
     if not args.no_cpu_baseline and args.grid == "int4":   # the oracle leg times the headline (integer-grid) path
         result["cpu_baseline"] = cpu_baseline(x_bits, w_bits, dy_bits, cfg)
     print(json.dumps(result))

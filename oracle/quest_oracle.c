@@ -557,3 +557,13 @@ int qo_threads(void)
 #endif
     return count;
 }
+
+/* Sets how many threads the row loops run on from now on (timing only: results do not depend on it). */
+void qo_set_threads(int count)
+{
+#ifdef _OPENMP
+    omp_set_num_threads(count < 1 ? 1 : count);
+#else
+    (void)count;
+#endif
+}

@@ -74,6 +74,7 @@ def _load():
         lib.qo_weight_only_gemm.argtypes = [_p, _p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_grad_weight.argtypes = [_p, _p, _p, _c_i64, _c_i64, _c_i64, _p]
         lib.qo_threads.restype = _c_int
+        lib.qo_set_threads.argtypes = [_c_int]
         _lib = lib
     return _lib
 
@@ -88,6 +89,11 @@ def _c(a: np.ndarray, dtype) -> np.ndarray:
 
 def threads() -> int:
     return int(_load().qo_threads())
+
+
+def set_threads(count: int) -> None:
+    """Number of threads for the row loops from now on (for timing; results do not depend on it)."""
+    _load().qo_set_threads(int(count))
 
 
 def container_bits(bits: int) -> int:

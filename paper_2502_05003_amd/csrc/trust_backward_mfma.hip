@@ -21,10 +21,7 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-#ifndef QUEST_TB_MAX_BLOCKS
-#define QUEST_TB_MAX_BLOCKS 1024
-#endif
-
+constexpr int kMaxBlocks = 1024;   // four workgroups of four waves per compute unit, each wave walking over its rows
 constexpr int kThreads = 256;
 constexpr int kRowsPerBlock = kThreads / 64;
 
@@ -66,6 +63,21 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
     v8bf bmat[2];
     hadamard_operand<(LOG2N > 5)>(log2n, m, h, bmat);
+    // rows of two tiles under one block of 2048: the stage that pairs the tiles is taken into the
+    // matrix instructions' accumulation
+    constexpr bool kFold = T == 2 && LOG2N == 11;
+    v8bf bneg[2];
+    if constexpr (kFold) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            uint32_t words[4];
+            __builtin_memcpy(words, &bmat[s], 16);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                words[i] ^= 0x80008000u;   // every entry is +-1 here: flip the signs
+            __builtin_memcpy(&bneg[s], words, 16);
+        }
+    }
     const float inv_sqrt_n = inv_sqrt_pow2(log2n);
     // exchange with lane ^ 1: even lanes keep the low halves, odd lanes the high halves
     const uint32_t pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
@@ -78,6 +90,7 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
 #pragma unroll
         for (int g0 = 0; g0 < T; g0 += G) {
             float acc[G][16];
+            v8bf frag[G][2];   // masked inputs of the group's tiles as matrix-instruction operands
 #pragma unroll
             for (int u = 0; u < G; ++u) {
                 const int t = g0 + u;
@@ -95,21 +108,30 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
                     for (int i = 0; i < 8; ++i)
                         w[i] = keep_trusted(w[i], bits, 2 * i);
                 }
-                v8bf f0, f1;
-                __builtin_memcpy(&f0, &w[0], 16);
-                __builtin_memcpy(&f1, &w[4], 16);
+                __builtin_memcpy(&frag[u][0], &w[0], 16);
+                __builtin_memcpy(&frag[u][1], &w[4], 16);
+            }
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
                 v16f z;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     z[r] = 0.0f;
-                z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
-                z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
+                if constexpr (kFold) {   // tile 0 +- tile 1 in the accumulation: the second tile meets -H for the difference
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[0][0], bmat[0], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[0][1], bmat[1], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[1][0], u == 0 ? bmat[0] : bneg[0], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[1][1], u == 0 ? bmat[1] : bneg[1], z, 0, 0, 0);
+                } else {
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[u][0], bmat[0], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[u][1], bmat[1], z, 0, 0, 0);
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     acc[u][r] = z[r];
             }
 
-            tile_stages<LOG2N, G>(acc);
+            tile_stages<LOG2N, G, kFold>(acc);
 
             // element = (lane & 31) + 32 h + 64 iota; this group holds iota = 16 g0 .. as far as the row goes
             constexpr int kGroupI = 16 * G;
@@ -146,7 +168,7 @@ template <int U, int LOG2N, typename Out = uint16_t>
 void launch(const BackwardArgs &a, hipStream_t stream)
 {
     const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
-    const int64_t max_blocks = QUEST_TB_MAX_BLOCKS;
+    const int64_t max_blocks = kMaxBlocks;
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *g = static_cast<const uint16_t *>(a.g);
     auto *out = static_cast<Out *>(a.out);

@@ -356,8 +356,13 @@ FP4_GEMM_CASES = [(256, 512, 512), (130, 200, 1024), (1, 1, 128), (257, 129, 204
                   (768, 512, 5632), (513, 1025, 4096), (1024, 777, 4224)]
 
 
-@pytest.mark.parametrize("M,N,K", FP4_GEMM_CASES)
-def test_fp4_gemm_accumulators_exact_and_output_close(M, N, K):
+# larger outputs with the row pitch equal to N (or a multiple of eight above it): whole tiles, ragged last
+# tile row and column, one contraction step and many
+FP4_GEMM_LARGE = [(4096, 4096, 128, 0), (3600, 3848, 512, 0), (4090, 3080, 1152, 8), (3585, 3592, 2048, 0)]
+
+
+@pytest.mark.parametrize("M,N,K,pad", [(*c, 2) for c in FP4_GEMM_CASES] + FP4_GEMM_LARGE)
+def test_fp4_gemm_accumulators_exact_and_output_close(M, N, K, pad):
     """E2M1 codes on the FP4 matrix instructions (Sec. 4.4): accumulators equal the exact sums."""
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     a_codes = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
@@ -368,7 +373,7 @@ def test_fp4_gemm_accumulators_exact_and_output_close(M, N, K):
         b_codes[1] = 0xFF                   # -6 everywhere
     sa = (rng.random(M) + 0.5).astype(np.float32)
     sb = ((rng.random(N) + 0.5) * 0.01).astype(np.float32)
-    y = torch.full((M, N + 2), 7.0, dtype=torch.bfloat16, device=DEV)   # ld_y > N
+    y = torch.full((M, N + pad), 7.0, dtype=torch.bfloat16, device=DEV)   # ld_y >= N
     acc = torch.empty(M, N, dtype=torch.float32, device=DEV)
     q.quest_lowbit_gemm_fp4(to_device(a_codes), to_device(sa), to_device(b_codes), to_device(sb), K,
                             y=y[:, :N], acc_out=acc)

@@ -37,6 +37,22 @@ def test_algorithmic_bytes_of_the_bandwidth_bound_kernels():
     assert bench.algorithmic_bytes_backward(rows, cols) == rows * (cols * 2 + cols // 8 + cols * 2)
 
 
+def test_traffic_constants_of_the_benchmark_are_those_of_the_committed_profile():
+    """bench.py reports measured HBM-side traffic from constants; they must be the table of the
+    rocprofv3 summary under profiles/, so that a re-measurement updates one place and fails here
+    until the other follows."""
+    import re
+    sys.path.insert(0, ROOT)
+    import bench
+    text = open(os.path.join(ROOT, "profiles", "bench_step_mlp_up_1p6b_hbm_traffic.md")).read()
+    table = {}
+    for key, read, write in re.findall(r"^\| `(\w+)` \| ([0-9.]+) \| ([0-9.]+) \|$", text, flags=re.M):
+        table[key] = (float(read), float(write))
+    assert set(table) == set(bench.MEASURED_TRAFFIC_MIB) == set(bench.KERNELS)
+    for key, pair in bench.MEASURED_TRAFFIC_MIB.items():
+        assert table[key] == pair, key
+
+
 def test_the_product_never_imports_the_oracle_and_the_oracle_never_imports_the_product():
     package = os.path.join(ROOT, "paper_2502_05003_amd")
     for name in os.listdir(package):
