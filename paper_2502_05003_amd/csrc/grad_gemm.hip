@@ -607,6 +607,12 @@ GradGemmPlan plan_grad_gemm(int which, bool fp4, int64_t M, int64_t N, int64_t K
     p.blocks = (tiles + 7) / 8 * 8;
     p.per_block = p.steps;
     p.phase_period = 0;
+    if (!p.split && cus >= 8 && tiles > cus) {
+        // more whole tiles than compute units: one workgroup per unit walks over several tiles, so that
+        // no tile after the first waits for a workgroup to be dispatched (7 us per tile here)
+        p.blocks = cus;
+        p.per_block = (tiles + cus - 1) / cus * p.steps;
+    }
     if (p.split) {
         p.blocks = cus;
         p.per_block = (int)((units + p.blocks - 1) / p.blocks);
