@@ -316,6 +316,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true",
                     help="skip what is measured after the timed region: the streaming kernel, the 100M-model "
                          "forward layer and the bit-width sweep")
+    ap.add_argument("--streaming-only", action="store_true",
+                    help="of the measurements after the timed region keep only the streaming kernel (the "
+                         "yardstick of the rocprofv3 traffic counters)")
     ap.add_argument("--workload", choices=WORKLOADS, default=WORKLOAD,
                     help="layer shape; the default is the one the headline metric is quoted on")
     ap.add_argument("--grid", choices=("int4", "fp4"), default="int4",
@@ -507,7 +510,7 @@ def main():
             graphs[i % n_sets].replay()
         torch.cuda.synchronize()
         result["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / args.steps
-    if not args.no_extra:
+    if not args.no_extra and not args.streaming_only:
         del sets
         torch.cuda.empty_cache()
         result["forward_100m"] = extra_config_100m(torch, q, synth, dev, streaming)

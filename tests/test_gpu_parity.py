@@ -206,8 +206,10 @@ def test_quantizer_and_gemm_100m_layer_full_size(n):
     gx = gpu_quantize(x, n, bits, want_xh=False)
     gw = gpu_quantize(w, n, bits, want_xh=False)
     rx, rw = qo.hadamard_quantize(x, n, bits), qo.hadamard_quantize(w, n, bits)
-    compare_quantizer(gx, rx, K, bits)
-    compare_quantizer(gw, rw, K, bits)
+    counts_x = compare_quantizer(gx, rx, K, bits)
+    counts_w = compare_quantizer(gw, rw, K, bits)
+    print(f"100M layer, block {n}: X {counts_x[0]} codes / {counts_x[1]} mask bits at a boundary out of {x.size}; "
+          f"W {counts_w[0]} / {counts_w[1]} out of {w.size}")
     M, N = x.shape[0], w.shape[0]
     y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
     q.quest_lowbit_gemm(gx["dev"]["codes"], gx["dev"]["scales"], gw["dev"]["codes"], gw["dev"]["scales"],
@@ -233,7 +235,8 @@ def test_bit_sweep_student_t_full_size(bits, outer_trust, alpha_table):
     K, n = cfg["K"], cfg["had_block"]
     got = gpu_quantize(x, n, bits, outer_trust=outer_trust, want_xh=False)
     ref = qo.hadamard_quantize(x, n, bits, outer_trust=outer_trust)
-    compare_quantizer(got, ref, K, bits, outer_trust=outer_trust)
+    n_code, n_mask = compare_quantizer(got, ref, K, bits, outer_trust=outer_trust)
+    print(f"bit sweep b={bits} outer_trust={outer_trust}: {n_code} codes / {n_mask} mask bits at a boundary out of {x.size}")
     untrusted = 1.0 - qo.unpack_mask(got["mask"], K).mean()
     levels = 1 << bits
     edge = alpha_table[bits] * (1.0 + outer_trust / (levels - 1))
@@ -568,7 +571,8 @@ def test_down_projection_full_size():
     gx = gpu_quantize(x, n, bits, want_xh=False)
     gw = gpu_quantize(w, n, bits, want_xh=False)
     ref = qo.hadamard_quantize(x, n, bits)
-    compare_quantizer(gx, ref, K, bits)
+    n_code, n_mask = compare_quantizer(gx, ref, K, bits)
+    print(f"down-projection X: {n_code} codes / {n_mask} mask bits at a boundary out of {x.size}")
     del ref
     y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
     q.quest_lowbit_gemm(gx["dev"]["codes"], gx["dev"]["scales"], gw["dev"]["codes"], gw["dev"]["scales"],
