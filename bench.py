@@ -212,6 +212,41 @@ def streaming_rate(torch, dev):
     return 2.0 * (1 << 30) / (us * 1e-6) / 1e9
 
 
+def mfma_loop_rates(torch, dev, codes, lib_dir):
+    """What the matrix pipes sustain on this machine with nothing else to do: the register-only loop
+    of include/quest_probe.h on operand data shaped like the method's, taken from quantizer output
+    (`codes`: packed 4-bit codes): signed bytes 8 u for the INT8 instruction, bf16 values s u for
+    the bf16 one.  Six launches of a few milliseconds back to back; the chip is power-limited, so
+    the first (best) and the last (sustained) differ.  Returns T(FL)OP/s."""
+    import ctypes
+    lib = ctypes.CDLL(os.path.join(lib_dir, "libquest_probe.so"))
+    lib.quest_probe_mfma_loop.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_void_p]
+    lib.quest_probe_mfma_loop.restype = ctypes.c_int32
+    workgroups, iterations = 512, 12000                      # two waves per SIMD
+    count = workgroups * 256 * 32                            # operand bytes
+    u = (codes.reshape(-1)[:count] & 0xF).to(torch.int16) * 2 - 15          # odd integers of the 4-bit grid
+    operands = {0: (u * 8).to(torch.int8).contiguous(),
+                1: (u[:count // 2].to(torch.float32) * 0.17).to(torch.bfloat16).contiguous()}
+    sink = torch.empty(workgroups * 256, dtype=torch.int32, device=dev)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    out = {}
+    for kind, name, macs in ((0, "int8", 32768.0), (1, "bf16", 16384.0)):
+        ops = 2.0 * workgroups * 4 * iterations * 8 * macs
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(6)]
+        for start, end in pairs:
+            start.record()
+            status = lib.quest_probe_mfma_loop(kind, ctypes.c_void_p(operands[kind].data_ptr()),
+                                               ctypes.c_void_p(sink.data_ptr()), workgroups, iterations, stream)
+            end.record()
+            if status != 0:
+                raise RuntimeError(f"quest_probe_mfma_loop: status {status}")
+        torch.cuda.synchronize()
+        rates = [ops / (a.elapsed_time(b) * 1e-3) / 1e12 for a, b in pairs]
+        out[name] = {"sustained": rates[-1], "best": max(rates)}
+    return out
+
+
 def bf16_tensor(torch, bits, dev):
     return torch.from_numpy(bits.view("int16")).to(dev).view(torch.bfloat16)
 
@@ -511,6 +546,15 @@ def main():
         torch.cuda.synchronize()
         result["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / args.steps
     if not args.no_extra and not args.streaming_only:
+        loop = mfma_loop_rates(torch, dev, sets[0].x_codes, os.path.dirname(q.LIB_PATH))
+        result["mfma_loop"] = {"int8_TOPS": loop["int8"], "bf16_TFLOPS": loop["bf16"],
+                               "what": "register-only matrix-instruction loop on operand data shaped like the "
+                                       "method's, 6 launches back to back: first (best) and last (sustained)"}
+        for name in ("lowbit_gemm", "grad_gemm_x", "grad_gemm_w"):
+            ceiling = loop["bf16" if name.startswith("grad") else "int8"]["sustained"]
+            if not (name == "lowbit_gemm" and args.grid == "fp4"):
+                rooflines[name]["frac_of_mfma_loop"] = rooflines[name]["achieved"] / ceiling
+        result["roofline"] = dict(rooflines["lowbit_gemm"])
         del sets
         torch.cuda.empty_cache()
         result["forward_100m"] = extra_config_100m(torch, q, synth, dev, streaming)

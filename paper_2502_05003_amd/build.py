@@ -7,6 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libquest.so")
+PROBE_LIB = os.path.join(_HERE, "libquest_probe.so")   # measurement aid of bench.py (include/quest_probe.h)
 SOURCES = ["quest_api.hip", "hadamard_quantize.hip", "hadamard_quantize_mfma.hip",
            "lowbit_gemm.hip", "fp4_gemm.hip", "trust_backward.hip", "trust_backward_mfma.hip", "grad_gemm.hip"]
 # per-source extra flags: kernels whose MFMA results are consumed by vector code keep them in VGPRs
@@ -42,6 +43,12 @@ def build_library(verbose: bool = False) -> str:
     tmp = LIB + f".tmp{os.getpid()}"
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objects])
     os.replace(tmp, LIB)
+    tmp = PROBE_LIB + f".tmp{os.getpid()}"
+    out = subprocess.run([hipcc, *HIPCC_FLAGS, "-shared", os.path.join(CSRC, "peak_probe.hip"), "-o", tmp],
+                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    if out.returncode != 0:
+        raise RuntimeError("hipcc failed on peak_probe.hip\n" + out.stdout.decode())
+    os.replace(tmp, PROBE_LIB)
     return LIB
 
 

@@ -146,6 +146,20 @@ def test_variant_entry_points_reject_bad_arguments(lib):
     assert wonly(y=ctypes.c_void_p(0x10002)) == 5
 
 
+def test_probe_library_exports_what_its_header_declares(lib):
+    """The benchmark's measurement aid (include/quest_probe.h) is a library of its own."""
+    from paper_2502_05003_amd import build
+    header = open(os.path.join(ROOT, "include", "quest_probe.h")).read()
+    declared = set(re.findall(r"\b(quest_[a-z_0-9]+)\s*\(", header))
+    assert declared == {"quest_probe_mfma_loop"}
+    probe = ctypes.CDLL(build.PROBE_LIB)
+    probe.quest_probe_mfma_loop.restype = ctypes.c_int32
+    probe.quest_probe_mfma_loop.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                            ctypes.c_int32, ctypes.c_void_p]
+    assert probe.quest_probe_mfma_loop(0, None, FAKE, 1, 1, None) == 1          # validation before any launch
+    assert probe.quest_probe_mfma_loop(2, FAKE, FAKE, 1, 1, None) == 1 and probe.quest_probe_mfma_loop(0, FAKE, FAKE, 0, 1, None) == 1
+
+
 def test_status_strings(lib):
     assert q.status_string(0) == "ok"
     assert len({q.status_string(s) for s in range(10)}) == 10
