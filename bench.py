@@ -15,7 +15,8 @@ After the timed region (never inside it) the same run also measures, unless --no
     bandwidth and trust-mask density), the other two benchmark configurations of this build.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-extra]
-                    [--workload mlp_down_1p6b] [--grid fp4] [--bits b] [--graph] [--only KERNEL]
+                    [--workload mlp_down_1p6b] [--grid fp4] [--bits b] [--graph] [--library-gemm]
+                    [--only KERNEL]
 """
 from __future__ import annotations
 
@@ -178,6 +179,32 @@ def cpu_baseline(x_bits, w_bits, dy_bits, cfg):
                                "sample": (f"quantize 1024 of {M} X rows and all of W; the matmuls and inverse "
                                           f"transforms on {rows_one} token rows; {seconds_one:.1f} s")}
     return result
+
+
+def library_gemm_us(torch, dev, M, N, K, reps=20):
+    """Context for the matmul rooflines, not part of the step: the vendor library on the step's three
+    products with operands already in its own format: int8 matrices for the forward product (no
+    widening from nibbles), bf16 matrices for the gradient products (no expansion of codes).  Mean
+    microseconds per call, launched back to back."""
+    a8 = torch.randint(-15, 16, (M, K), device=dev, dtype=torch.int8)
+    b8 = torch.randint(-15, 16, (N, K), device=dev, dtype=torch.int8)
+    dy = torch.randn(M, N, device=dev, dtype=torch.bfloat16)
+    w = torch.randn(N, K, device=dev, dtype=torch.bfloat16)
+    x = torch.randn(M, K, device=dev, dtype=torch.bfloat16)
+    cases = {"int8_forward": lambda: torch._int_mm(a8, b8.t()),
+             "bf16_grad_x": lambda: torch.matmul(dy, w),
+             "bf16_grad_w": lambda: torch.matmul(dy.t(), x)}
+    out = {}
+    for name, f in cases.items():
+        for _ in range(5):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            f()
+        torch.cuda.synchronize()
+        out[name] = (time.perf_counter() - t0) * 1e6 / reps
+    return out
 
 
 def time_launches(torch, launches, batch=200, batches=5, warmup=20):
@@ -365,6 +392,10 @@ def main():
     ap.add_argument("--only", choices=KERNELS + FP4_KERNELS, default=None,
                     help="profiling aid: launch just this kernel --warmup + --steps times back to back "
                          "(outputs of a whole step prepared once) and print its mean time; no benchmark line")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the vendor library (torch.matmul bf16, torch._int_mm int8) on this "
+                         "workload's three matrix products, operands already in the library's own format: "
+                         "context for the kernels' rooflines, not part of the step")
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from HIP graphs (one per buffer set, captured after the timed "
                          "region) and report that step time as ms_per_step_graph: the same kernels without "
@@ -545,6 +576,8 @@ def main():
             graphs[i % n_sets].replay()
         torch.cuda.synchronize()
         result["ms_per_step_graph"] = (time.perf_counter() - t0) * 1e3 / args.steps
+    if args.library_gemm:
+        result["library_gemm_us"] = library_gemm_us(torch, dev, M, N, K)
     if not args.no_extra and not args.streaming_only:
         loop = mfma_loop_rates(torch, dev, sets[0].x_codes, os.path.dirname(q.LIB_PATH))
         result["mfma_loop"] = {"int8_TOPS": loop["int8"], "bf16_TFLOPS": loop["bf16"],

@@ -240,9 +240,7 @@ __device__ __forceinline__ void tile_origin(int tile, int tiles_r, int tiles_k, 
  * R and K need not be whole tiles: the transfers of an edge tile fetch the last rows or columns
  * that exist in place of those that do not (results of those positions are never stored).
  */
-#ifndef QUEST_GG_SPREAD_MODES
-#define QUEST_GG_SPREAD_MODES 5   // bit m: MODE m spreads its transfers over the whole step
-#endif
+constexpr int kSpreadModes = 5;   // bit m: MODE m spreads its transfers over the whole step (measured, see below)
 
 template <int MODE, int STAGES>
 __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
@@ -398,7 +396,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     //          through the step, at the price of one step less of look-ahead.
     // Spreading is 1-3 % faster when the left operand is in row form (G_x: 320 instead of 328 us on
     // one box, 334 instead of 338 on another) and 0-1 % slower when both operands are in column form.
-    constexpr bool kSpread = QUEST_GG_SPREAD_MODES & (1 << MODE);
+    constexpr bool kSpread = kSpreadModes & (1 << MODE);
     constexpr int kAhead = kSpread ? STAGES - 2 : STAGES - 1;   // steps in flight beyond the current one
     static_for<kAhead>([&](auto sc) {
         static_for<8>([&](auto pc) {
