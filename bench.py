@@ -49,13 +49,13 @@ FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the f
 # of known size that the same run launches.  A gradient matmul is the sum over the kernels of its call.
 MIB = 1 << 20
 MEASURED_TRAFFIC_MIB = {
-    "quantize_x": (64.2, 20.1),
-    "quantize_w": (22.0, 6.9),
-    "lowbit_gemm": (128.0, 176.0),
-    "grad_gemm_x": (551.8, 110.5),
-    "grad_gemm_w": (1002.6, 206.4),
-    "trust_backward_x": (68.2, 64.0),
-    "trust_backward_w": (23.6, 22.0),
+    "quantize_x": (64.1, 20.3),
+    "quantize_w": (22.1, 7.0),
+    "lowbit_gemm": (127.2, 176.0),
+    "grad_gemm_x": (555.5, 102.8),
+    "grad_gemm_w": (1005.7, 205.7),
+    "trust_backward_x": (68.4, 64.0),
+    "trust_backward_w": (23.5, 22.0),
 }
 
 
