@@ -186,8 +186,6 @@ constexpr int kTileThreads = 256;
 constexpr int kRowBytes = TK / 2;                      // packed bytes per tile row and step
 constexpr int kStageBytes = (TM + TN) * kRowBytes;     // 24 KiB
 constexpr int kStages = 3;
-constexpr int kParkBytes = 4 * 128 * 64 * 2;           // epilogue: four waves x 128 x 64 bf16 (reuses the stages)
-static_assert(kParkBytes <= kStages * kStageBytes, "the epilogue parks in the stages");
 constexpr int kTileLds = kStages * kStageBytes + TN * 4;   // 72 KiB + the tile's weight scales
 
 // 16-byte chunk c (0..3) of tile row `row` lives at chunk c ^ swz(row).  The LDS serves 128-bit
@@ -212,6 +210,87 @@ __device__ __forceinline__ void widen8(uint32_t w, uint32_t field_mask, int &eve
     constexpr uint32_t forced = BITS == 4 ? 0x88888888u : 0x90909090u;
     odd = (int)__builtin_amdgcn_bitop3_b32(w << (4 - BITS), field_mask, forced, 0x6A);
     even = (int)__builtin_amdgcn_bitop3_b32(w << (8 - BITS), field_mask, forced, 0x6A);
+}
+
+// Epilogue of the 256 x 128 tile kernel: the wave's 128 x 64 block at (row0, col0) goes from its
+// transposed accumulator tiles (lane l holds output row l % 32 and runs of four consecutive columns)
+// to memory without a detour through LDS: a lane pair (l, l + 32) exchanges half of its packed
+// results, after which every lane holds sixteen consecutive columns of its row and writes them as
+// two 16-byte pieces.  sa_reg holds s_a / 2^CARRY of the lane's four rows.
+template <int CARRY>
+__device__ __forceinline__ void store_wave_block_direct(const v16i (&acc)[4][2], const float (&sa_reg)[4],
+                                                        const float *sb_lds_wave, int row0, int col0, int M,
+                                                        int N, uint16_t *__restrict__ y, int64_t ld_y,
+                                                        int32_t *__restrict__ acc_out, int lane)
+{
+    const int lm = lane & 31, lh = lane >> 5;
+    if (acc_out) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = row0 + i * 32 + lm;
+                    const int n = col0 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    if (m < M && n < N)
+                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> CARRY;   // exact: a multiple of 2^CARRY
+                }
+    }
+    if (!y)
+        return;
+    float4 sb_reg[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            sb_reg[j][q] = *reinterpret_cast<const float4 *>(sb_lds_wave + j * 32 + 8 * q + 4 * lh);
+    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) && (col0 + 64 <= N);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = row0 + i * 32 + lm;
+        const float sa = sa_reg[i];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            uint32_t d[4][2];   // quad q: columns 8 q + 4 lh .. + 4 of the 32-column tile
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 sb = sb_reg[j][q];
+                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
+                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
+                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
+                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
+                d[q][0] = pack_bf16(v0, v1);
+                d[q][1] = pack_bf16(v2, v3);
+            }
+            if (vector_ok) {
+                // lanes l and l + 32 hold interleaved runs of four columns of the same row; after the
+                // exchange lane (lm, lh) holds columns 16 lh .. + 16 in the order d[0], d[2], d[1], d[3]
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(d[q][e], d[q + 2][e], false, false);
+                        d[q][e] = sw[0];
+                        d[q + 2][e] = sw[1];
+                    }
+                if (row < M) {
+                    uint16_t *dst = y + (int64_t)row * ld_y + col0 + j * 32 + 16 * lh;
+                    *reinterpret_cast<uint4 *>(dst) = make_uint4(d[0][0], d[0][1], d[2][0], d[2][1]);
+                    *reinterpret_cast<uint4 *>(dst + 8) = make_uint4(d[1][0], d[1][1], d[3][0], d[3][1]);
+                }
+            } else if (row < M) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int n = col0 + j * 32 + 8 * q + 4 * lh + e;
+                        if (n < N)
+                            y[(int64_t)row * ld_y + n] = (uint16_t)(d[q][e >> 1] >> (16 * (e & 1)));
+                    }
+            }
+        }
+    }
 }
 
 template <int BITS>
@@ -276,7 +355,7 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     const uint32_t smem_addr = lds_address(smem);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #define QUEST_DMA(STAGE, I, STEP)                                                                  \
-    lds_dma16(((I) < 4 ? a_codes : b_codes) + src_off[I] + (int64_t)min((STEP), steps - 1) * kRowBytes, \
+    lds_dma16(((I) < 4 ? a_codes : b_codes) + (int64_t)min((STEP), steps - 1) * kRowBytes, src_off[I],  \
               (STAGE) + ((I) < 4 ? 0 : TM * kRowBytes) +                                           \
                   (64 * ((I) < 4 ? (I) : (I)-4) + 16 * wave_u) * kRowBytes)
 
@@ -310,10 +389,10 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     };
     static_for<6>([&](auto f) { load_frag(smem, 0, decltype(f)::value); });
 
-    // Widened operands of the sub-step being multiplied: both B fragments, and two A fragments
-    // (A fragment i sits in wa[i % 2] while its two instructions run).  Sub-step g = 2 p + e takes
-    // words (x, y) (e = 0) or (z, w) (e = 1) of the packed fragments of pair p.
-    v4i wa[2], wb[2];
+    // Widened operands.  A fragment i sits in wa[i % 2] while its two instructions run; the B
+    // fragments of sub-step g sit in wb[g % 2][j].  Sub-step g = 2 p + e takes words (x, y) (e = 0)
+    // or (z, w) (e = 1) of the packed fragments of pair p.
+    v4i wa[2], wb[2][2];
     auto widen_a = [&](auto gc, auto ic) {
         constexpr int g = decltype(gc)::value & 3, i = decltype(ic)::value;
         constexpr int p = g >> 1, e = g & 1;
@@ -328,21 +407,25 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
         int w0, w1, w2, w3;
         widen8<BITS>(e ? bf[p][j].z : bf[p][j].x, nibble_mask, w0, w1);
         widen8<BITS>(e ? bf[p][j].w : bf[p][j].y, nibble_mask, w2, w3);
-        wb[j] = v4i{w0, w1, w2, w3};
+        wb[g & 1][j] = v4i{w0, w1, w2, w3};
     };
     widen_a(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     widen_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    widen_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
 
     // Main loop: 32 MFMAs per step and wave, everything else pinned between them, at most one
-    // widening (six vector ops) per MFMA so that the vector unit never has a burst to work off.
+    // widening (six vector ops) per MFMA so that the vector unit never has a burst to work off, and
+    // every widening at least one MFMA ahead of the first instruction that reads its result (a
+    // matrix instruction directly behind the vector op that writes its operand waits).
     //   MFMA k: sub-step g = k / 8, within it s = k % 8 multiplies A fragment s / 2 with B fragment s % 2
-    //   s = 0: widen B1   s = 1, 3, 5: widen A1, A2, A3   s = 6, 7: widen B0, A0 of the next sub-step
+    //   after s = 0, 2, 4: widen A1, A2, A3    after s = 5, 6, 7: widen B0, A0, B1 of the next sub-step
     //   k = 0, 3, .. 15  start the transfers of step + 2 into the stage that was read in step - 1
     //               (spread out: a transfer that finds the memory queue full holds up the MFMAs)
-    //   k = 2..7    load the packed fragments of pair 1 (first needed after k = 14)
-    //   k = 20      wait for this wave's transfers of step + 1 (issued one step ago: all but the six
+    //   k = 2..7    load the packed fragments of pair 1 (first needed after k = 13)
+    //   k = 16      wait for this wave's transfers of step + 1 (issued one step ago: all but the six
     //               newest), then the workgroup barrier: step + 1 is complete in LDS
-    //   k = 21..26  load the packed fragments of pair 0 of step + 1 (first needed after k = 30)
+    //   k = 17..22  load the packed fragments of pair 0 of step + 1 in the order of their first use
+    //               (B0, A0, B1 are widened after k = 29, 30, 31)
     // Three stages: a transfer has almost two steps to land, and no wave waits on the barrier with
     // an empty MFMA queue.
     int stage_cur = 0;   // byte offsets of the stages holding step, step + 1, step + 2
@@ -354,25 +437,27 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
             constexpr int k = decltype(kc)::value;
             constexpr int g = k >> 3, s = k & 7, i = s >> 1, j = s & 1;
             // weight fragment as the row operand: transposed accumulator tiles
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[j], wa[i & 1], acc[i][j], 0, 0, 0);
-            if constexpr (s == 0)
-                widen_b(std::integral_constant<int, g>{}, std::integral_constant<int, 1>{});
-            if constexpr (s == 1 || s == 3 || s == 5)
-                widen_a(std::integral_constant<int, g>{}, std::integral_constant<int, (s + 1) / 2>{});
-            if constexpr (s == 6)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[g & 1][j], wa[i & 1], acc[i][j], 0, 0, 0);
+            if constexpr (s == 0 || s == 2 || s == 4)
+                widen_a(std::integral_constant<int, g>{}, std::integral_constant<int, s / 2 + 1>{});
+            if constexpr (s == 5)
                 widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
-            if constexpr (s == 7)
+            if constexpr (s == 6)
                 widen_a(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
+            if constexpr (s == 7)
+                widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 1>{});
             if constexpr (k < 18 && k % 3 == 0)
                 QUEST_DMA(smem_addr + stage_two, k / 3, step + 2);
             if constexpr (k >= 2 && k < 8)
                 load_frag(cur, 1, k - 2);
-            if constexpr (k == 20) {
+            if constexpr (k == 16) {
                 wait_vmcnt<6>();
                 __builtin_amdgcn_s_barrier();
             }
-            if constexpr (k >= 21 && k < 27)
-                load_frag(one, 0, k - 21);
+            if constexpr (k >= 17 && k < 23) {
+                constexpr int order[6] = {4, 0, 5, 1, 2, 3};   // B0, A0, B1, A1, A2, A3
+                load_frag(one, 0, order[k - 17]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
         const int t = stage_cur;
@@ -383,10 +468,9 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     wait_vmcnt<0>();   // all transfers landed before the stages are reused
 #undef QUEST_DMA
 
-    // Epilogue: each wave's 128 x 64 block (see store_wave_block), parked in the stages.
-    __syncthreads();   // every wave is done with the stages
-    store_wave_block<4, kCarry>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (128 * 128), m0 + wm * 128,
-                                n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
+    // Epilogue: each wave's 128 x 64 block, straight from registers.
+    store_wave_block_direct<kCarry>(acc, sa_reg, scale_lds + wn * 64, m0 + wm * 128, n0 + wn * 64, M, N, y, ld_y,
+                                    acc_out, lane);
 }
 
 // ------------------------------------------------------------------------------------------
