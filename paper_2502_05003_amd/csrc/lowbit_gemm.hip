@@ -736,7 +736,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     const uint32_t smem_addr = lds_address(smem);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #define QUEST_WIDE_DMA(STAGE, I, STEP)                                                                  \
-    lds_dma16(((I) < 4 ? a_codes : b_codes) + src_off[I] + (int64_t)min((STEP), steps - 1) * kWideRowBytes, \
+    lds_dma16(((I) < 4 ? a_codes : b_codes) + (int64_t)min((STEP), steps - 1) * kWideRowBytes, src_off[I], \
               (STAGE) + ((I) < 4 ? 0 : WTM * kWideRowBytes) + (64 * ((I)&3) + 8 * wave_u) * kWideRowBytes)
 
     static_for<8>([&](auto i) { QUEST_WIDE_DMA(smem_addr, decltype(i)::value, 0); });
@@ -766,58 +766,76 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     };
     static_for<6>([&](auto f) { load_frag(smem, 0, decltype(f)::value); });
 
-    // Main loop: 64 MFMAs per step and wave, everything else pinned between them.
-    //   MFMA k: pair p = k / 16, half e = (k / 8) % 2, A tile i = (k / 2) % 4, B tile j = k % 2
+    // Widened operands, as in the 256 x 128 kernel: A fragment i in wa[i % 2], the B fragments of
+    // sub-step g in wb[g % 2][j]; sub-step g (eight per step) takes words (x, y) (g even) or (z, w)
+    // (g odd) of the packed fragments of pair g / 2, which sit in af / bf [(g / 2) % 2].
+    v4i wa[2], wb[2][2];
+    auto widen_a = [&](auto gc, auto ic) {
+        constexpr int g = decltype(gc)::value & 7, i = decltype(ic)::value;
+        constexpr int q = (g >> 1) & 1, e = g & 1;
+        int w0, w1, w2, w3;
+        widen8<BITS>(e ? af[q][i].z : af[q][i].x, nibble_mask, w0, w1);
+        widen8<BITS>(e ? af[q][i].w : af[q][i].y, nibble_mask, w2, w3);
+        wa[i & 1] = v4i{w0, w1, w2, w3};
+    };
+    auto widen_b = [&](auto gc, auto jc) {
+        constexpr int g = decltype(gc)::value & 7, j = decltype(jc)::value;
+        constexpr int q = (g >> 1) & 1, e = g & 1;
+        int w0, w1, w2, w3;
+        widen8<BITS>(e ? bf[q][j].z : bf[q][j].x, nibble_mask, w0, w1);
+        widen8<BITS>(e ? bf[q][j].w : bf[q][j].y, nibble_mask, w2, w3);
+        wb[g & 1][j] = v4i{w0, w1, w2, w3};
+    };
+    widen_a(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    widen_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    widen_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+
+    // Main loop: 64 MFMAs per step and wave, everything else pinned between them, every widening
+    // at least one MFMA ahead of the first instruction that reads its result.
+    //   MFMA k: sub-step g = k / 8, within it s = k % 8 multiplies A fragment s / 2 with B fragment s % 2
+    //   after s = 0, 2, 4: widen A1, A2, A3    after s = 5, 6, 7: widen B0, A0, B1 of the next sub-step
     //   k = 0..7         start the transfer of step + 1 into the other stage (last read in step - 1)
-    //   k = 16 p + 0..5  load the fragments of pair p + 1 (p < 3)
+    //   k = 16 p + 0..5  load the fragments of pair p + 1 (p < 3; first needed after k = 16 p + 13)
     //   k = 47           wait for this wave's transfers, then the workgroup barrier: step + 1 is in LDS
-    //   k = 48..53       load the fragments of pair 0 of step + 1
+    //   k = 48..53       load the fragments of pair 0 of step + 1 in the order of their first use
     // The barrier sits before the last pair, so no wave waits on it with an empty MFMA queue.
     for (int step = 0; step < steps; ++step) {
         const uint8_t *cur = smem + (step & 1) * kWideStageBytes;
         const uint8_t *nxt = smem + ((step + 1) & 1) * kWideStageBytes;
         const uint32_t nxt_addr = smem_addr + ((step + 1) & 1) * kWideStageBytes;
-        v4i bw[2];
         static_for<64>([&](auto kc) {
             constexpr int k = decltype(kc)::value;
-            constexpr int p = k >> 4, e = (k >> 3) & 1, i = (k >> 1) & 3, j = k & 1;
-            if constexpr ((k & 7) == 0) {   // widen the two B fragments of this half
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    int w0, w1, w2, w3;
-                    widen8<BITS>(e ? bf[p & 1][jj].z : bf[p & 1][jj].x, nibble_mask, w0, w1);
-                    widen8<BITS>(e ? bf[p & 1][jj].w : bf[p & 1][jj].y, nibble_mask, w2, w3);
-                    bw[jj] = v4i{w0, w1, w2, w3};
-                }
-            }
-            v4i aw;
-            {
-                int w0, w1, w2, w3;
-                widen8<BITS>(e ? af[p & 1][i].z : af[p & 1][i].x, nibble_mask, w0, w1);
-                widen8<BITS>(e ? af[p & 1][i].w : af[p & 1][i].y, nibble_mask, w2, w3);
-                aw = v4i{w0, w1, w2, w3};
-            }
+            constexpr int g = k >> 3, s = k & 7, i = s >> 1, j = s & 1;
             // weight fragment as the row operand: transposed accumulator tiles
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bw[j], aw, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[g & 1][j], wa[i & 1], acc[i][j], 0, 0, 0);
+            if constexpr (s == 0 || s == 2 || s == 4)
+                widen_a(std::integral_constant<int, g>{}, std::integral_constant<int, s / 2 + 1>{});
+            if constexpr (s == 5)
+                widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
+            if constexpr (s == 6)
+                widen_a(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 0>{});
+            if constexpr (s == 7)
+                widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 1>{});
             if constexpr (k < 8)
                 QUEST_WIDE_DMA(nxt_addr, k, step + 1);
-            if constexpr (p < 3 && (k & 15) < 6)
-                load_frag(cur, p + 1, k & 15);
+            if constexpr (k < 48 && (k & 15) < 6)
+                load_frag(cur, (k >> 4) + 1, k & 15);
             if constexpr (k == 47) {
                 wait_vmcnt<0>();
                 __builtin_amdgcn_s_barrier();
             }
-            if constexpr (k >= 48 && k < 54)
-                load_frag(nxt, 0, k - 48);
+            if constexpr (k >= 48 && k < 54) {
+                constexpr int order[6] = {4, 0, 5, 1, 2, 3};   // B0, A0, B1, A1, A2, A3
+                load_frag(nxt, 0, order[k - 48]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
     }
 #undef QUEST_WIDE_DMA
 
-    // Epilogue: each wave's 128 x 64 block (see store_wave_block), parked in the stages.
-    __syncthreads();   // every wave is done with the stages
-    store_wave_block<4, kCarry>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (128 * 128), m0 + wm * 128,
-                                n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
+    // Epilogue: each wave's 128 x 64 block, straight from registers.
+    store_wave_block_direct<kCarry>(acc, sa_reg, scale_lds + wn * 64, m0 + wm * 128, n0 + wn * 64, M, N, y, ld_y,
+                                    acc_out, lane);
 }
 
 // ------------------------------------------------------------------------------------------
