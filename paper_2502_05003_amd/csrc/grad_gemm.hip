@@ -358,6 +358,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
                       stage + kOperandBytes + (4 * (p - 4) + wave_u) * 1024);
     };
 
+    // the same from operand positions that the caller keeps up to date
+    // (`wave_stage`: LDS byte address of the stage plus 1024 * wave)
+    auto transfer_from = [&](auto pc, uint32_t wave_stage, const char *left_at, const char *right_at) {
+        constexpr int p = decltype(pc)::value;
+        if constexpr (p < 4)
+            lds_dma16_at<4096 * p>(left_at, left_voff[p], wave_stage);
+        else
+            lds_dma16_at<kOperandBytes + 4096 * (p - 4)>(right_at, right_voff[p - 4], wave_stage);
+    };
+
     // fragments as halves of four contraction elements: [k-step][fragment][half]
     v4bf lf[2][4][2], rf[2][4][2];
     // read number n of k-step ks out of `stage`, in the order the matrix instructions want them
@@ -407,13 +417,20 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
     __builtin_amdgcn_s_barrier();
     static_for<kReads>([&](auto nc) { load_frag(nc, smem, std::integral_constant<int, 0>{}); });
 
-    int cur = 0;   // stage of the current step
+    // Scalar bookkeeping of a step is kept to additions and selects (one wave per SIMD: a chain of
+    // dependent scalar instructions between two matrix instructions is time the matrix pipe idles):
+    // byte offsets of the current stage and of the stage being refilled, and the operands' positions
+    // at the step being fetched, min(step + kAhead, s_end - 1).
+    constexpr int kRing = STAGES * kGStage;
+    int cur_off = 0;
+    int refill_off = (kSpread ? kAhead : STAGES - 1) * kGStage;
+    const char *left_fetch = left_base + (int64_t)min(s_begin + kAhead, s_end - 1) * left_step;
+    const char *right_fetch = right_base + (int64_t)min(s_begin + kAhead, s_end - 1) * right_step;
     for (int step = s_begin; step < s_end; ++step) {
-        const uint8_t *cur_stage = smem + cur * kGStage;
-        const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
-        const int prv = cur == 0 ? STAGES - 1 : cur - 1;
-        const uint8_t *nxt_stage = smem + nxt * kGStage;
-        const uint32_t refill = smem_addr + (kSpread ? (cur + kAhead) % STAGES : prv) * kGStage;
+        const uint8_t *cur_stage = smem + cur_off;
+        const int nxt_off = cur_off + kGStage == kRing ? 0 : cur_off + kGStage;
+        const uint8_t *nxt_stage = smem + nxt_off;
+        const uint32_t refill = smem_addr + refill_off + wave_u * 1024;
         // 32 matrix instructions; each is followed by one slice of the other work, pinned in place:
         //    0..15  fragment reads of the step's second k-step
         //   15      transfers of step + 1 have landed (all but the newer groups), barrier
@@ -428,7 +445,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
                 __builtin_shufflevector(rf[ks][j][0], rf[ks][j][1], 0, 1, 2, 3, 4, 5, 6, 7),
                 __builtin_shufflevector(lf[ks][i][0], lf[ks][i][1], 0, 1, 2, 3, 4, 5, 6, 7), acc[i][j], 0, 0, 0);
             if constexpr (kSpread && (k & 3) == 0)
-                transfer(std::integral_constant<int, k / 4>{}, refill, step + kAhead);
+                transfer_from(std::integral_constant<int, k / 4>{}, refill, left_fetch, right_fetch);
             if constexpr (k < 16) {
                 if constexpr (k < kReads)
                     load_frag(std::integral_constant<int, k>{}, cur_stage, std::integral_constant<int, 1>{});
@@ -442,11 +459,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void grad_gemm_tile_kernel(
                 if constexpr (k - 16 < kReads)
                     load_frag(std::integral_constant<int, k - 16>{}, nxt_stage, std::integral_constant<int, 0>{});
                 if constexpr (!kSpread && (k & 1) == 0)
-                    transfer(std::integral_constant<int, (k - 16) / 2>{}, refill, step + kAhead);
+                    transfer_from(std::integral_constant<int, (k - 16) / 2>{}, refill, left_fetch, right_fetch);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
-        cur = nxt;
+        cur_off = nxt_off;
+        refill_off = refill_off + kGStage == kRing ? 0 : refill_off + kGStage;
+        if (step + 1 + kAhead < s_end) {
+            left_fetch += left_step;
+            right_fetch += right_step;
+        }
     }
     wait_vmcnt<0>();   // the look-ahead transfers still write into the stages
 

@@ -181,6 +181,18 @@ __device__ __forceinline__ void lds_dma16(const void *uniform_base, uint32_t lan
                  : "memory");
 }
 
+// Same, the LDS destination given as a wave-uniform base plus a compile-time byte offset: one
+// scalar instruction writes M0 (the addition sets SCC, which is declared clobbered).
+template <int LDS_IMM>
+__device__ __forceinline__ void lds_dma16_at(const void *uniform_base, uint32_t lane_offset, uint32_t lds_base)
+{
+    static_assert(LDS_IMM >= 0, "byte offset into LDS");
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_base), "n"(LDS_IMM)
+                 : "memory", "scc");
+}
+
 // LDS byte address of a pointer into shared memory
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {
