@@ -186,6 +186,8 @@ constexpr int kTileThreads = 256;
 constexpr int kRowBytes = TK / 2;                      // packed bytes per tile row and step
 constexpr int kStageBytes = (TM + TN) * kRowBytes;     // 24 KiB
 constexpr int kStages = 3;
+constexpr int kParkBytes = 4 * 128 * 64 * 2;           // epilogue: four waves x 128 x 64 bf16 (reuses the stages)
+static_assert(kParkBytes <= kStages * kStageBytes, "the epilogue parks in the stages");
 constexpr int kTileLds = kStages * kStageBytes + TN * 4;   // 72 KiB + the tile's weight scales
 
 // 16-byte chunk c (0..3) of tile row `row` lives at chunk c ^ swz(row).  The LDS serves 128-bit
@@ -210,87 +212,6 @@ __device__ __forceinline__ void widen8(uint32_t w, uint32_t field_mask, int &eve
     constexpr uint32_t forced = BITS == 4 ? 0x88888888u : 0x90909090u;
     odd = (int)__builtin_amdgcn_bitop3_b32(w << (4 - BITS), field_mask, forced, 0x6A);
     even = (int)__builtin_amdgcn_bitop3_b32(w << (8 - BITS), field_mask, forced, 0x6A);
-}
-
-// Epilogue of the 256 x 128 tile kernel: the wave's 128 x 64 block at (row0, col0) goes from its
-// transposed accumulator tiles (lane l holds output row l % 32 and runs of four consecutive columns)
-// to memory without a detour through LDS: a lane pair (l, l + 32) exchanges half of its packed
-// results, after which every lane holds sixteen consecutive columns of its row and writes them as
-// two 16-byte pieces.  sa_reg holds s_a / 2^CARRY of the lane's four rows.
-template <int CARRY>
-__device__ __forceinline__ void store_wave_block_direct(const v16i (&acc)[4][2], const float (&sa_reg)[4],
-                                                        const float *sb_lds_wave, int row0, int col0, int M,
-                                                        int N, uint16_t *__restrict__ y, int64_t ld_y,
-                                                        int32_t *__restrict__ acc_out, int lane)
-{
-    const int lm = lane & 31, lh = lane >> 5;
-    if (acc_out) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = row0 + i * 32 + lm;
-                    const int n = col0 + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (m < M && n < N)
-                        acc_out[(int64_t)m * N + n] = acc[i][j][r] >> CARRY;   // exact: a multiple of 2^CARRY
-                }
-    }
-    if (!y)
-        return;
-    float4 sb_reg[2][4];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            sb_reg[j][q] = *reinterpret_cast<const float4 *>(sb_lds_wave + j * 32 + 8 * q + 4 * lh);
-    const bool vector_ok = ((ld_y & 7) == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) && (col0 + 64 <= N);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = row0 + i * 32 + lm;
-        const float sa = sa_reg[i];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            uint32_t d[4][2];   // quad q: columns 8 q + 4 lh .. + 4 of the 32-column tile
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 sb = sb_reg[j][q];
-                const float v0 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 0], sa), sb.x);
-                const float v1 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 1], sa), sb.y);
-                const float v2 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 2], sa), sb.z);
-                const float v3 = __fmul_rn(__fmul_rn((float)acc[i][j][4 * q + 3], sa), sb.w);
-                d[q][0] = pack_bf16(v0, v1);
-                d[q][1] = pack_bf16(v2, v3);
-            }
-            if (vector_ok) {
-                // lanes l and l + 32 hold interleaved runs of four columns of the same row; after the
-                // exchange lane (lm, lh) holds columns 16 lh .. + 16 in the order d[0], d[2], d[1], d[3]
-#pragma unroll
-                for (int q = 0; q < 2; ++q)
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const auto sw = __builtin_amdgcn_permlane32_swap(d[q][e], d[q + 2][e], false, false);
-                        d[q][e] = sw[0];
-                        d[q + 2][e] = sw[1];
-                    }
-                if (row < M) {
-                    uint16_t *dst = y + (int64_t)row * ld_y + col0 + j * 32 + 16 * lh;
-                    *reinterpret_cast<uint4 *>(dst) = make_uint4(d[0][0], d[0][1], d[2][0], d[2][1]);
-                    *reinterpret_cast<uint4 *>(dst + 8) = make_uint4(d[1][0], d[1][1], d[3][0], d[3][1]);
-                }
-            } else if (row < M) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int n = col0 + j * 32 + 8 * q + 4 * lh + e;
-                        if (n < N)
-                            y[(int64_t)row * ld_y + n] = (uint16_t)(d[q][e >> 1] >> (16 * (e & 1)));
-                    }
-            }
-        }
-    }
 }
 
 template <int BITS>
@@ -354,13 +275,14 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     // piece I of contraction step STEP -> stage at LDS byte address STAGE (wave-uniform)
     const uint32_t smem_addr = lds_address(smem);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-#define QUEST_DMA(STAGE, I, STEP)                                                                  \
-    lds_dma16(((I) < 4 ? a_codes : b_codes) + (int64_t)min((STEP), steps - 1) * kRowBytes, src_off[I],  \
-              (STAGE) + ((I) < 4 ? 0 : TM * kRowBytes) +                                           \
-                  (64 * ((I) < 4 ? (I) : (I)-4) + 16 * wave_u) * kRowBytes)
+    // (WAVE_STAGE: LDS byte address of the stage plus this wave's 16 rows)
+#define QUEST_DMA(WAVE_STAGE, I, STEP)                                                             \
+    lds_dma16_at<((I) < 4 ? 0 : TM * kRowBytes) + 64 * ((I) < 4 ? (I) : (I)-4) * kRowBytes>(         \
+        ((I) < 4 ? a_codes : b_codes) + (int64_t)min((STEP), steps - 1) * kRowBytes, src_off[I], (WAVE_STAGE))
 
-    static_for<6>([&](auto i) { QUEST_DMA(smem_addr, decltype(i)::value, 0); });
-    static_for<6>([&](auto i) { QUEST_DMA(smem_addr + kStageBytes, decltype(i)::value, 1); });
+    const uint32_t wave_smem = smem_addr + 16 * wave_u * kRowBytes;
+    static_for<6>([&](auto i) { QUEST_DMA(wave_smem, decltype(i)::value, 0); });
+    static_for<6>([&](auto i) { QUEST_DMA(wave_smem + kStageBytes, decltype(i)::value, 1); });
     // the epilogue's scales, fetched while the first stages are on their way: the weight scales of
     // the tile's columns into their own corner of LDS, this lane's four activation scales into
     // registers (float(64 acc) * (s_a / 64) rounds exactly like float(acc) * s_a)
@@ -447,7 +369,7 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
             if constexpr (s == 7)
                 widen_b(std::integral_constant<int, g + 1>{}, std::integral_constant<int, 1>{});
             if constexpr (k < 18 && k % 3 == 0)
-                QUEST_DMA(smem_addr + stage_two, k / 3, step + 2);
+                QUEST_DMA(wave_smem + stage_two, k / 3, step + 2);
             if constexpr (k >= 2 && k < 8)
                 load_frag(cur, 1, k - 2);
             if constexpr (k == 16) {
@@ -468,9 +390,10 @@ __global__ __launch_bounds__(kTileThreads, 2) void lowbit_gemm_tile_kernel(
     wait_vmcnt<0>();   // all transfers landed before the stages are reused
 #undef QUEST_DMA
 
-    // Epilogue: each wave's 128 x 64 block, straight from registers.
-    store_wave_block_direct<kCarry>(acc, sa_reg, scale_lds + wn * 64, m0 + wm * 128, n0 + wn * 64, M, N, y, ld_y,
-                                    acc_out, lane);
+    // Epilogue: each wave's 128 x 64 block (see store_wave_block), parked in the stages.
+    __syncthreads();   // every wave is done with the stages
+    store_wave_block<4, kCarry>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (128 * 128), m0 + wm * 128,
+                                n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -735,11 +658,13 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     // piece I of contraction step STEP -> stage at LDS byte address STAGE (wave-uniform)
     const uint32_t smem_addr = lds_address(smem);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-#define QUEST_WIDE_DMA(STAGE, I, STEP)                                                                  \
-    lds_dma16(((I) < 4 ? a_codes : b_codes) + (int64_t)min((STEP), steps - 1) * kWideRowBytes, src_off[I], \
-              (STAGE) + ((I) < 4 ? 0 : WTM * kWideRowBytes) + (64 * ((I)&3) + 8 * wave_u) * kWideRowBytes)
+    // (WAVE_STAGE: LDS byte address of the stage plus this wave's 8 rows)
+#define QUEST_WIDE_DMA(WAVE_STAGE, I, STEP)                                                            \
+    lds_dma16_at<((I) < 4 ? 0 : WTM * kWideRowBytes) + 64 * ((I)&3) * kWideRowBytes>(                   \
+        ((I) < 4 ? a_codes : b_codes) + (int64_t)min((STEP), steps - 1) * kWideRowBytes, src_off[I], (WAVE_STAGE))
 
-    static_for<8>([&](auto i) { QUEST_WIDE_DMA(smem_addr, decltype(i)::value, 0); });
+    const uint32_t wave_smem = smem_addr + 8 * wave_u * kWideRowBytes;
+    static_for<8>([&](auto i) { QUEST_WIDE_DMA(wave_smem, decltype(i)::value, 0); });
     // the epilogue's scales, fetched while the first stage is on its way (see the kernel above)
     float *scale_lds = reinterpret_cast<float *>(smem + 2 * kWideStageBytes);
     if (tid < WTN)
@@ -802,7 +727,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     for (int step = 0; step < steps; ++step) {
         const uint8_t *cur = smem + (step & 1) * kWideStageBytes;
         const uint8_t *nxt = smem + ((step + 1) & 1) * kWideStageBytes;
-        const uint32_t nxt_addr = smem_addr + ((step + 1) & 1) * kWideStageBytes;
+        const uint32_t nxt_addr = wave_smem + ((step + 1) & 1) * kWideStageBytes;
         static_for<64>([&](auto kc) {
             constexpr int k = decltype(kc)::value;
             constexpr int g = k >> 3, s = k & 7, i = s >> 1, j = s & 1;
@@ -833,9 +758,10 @@ __global__ __launch_bounds__(kWideThreads, 1) void lowbit_gemm_wide_kernel(
     }
 #undef QUEST_WIDE_DMA
 
-    // Epilogue: each wave's 128 x 64 block, straight from registers.
-    store_wave_block_direct<kCarry>(acc, sa_reg, scale_lds + wn * 64, m0 + wm * 128, n0 + wn * 64, M, N, y, ld_y,
-                                    acc_out, lane);
+    // Epilogue: each wave's 128 x 64 block (see store_wave_block), parked in the stages.
+    __syncthreads();   // every wave is done with the stages
+    store_wave_block<4, kCarry>(acc, sa_reg, scale_lds + wn * 64, smem + wave * (128 * 128), m0 + wm * 128,
+                                n0 + wn * 64, M, N, y, ld_y, acc_out, lane);
 }
 
 // ------------------------------------------------------------------------------------------
