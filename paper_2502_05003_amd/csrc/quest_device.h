@@ -208,4 +208,52 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// ---- rows staged through LDS by the memory system (fused quantizer, trust backward) ----
+// A wave requests its next row with global -> LDS transfers, which hold no registers while in flight,
+// and goes on with the current row; when it comes back for the row, the vector-memory operations it
+// has issued since (its stores) may still be outstanding, the transfers, issued before them, may not
+// (a wave's vector-memory operations complete in issue order).  So the stores are issued by hand,
+// counted, and the wait is for "all but that many".
+
+// one streaming dword store per lane, as an instruction the compiler neither merges nor moves
+__device__ __forceinline__ void store_word_counted(uint32_t *p, uint32_t v)
+{
+    asm volatile("global_store_dword %0, %1, off nt" : : "v"(p), "v"(v) : "memory");
+}
+
+// 16 bytes per lane from global memory straight into LDS (lane l lands at lds_base + 16 l), streaming
+// (the input is read once).  Source = wave-uniform base + per-lane byte offset.
+__device__ __forceinline__ void lds_dma16_stream(const void *uniform_base, uint32_t lane_offset, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_base)
+                 : "memory");
+}
+
+// wait until at most n (0 .. 24; larger values wait as for 24) vector-memory operations are outstanding
+__device__ __forceinline__ void wait_vmcnt_upto(int n)
+{
+    switch (n) {
+#define QUEST_WAIT_CASE(N) case N: wait_vmcnt<N>(); break;
+    QUEST_WAIT_CASE(0) QUEST_WAIT_CASE(1) QUEST_WAIT_CASE(2) QUEST_WAIT_CASE(3) QUEST_WAIT_CASE(4)
+    QUEST_WAIT_CASE(5) QUEST_WAIT_CASE(6) QUEST_WAIT_CASE(7) QUEST_WAIT_CASE(8) QUEST_WAIT_CASE(9)
+    QUEST_WAIT_CASE(10) QUEST_WAIT_CASE(11) QUEST_WAIT_CASE(12) QUEST_WAIT_CASE(13) QUEST_WAIT_CASE(14)
+    QUEST_WAIT_CASE(15) QUEST_WAIT_CASE(16) QUEST_WAIT_CASE(17) QUEST_WAIT_CASE(18) QUEST_WAIT_CASE(19)
+    QUEST_WAIT_CASE(20) QUEST_WAIT_CASE(21) QUEST_WAIT_CASE(22) QUEST_WAIT_CASE(23)
+#undef QUEST_WAIT_CASE
+    default: wait_vmcnt<24>(); break;
+    }
+    asm volatile("" ::: "memory");   // the compiler keeps later LDS reads behind the wait
+}
+
+// 4 bytes per lane (lane l lands at lds_base + 4 l), streaming
+__device__ __forceinline__ void lds_dma4_stream(const void *uniform_base, uint32_t lane_offset, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 nt"
+                 :
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_base)
+                 : "memory");
+}
+
 }  // namespace quest

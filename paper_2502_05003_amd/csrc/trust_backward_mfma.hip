@@ -10,7 +10,10 @@
 //     bits from 6 up; values are scaled by 1 / sqrt(n), rounded to bf16 in pairs (iota, iota + 1),
 //     and one exchange with the neighbouring lane turns those into pairs of adjacent elements, so
 //     that a wave stores 256 contiguous bytes per instruction;
-//   * fp32 outputs are stored as they are, 64 consecutive floats per wave instruction.
+//   * fp32 outputs are stored as they are, 64 consecutive floats per wave instruction;
+//   * rows made of whole 1 KiB pieces, up to 4096 elements, come in through LDS one row ahead, with
+//     their mask bytes behind them (see the quantizer): the next row's memory latency runs under
+//     this row's arithmetic and stores.
 #include "hadamard_tile.h"
 #include "quest_internal.h"
 
@@ -43,6 +46,19 @@ __device__ __forceinline__ uint32_t keep_trusted(uint32_t pair, uint32_t mask_bi
     return pair & __builtin_amdgcn_perm(hi, lo, 0x07060100u);   // low half from lo, high half from hi
 }
 
+// Rows of whole 1 KiB pieces, at most 4096 elements (four workgroups' buffers fit a CU's LDS), and few
+// enough stores per row and lane for the wait on the vector-memory counter to tell them from the
+// transfers (the counter has six bits).
+constexpr bool tb_rows_through_lds(int u, bool f32_out)
+{
+    return (u % 8) == 0 && u <= 32 && (f32_out ? 4 * u : 2 * u) / 2 <= 48;
+}
+// LDS per wave: the row, then its mask bytes rounded up to whole 256-byte transfers
+constexpr int tb_wave_buffer_bytes(int u)
+{
+    return 256 * u + 256 * ((16 * u + 255) / 256);
+}
+
 template <int U, int LOG2N, bool WITH_MASK, typename Out = uint16_t>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4)))
 void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ mask, int64_t rows,
@@ -59,6 +75,40 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
+
+    // Row staging through LDS, as in the fused quantizer: each wave owns a buffer of one gradient row
+    // (pieces of 16 tile rows of 64 bytes, chunk c of tile row r in slot c ^ ((r >> 2) & 3)) followed
+    // by the row's mask bytes, both filled by global -> LDS transfers that are requested one row ahead.
+    constexpr int kStoresPerRow = kF32Out ? NI : NI / 2;
+    constexpr bool kLdsRow = tb_rows_through_lds(U, kF32Out);
+    constexpr int kPieces = U / 4;
+    constexpr int kMaskBytes = 16 * U, kMaskPieces = (kMaskBytes + 255) / 256;
+    constexpr int kWaveBuffer = tb_wave_buffer_bytes(U);
+    extern __shared__ __attribute__((aligned(16))) uint8_t row_buffers[];
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint8_t *my_buffer = row_buffers + wave_u * kWaveBuffer;
+    const uint32_t my_buffer_addr = lds_address(row_buffers) + (uint32_t)(wave_u * kWaveBuffer);
+    const uint32_t piece_offset = (uint32_t)(64 * (lane >> 2) + 16 * ((lane & 3) ^ ((lane >> 4) & 3)));
+    auto request_row = [&](int64_t row) {
+        const char *base = reinterpret_cast<const char *>(g + row * cols);
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i)
+            lds_dma16_stream(base + 1024 * i, piece_offset, my_buffer_addr + 1024 * i);
+        if constexpr (WITH_MASK) {
+            // lanes past the end of the row's mask fetch its last dword again (in bounds, never read)
+            const char *mask_base = reinterpret_cast<const char *>(mask + row * (cols / 8));
+#pragma unroll
+            for (int i = 0; i < kMaskPieces; ++i)
+                lds_dma4_stream(mask_base, (uint32_t)min(256 * i + 4 * lane, kMaskBytes - 4),
+                                my_buffer_addr + 256 * U + 256 * i);
+        }
+    };
+    const int64_t row_stride = (int64_t)gridDim.x * kRowsPerBlock;
+    int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave_u;
+    if constexpr (kLdsRow) {
+        if (row < rows)
+            request_row(row);   // before anything else is set up
+    }
 
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
     v8bf bmat[2];
@@ -82,10 +132,28 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
     // exchange with lane ^ 1: even lanes keep the low halves, odd lanes the high halves
     const uint32_t pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
 
-    for (int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave; row < rows;
-         row += (int64_t)gridDim.x * kRowsPerBlock) {
+    int stores_after_request = 0;   // stores issued since the transfers of the row about to be read
+    for (; row < rows; row += row_stride) {
         const uint16_t *src = g + row * cols + 32 * m + 16 * h;
         const uint8_t *mask_src = mask + row * (cols / 8) + 4 * m + 2 * h;
+        // the whole row's inputs, out of LDS, before the buffer is handed to the next row
+        v4u staged[kLdsRow ? T : 1][2];
+        uint32_t staged_bits[kLdsRow ? T : 1];
+        if constexpr (kLdsRow) {
+            wait_vmcnt_upto(stores_after_request);   // this row has landed
+            const int slot0 = (2 * h) ^ ((m >> 2) & 3), slot1 = (2 * h + 1) ^ ((m >> 2) & 3);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                staged[t][0] = *reinterpret_cast<const v4u *>(my_buffer + 2048 * t + 64 * m + 16 * slot0);
+                staged[t][1] = *reinterpret_cast<const v4u *>(my_buffer + 2048 * t + 64 * m + 16 * slot1);
+                staged_bits[t] = WITH_MASK ? *reinterpret_cast<const uint16_t *>(my_buffer + 256 * U + 128 * t + 4 * m + 2 * h)
+                                           : 0xffffu;
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): the buffer has been read, it may be refilled
+            if (row + row_stride < rows)
+                request_row(row + row_stride);
+            stores_after_request = kStoresPerRow;
+        }
         // tiles that one Hadamard block couples are transformed together, the others one after another
 #pragma unroll
         for (int g0 = 0; g0 < T; g0 += G) {
@@ -96,7 +164,11 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
                 const int t = g0 + u;
                 v4u n0 = {0, 0, 0, 0}, n1 = {0, 0, 0, 0};
                 uint32_t bits = 0xffffu;
-                if (t < T && (t < T - 1 || m < kTailRows)) {
+                if constexpr (kLdsRow) {   // whole tiles only
+                    n0 = staged[t][0];
+                    n1 = staged[t][1];
+                    bits = staged_bits[t];
+                } else if (t < T && (t < T - 1 || m < kTailRows)) {
                     n0 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t));
                     n1 = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src + 1024 * t + 8));
                     if (WITH_MASK)
@@ -141,8 +213,13 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
                 float *dst = out + row * cols + lane + 64 * first;
 #pragma unroll
                 for (int i = 0; i < kGroupI; ++i)
-                    if (i < count_i)
-                        __builtin_nontemporal_store(__fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n), dst + 64 * i);
+                    if (i < count_i) {
+                        const float v = __fmul_rn(acc[i >> 4][reg_of_iota(i & 15)], inv_sqrt_n);
+                        if constexpr (kLdsRow)
+                            store_word_counted(reinterpret_cast<uint32_t *>(dst + 64 * i), __float_as_uint(v));
+                        else
+                            __builtin_nontemporal_store(v, dst + 64 * i);
+                    }
             } else {
                 // Round (iota, iota + 1) to a bf16 pair, swap halves with lane ^ 1: an even lane then
                 // holds elements (l, l + 1) of iota, an odd lane elements (l - 1, l) of iota + 1.  A wave
@@ -156,7 +233,10 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
                         const float v1 = __fmul_rn(acc[(i + 1) >> 4][reg_of_iota((i + 1) & 15)], inv_sqrt_n);
                         const uint32_t own = pack_bf16_pair(v0, v1);
                         const uint32_t other = (uint32_t)__builtin_amdgcn_ds_swizzle((int)own, (1 << 10) | 0x1f);
-                        __builtin_nontemporal_store(__builtin_amdgcn_perm(other, own, pair_sel), dst + 32 * i);
+                        if constexpr (kLdsRow)
+                            store_word_counted(dst + 32 * i, __builtin_amdgcn_perm(other, own, pair_sel));
+                        else
+                            __builtin_nontemporal_store(__builtin_amdgcn_perm(other, own, pair_sel), dst + 32 * i);
                     }
                 }
             }
@@ -172,11 +252,13 @@ void launch(const BackwardArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *g = static_cast<const uint16_t *>(a.g);
     auto *out = static_cast<Out *>(a.out);
+    constexpr unsigned lds_bytes = tb_rows_through_lds(U, sizeof(Out) == 4) ? kRowsPerBlock * tb_wave_buffer_bytes(U) : 0;
+    static_assert(lds_bytes <= 40960, "four workgroups per CU");
     if (a.mask)
-        hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, true, Out>), grid, dim3(kThreads), 0, stream, g,
+        hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, true, Out>), grid, dim3(kThreads), lds_bytes, stream, g,
                            a.mask, a.rows, a.log2n, out);
     else
-        hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, false, Out>), grid, dim3(kThreads), 0, stream, g,
+        hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, false, Out>), grid, dim3(kThreads), lds_bytes, stream, g,
                            a.mask, a.rows, a.log2n, out);
 }
 
