@@ -148,21 +148,27 @@ __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__rest
                                                            int cb, int K, int64_t groups,
                                                            uint16_t *__restrict__ qhat)
 {
-    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;   // group of eight elements
-    if (g >= groups)
-        return;
+    // a workgroup takes 1024 consecutive groups of eight elements, a thread four of them, 256 apart:
+    // every load instruction of a wave reads 256 contiguous bytes of codes (at 4 bits), every store
+    // writes 1 KiB, and a thread has four independent chains in flight
     const int per_row = K / 8;
+    const float offset = -(float)(levels - 1);
+    const uint32_t field = (1u << cb) - 1u;
+#pragma unroll
+    for (int part = 0; part < 4; ++part) {
+    const int64_t g = (int64_t)blockIdx.x * 1024 + part * 256 + threadIdx.x;   // group of eight elements
+    if (g >= groups)
+        continue;
     const int64_t row = g / per_row;
     const uint8_t *src = codes + g * cb;
     uint32_t bits = 0;
     if (cb == 4) {
-        bits = *reinterpret_cast<const uint32_t *>(src);
+        bits = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src));
     } else {
         for (int byte = 0; byte < cb; ++byte)
             bits |= (uint32_t)src[byte] << (8 * byte);
     }
-    const float s = scales[row], offset = -(float)(levels - 1);
-    const uint32_t field = (1u << cb) - 1u;
+    const float s = scales[row];
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -178,6 +184,7 @@ __global__ __launch_bounds__(256) void expand_codes_kernel(const uint8_t *__rest
     }
     *reinterpret_cast<uint4 *>(qhat + g * 8) = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]),
                                                           pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+    }
 }
 
 // Work is counted in (tile, step) units: tile t owns the units [t * steps, (t + 1) * steps) and
@@ -693,7 +700,7 @@ hipError_t launch_grad_gemm(const GradGemmArgs &a, hipStream_t stream)
         const int64_t ld_left = p.ld_left, contraction = p.contraction, out_rows = p.out_rows, out_cols = p.out_cols;
 
         const int64_t groups = p.q_rows * a.K / 8;
-        hipLaunchKernelGGL(expand_codes_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream,
+        hipLaunchKernelGGL(expand_codes_kernel, dim3((unsigned)((groups + 1023) / 1024)), dim3(256), 0, stream,
                            a.q_codes, a.q_scales, levels, a.cb, (int)a.K, groups, qhat);
         err = hipGetLastError();
         if (err != hipSuccess)
