@@ -51,10 +51,10 @@ MIB = 1 << 20
 MEASURED_TRAFFIC_MIB = {
     "quantize_x": (64.1, 20.3),
     "quantize_w": (22.1, 7.0),
-    "lowbit_gemm": (127.2, 176.0),
-    "grad_gemm_x": (555.5, 102.8),
-    "grad_gemm_w": (1005.7, 205.7),
-    "trust_backward_x": (68.4, 64.0),
+    "lowbit_gemm": (128.2, 176.0),
+    "grad_gemm_x": (555.7, 102.8),
+    "grad_gemm_w": (1013.0, 205.7),
+    "trust_backward_x": (68.1, 64.0),
     "trust_backward_w": (23.5, 22.0),
 }
 
