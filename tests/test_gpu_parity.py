@@ -71,6 +71,10 @@ QUANT_CASES = [
     (37, 1792, 256, 4, "f32"), (37, 2816, 256, 4, "f32"), (37, 3584, 512, 4, "f32"), (37, 4608, 512, 4, "f32"),
     # blocks that span two of a row's four tiles, and one of them
     (33, 4096, 2048, 4, "bf16"), (33, 4096, 1024, 4, "bf16"), (33, 4096, 512, 4, "bf16"),
+    # more rows than waves on the chip (4096): every wave takes several rows, the next one staged through
+    # LDS while the current one is quantized, with a ragged last pass; a row count below one pass
+    (8229, 1024, 1024, 4, "bf16"), (9001, 2048, 512, 2, "bf16"), (5003, 4096, 4096, 8, "bf16"),
+    (4099, 2048, 2048, 4, "bf16"),
 ]
 
 
@@ -439,7 +443,11 @@ BACK_CASES = [(37, 1024, 128, "bf16", "bf16"), (130, 2048, 2048, "bf16", "bf16")
               (37, 640, 128, "bf16", "f32"), (37, 1664, 128, "bf16", "f32"), (37, 2816, 256, "bf16", "f32"),
               (37, 4608, 512, "bf16", "f32"), (21, 11008, 256, "bf16", "f32"),
               # blocks that span two of a row's four tiles, and one of them
-              (33, 4096, 2048, "bf16", "bf16"), (33, 4096, 1024, "bf16", "bf16"), (33, 4096, 128, "bf16", "bf16")]
+              (33, 4096, 2048, "bf16", "bf16"), (33, 4096, 1024, "bf16", "bf16"), (33, 4096, 128, "bf16", "bf16"),
+              # more rows than waves on the chip (4096): every wave takes several rows, the next one staged
+              # through LDS while the current one is transformed and stored, and the last pass is ragged
+              (8229, 1024, 1024, "bf16", "bf16"), (8229, 1024, 128, "bf16", "f32"), (9001, 2048, 2048, "bf16", "f32"),
+              (5003, 4096, 4096, "bf16", "bf16")]
 
 
 @pytest.mark.parametrize("rows,cols,n,gd,od", BACK_CASES)
