@@ -37,8 +37,11 @@ FP4_PEAK_TOPS = 10100.0      # dense FP4 MFMA (--grid fp4)
 
 WORKLOAD = "mlp_up_1p6b"     # the headline: X 16384x2048, W 5632x2048, Hadamard block 2048, b = 4
 WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b")   # down: X 16384x5632, W 2048x5632, block 512
-KERNELS = ("quantize_x", "quantize_w", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w",
-           "trust_backward_x", "trust_backward_w")
+# launches of a step: the integer grid quantizes activations and weights by one call (Algorithm 1 steps
+# 2-5 for both operands), the FP4 variant by two; --only can also launch either operand's quantizer alone
+STEP_KERNELS = ("quantize_xw", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w", "trust_backward_x", "trust_backward_w")
+STEP_KERNELS_FP4 = ("quantize_x", "quantize_w") + STEP_KERNELS[1:]
+KERNELS = ("quantize_x", "quantize_w") + STEP_KERNELS
 FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the forward (--only)
 
 
@@ -49,8 +52,7 @@ FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the f
 # of known size that the same run launches.  A gradient matmul is the sum over the kernels of its call.
 MIB = 1 << 20
 MEASURED_TRAFFIC_MIB = {
-    "quantize_x": (64.1, 20.3),
-    "quantize_w": (22.1, 7.0),
+    "quantize_xw": (86.2, 27.3),
     "lowbit_gemm": (128.2, 176.0),
     "grad_gemm_x": (555.7, 102.8),
     "grad_gemm_w": (1013.0, 205.7),
@@ -106,7 +108,7 @@ class BufferSet:
 
 
 def step_kernels(q, b, cfg, fp4=False):
-    """The seven launches of one step as (name, thunk) pairs, in execution order."""
+    """The launches of one step as (name, thunk) pairs, in execution order."""
     M, N, K, n, bits = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"], cfg["bits"]
     if fp4:   # the FP4 variant of the method (Sec. 4.4): E2M1 codes, FP4 matrix instructions
         return [
@@ -123,10 +125,10 @@ def step_kernels(q, b, cfg, fp4=False):
             ("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw)),
         ]
     return [
-        ("quantize_x", lambda: q.quest_hadamard_quantize(b.x, n, bits, codes=b.x_codes,
-                                                         scales=b.x_scales, mask=b.x_mask)),
-        ("quantize_w", lambda: q.quest_hadamard_quantize(b.w, n, bits, codes=b.w_codes,
-                                                         scales=b.w_scales, mask=b.w_mask)),
+        ("quantize_xw", lambda: q.quest_hadamard_quantize_pair(b.x, b.w, n, bits, x_codes=b.x_codes,
+                                                               x_scales=b.x_scales, x_mask=b.x_mask,
+                                                               w_codes=b.w_codes, w_scales=b.w_scales,
+                                                               w_mask=b.w_mask)),
         ("lowbit_gemm", lambda: q.quest_lowbit_gemm(b.x_codes, b.x_scales, b.w_codes, b.w_scales,
                                                     K, bits, y=b.y, workspace=b.ws_gemm)),
         ("grad_gemm_x", lambda: q.quest_grad_gemm(0, b.dy, b.w_codes, b.w_scales, bits, M, N, K,
@@ -448,6 +450,12 @@ def main():
                                                              scales=b.x_scales, mask=b.x_mask)
             if args.only == "lowbit_gemm_fp4":
                 return lambda: q.quest_lowbit_gemm_fp4(b.x_codes, b.x_scales, b.w_codes, b.w_scales, K, y=b.y)
+            if args.only == "quantize_x":
+                return lambda: q.quest_hadamard_quantize(b.x, cfg["had_block"], cfg["bits"], codes=b.x_codes,
+                                                         scales=b.x_scales, mask=b.x_mask)
+            if args.only == "quantize_w":
+                return lambda: q.quest_hadamard_quantize(b.w, cfg["had_block"], cfg["bits"], codes=b.w_codes,
+                                                         scales=b.w_scales, mask=b.w_mask)
             return dict(step_kernels(q, b, cfg, args.grid == "fp4"))[args.only]
 
         launches = [chosen(b) for b in sets]
@@ -473,7 +481,8 @@ def main():
     def event_pair():
         return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
-    events = [{k: event_pair() for k in KERNELS} for _ in range(args.steps)]
+    step_names = STEP_KERNELS_FP4 if args.grid == "fp4" else STEP_KERNELS
+    events = [{k: event_pair() for k in step_names} for _ in range(args.steps)]
     empty = [event_pair() for _ in range(args.steps)]
     scratch_pair = event_pair()
 
@@ -499,7 +508,7 @@ def main():
 
     gap_ms = 0.5 * float(np.median([a.elapsed_time(b) for a, b in empty]))
     ms = {k: max(float(np.mean([e[k][0].elapsed_time(e[k][1]) for e in events])) - gap_ms, 1e-6)
-          for k in KERNELS}
+          for k in step_names}
     ms_per_step = elapsed * 1e3 / args.steps
     gemm_ops = 2.0 * M * N * K
     step_ops = 3.0 * gemm_ops
@@ -524,16 +533,21 @@ def main():
 
     grad_x_bytes = 2 * M * N + N * K * cb // 8 + 4 * N + 2 * M * K     # dY + weight codes + scales + G_x
     grad_w_bytes = 2 * M * N + M * K * cb // 8 + 4 * M + 2 * N * K     # dY + activation codes + scales + G_w
-    rooflines = {
-        "quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K, cb)),
-        "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K, cb)),
+    if "quantize_xw" in ms:
+        rooflines = {"quantize_xw": hbm("quantize_xw", algorithmic_bytes_quantize(M, K, cb) +
+                                        algorithmic_bytes_quantize(N, K, cb))}
+    else:
+        rooflines = {"quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K, cb)),
+                     "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K, cb))}
+    quantize_ms = sum(v["ms"] for v in rooflines.values())
+    rooflines.update({
         "lowbit_gemm": mfma("lowbit_gemm", FP4_PEAK_TOPS if args.grid == "fp4" else INT8_PEAK_TOPS,
                             algorithmic_bytes_gemm(M, N, K, cb)),
         "grad_gemm_x": mfma("grad_gemm_x", BF16_PEAK_TFLOPS, grad_x_bytes),
         "grad_gemm_w": mfma("grad_gemm_w", BF16_PEAK_TFLOPS, grad_w_bytes),
         "trust_backward_x": hbm("trust_backward_x", algorithmic_bytes_backward(M, K)),
         "trust_backward_w": hbm("trust_backward_w", algorithmic_bytes_backward(N, K)),
-    }
+    })
 
     result = {
         "metric": f"W{cfg['bits']}A{cfg['bits']} QuEST-linear TOPS at d=2048 "
@@ -549,9 +563,9 @@ def main():
                                f"{cfg['had_block']}, b={cfg['bits']}, forward+backward",
                    "grid": args.grid, "M": M, "N": N, "K": K, "had_block": cfg["had_block"], "bits": cfg["bits"],
                    "buffer_sets": n_sets, "event_gap_us_subtracted": gap_ms * 1e3},
-        "quantizer_GBps": rooflines["quantize_x"]["achieved"],
+        "quantizer_GBps": rooflines["quantize_xw" if "quantize_xw" in rooflines else "quantize_x"]["achieved"],
         "gemm_TOPS": rooflines["lowbit_gemm"]["achieved"],
-        "forward_TOPS": gemm_ops / ((ms["quantize_x"] + ms["quantize_w"] + ms["lowbit_gemm"]) * 1e-3) / 1e12,
+        "forward_TOPS": gemm_ops / ((quantize_ms + ms["lowbit_gemm"]) * 1e-3) / 1e12,
         "roofline": dict(rooflines["lowbit_gemm"]),
         "kernels": rooflines,
     }

@@ -92,6 +92,28 @@ quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t r
                                      uint8_t *mask, float *xh_out, void *stream);
 
 /*
+ * Algorithm 1 for both operands of one layer in one call: steps 2 and 3 for the activations x, steps
+ * 4 and 5 for the weights w (the same transform, projection and trust mask as
+ * quest_hadamard_quantize; x and w share the row length, which is the layer's contraction dimension,
+ * the Hadamard block, the bit width and the clip).  Where one kernel covers the shape the two row
+ * sets are quantized by a single launch, which is what a QAT step wants: the weights are quantized
+ * anew in every step, and their launch, 5632 rows at the 1.6B model's width, is too small to fill
+ * the chip by itself.
+ *
+ *   x, w                [rows_x, ld_x] and [rows_w, ld_w] row-major, both of `dtype`
+ *   codes_*, scales_*   outputs as in quest_hadamard_quantize, one set per operand
+ *   mask_x, mask_w      trust bitmaps; give both or neither (QUEST_ERR_ARG otherwise)
+ *   dtype .. outer_trust as in quest_hadamard_quantize
+ * rows_x or rows_w may be 0 (that operand's pointers may then be NULL).  The outputs are identical, bit for bit, to those of two calls of
+ * quest_hadamard_quantize.  Same limits, alignment rules and errors; no xh_out.
+ */
+quest_status quest_hadamard_quantize_pair(const void *x, int64_t rows_x, int64_t ld_x, uint8_t *codes_x,
+                                          float *scales_x, uint8_t *mask_x, const void *w, int64_t rows_w,
+                                          int64_t ld_w, uint8_t *codes_w, float *scales_w, uint8_t *mask_w,
+                                          quest_dtype dtype, int64_t cols, int32_t had_block, int32_t bits,
+                                          float alpha, float outer_trust, void *stream);
+
+/*
  * The comparison quantizer of Sec. 4.1 (scale taken from the row's largest magnitude instead of
  * a fit to the value distribution), and with had_block = 1 the no-transform ablation of Sec. 4.3: everything as in
  * quest_hadamard_quantize, except that the grid spans the row's largest magnitude,

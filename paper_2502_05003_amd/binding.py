@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
-EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
+EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_pair", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
            "quest_lowbit_gemm", "quest_lowbit_gemm_workspace_bytes", "quest_lowbit_gemm_static", "quest_lowbit_gemm_fp4", "quest_trust_backward",
            "quest_grad_gemm", "quest_grad_gemm_workspace_bytes", "quest_grad_gemm_fp4",
            "quest_grad_gemm_fp4_workspace_bytes", "quest_weight_only_gemm", "quest_weight_only_gemm_workspace_bytes",
@@ -42,6 +42,9 @@ def load():
         lib = ctypes.CDLL(LIB_PATH)
         lib.quest_hadamard_quantize.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _i32, _f32, _f32,
                                                 _p, _p, _p, _p, _p]
+        lib.quest_hadamard_quantize_pair.argtypes = [_p, _i64, _i64, _p, _p, _p, _p, _i64, _i64, _p, _p, _p,
+                                                     _i32, _i64, _i32, _i32, _f32, _f32, _p]
+        lib.quest_hadamard_quantize_pair.restype = ctypes.c_int
         lib.quest_hadamard_quantize_absmax.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _i32,
                                                        _p, _p, _p, _p, _p]
         lib.quest_hadamard_quantize_fp4.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _f32, _p, _p, _p, _p, _p]
@@ -123,6 +126,20 @@ def quest_hadamard_quantize(x: torch.Tensor, had_block: int, bits: int, alpha: f
                                           had_block, bits, alpha, outer_trust, _ptr(codes),
                                           _ptr(scales), _ptr(mask), _ptr(xh_out), _stream()),
            "quest_hadamard_quantize")
+
+
+def quest_hadamard_quantize_pair(x: torch.Tensor, w: torch.Tensor, had_block: int, bits: int, alpha: float = 0.0,
+                                 outer_trust: float = -1.0, *, x_codes: torch.Tensor, x_scales: torch.Tensor,
+                                 w_codes: torch.Tensor, w_scales: torch.Tensor,
+                                 x_mask: torch.Tensor | None = None, w_mask: torch.Tensor | None = None) -> None:
+    """Activations x [rows_x, cols] and weights w [rows_w, cols] of one layer quantized by one call."""
+    if x.shape[1] != w.shape[1] or x.dtype != w.dtype:
+        raise ValueError("the two operands of a pair call share the row length and the dtype")
+    _check(load().quest_hadamard_quantize_pair(_ptr(x), x.shape[0], x.stride(0), _ptr(x_codes), _ptr(x_scales),
+                                               _ptr(x_mask), _ptr(w), w.shape[0], w.stride(0), _ptr(w_codes),
+                                               _ptr(w_scales), _ptr(w_mask), _dtype_code(x), x.shape[1], had_block,
+                                               bits, alpha, outer_trust, _stream()),
+           "quest_hadamard_quantize_pair")
 
 
 def quest_hadamard_quantize_absmax(x: torch.Tensor, had_block: int, bits: int, *, codes: torch.Tensor,

@@ -192,6 +192,25 @@ hipError_t prepare_quantize_kernels()
 
 hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream)
 {
+    if (a.rows2 != 0) {
+        // two operands: one launch where the matrix-core kernel covers the shape, else one after the other
+        if (a.rows != 0 && launch_hadamard_quantize_mfma(a, stream))
+            return hipGetLastError();
+        QuantizeArgs first = a, second = a;
+        first.x2 = nullptr;
+        first.rows2 = 0;
+        second.x = a.x2;
+        second.rows = a.rows2;
+        second.ld = a.ld2;
+        second.codes = a.codes2;
+        second.scales = a.scales2;
+        second.mask = a.mask2;
+        second.xh_out = nullptr;
+        second.x2 = nullptr;
+        second.rows2 = 0;
+        const hipError_t err = launch_hadamard_quantize(first, stream);
+        return err != hipSuccess ? err : launch_hadamard_quantize(second, stream);
+    }
     if (a.rows == 0)
         return hipSuccess;
     if (launch_hadamard_quantize_mfma(a, stream))

@@ -145,10 +145,16 @@ template <int U, int LOG2N, bool WITH_MASK, bool FP4 = false, int BITS = 4, type
 __global__ __launch_bounds__(kThreads)
 __attribute__((amdgpu_waves_per_eu(hq_waves_per_eu<U, (sizeof(In) == 4 || ABSMAX), sizeof(In) == 4>())))
 void hq_mfma_kernel(
-    const In *__restrict__ x, int64_t rows, int64_t ld, int log2n, float alpha,
-    float trust_edge, uint8_t *__restrict__ codes, float *__restrict__ scales,
-    uint8_t *__restrict__ mask, float *__restrict__ xh_out)
+    const In *__restrict__ x_a, int64_t rows_a, int64_t ld_a, int log2n, float alpha,
+    float trust_edge, uint8_t *__restrict__ codes_a, float *__restrict__ scales_a,
+    uint8_t *__restrict__ mask_a, float *__restrict__ xh_out,
+    const In *__restrict__ x_b, int64_t rows_b, int64_t ld_b, uint8_t *__restrict__ codes_b,
+    float *__restrict__ scales_b, uint8_t *__restrict__ mask_b)
 {
+    // Two operands of one layer (activations and weights, same row length, block and grid) can share
+    // a launch: the rows of the second follow those of the first in the launch's row numbering, and
+    // every row picks its operand's pointers.  rows_b = 0 is the single-operand call.
+    const int64_t rows = rows_a + rows_b;
     constexpr int T = (U + 7) / 8;         // tiles of 1024 elements; the last one may be partial
     constexpr int NI = 2 * U;              // elements per lane
     constexpr int cols = 128 * U;
@@ -183,18 +189,21 @@ void hq_mfma_kernel(
     const uint8_t *my_buffer = row_buffers + wave_u * (256 * U);
     const uint32_t my_buffer_addr = lds_address(row_buffers) + (uint32_t)wave_u * (256u * U);
     const uint32_t piece_offset = (uint32_t)(64 * (lane >> 2) + 16 * ((lane & 3) ^ ((lane >> 4) & 3)));
-    auto request_row = [&](int64_t row) {
-        const char *base = reinterpret_cast<const char *>(reinterpret_cast<const uint16_t *>(x) + row * ld);
+    auto request_row = [&](int64_t row_of_launch) {
+        const bool second = row_of_launch >= rows_a;
+        const char *base = reinterpret_cast<const char *>(
+            second ? reinterpret_cast<const uint16_t *>(x_b) + (row_of_launch - rows_a) * ld_b
+                   : reinterpret_cast<const uint16_t *>(x_a) + row_of_launch * ld_a);
 #pragma unroll
         for (int i = 0; i < kPieces; ++i)
             lds_dma16_stream(base + 1024 * i, piece_offset, my_buffer_addr + 1024 * i);
     };
     // the first row is requested before anything else is set up
     const int64_t row_stride = (int64_t)gridDim.x * kRowsPerBlock;
-    int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave_u;
+    int64_t row_of_launch = (int64_t)blockIdx.x * kRowsPerBlock + wave_u;
     if constexpr (kLdsRow) {
-        if (row < rows)
-            request_row(row);
+        if (row_of_launch < rows)
+            request_row(row_of_launch);
     }
 
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
@@ -238,7 +247,7 @@ void hq_mfma_kernel(
     struct RawRow {
         uint4 a[kF32 ? 1 : T][2];
     };
-    auto load_row = [&](int64_t row, RawRow &raw) {
+    auto load_row = [&](const In *x, int64_t ld, int64_t row, RawRow &raw) {
         if constexpr (!kF32) {   // fp32 rows stream in tile by tile, see below
             const uint16_t *src = reinterpret_cast<const uint16_t *>(x) + row * ld + 32 * m + 16 * h;
 #pragma unroll
@@ -287,17 +296,25 @@ void hq_mfma_kernel(
     };
 
     int stores_after_request = 0;   // stores issued since the transfers of the row about to be read
-    for (; row < rows; row += row_stride) {
+    for (; row_of_launch < rows; row_of_launch += row_stride) {
+        // this row's operand (wave-uniform)
+        const bool second = row_of_launch >= rows_a;
+        const int64_t row = second ? row_of_launch - rows_a : row_of_launch;
+        const In *x = second ? x_b : x_a;
+        const int64_t ld = second ? ld_b : ld_a;
+        uint8_t *codes = second ? codes_b : codes_a;
+        float *scales = second ? scales_b : scales_a;
+        uint8_t *mask = second ? mask_b : mask_a;
         RawRow raw;
         if constexpr (kLdsRow) {
             wait_vmcnt_upto(stores_after_request);   // this row has landed
             read_row(raw);
             __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): the buffer has been read, it may be refilled
-            if (row + row_stride < rows)
-                request_row(row + row_stride);
+            if (row_of_launch + row_stride < rows)
+                request_row(row_of_launch + row_stride);
             stores_issued = 0;
         } else {
-            load_row(row, raw);
+            load_row(x, ld, row, raw);
         }
         // Per-row constants in the un-normalised domain (x_h = raw / sqrt(n)).  The reciprocal and
         // the square root are the hardware approximations (1 ulp): the codes are decided on
@@ -460,7 +477,7 @@ void hq_mfma_kernel(
             const int first = 16 * g0;
             const int count_i = (NI - first) < kGroupI ? (NI - first) : kGroupI;
 
-            if (xh_out) {
+            if (xh_out && !second) {   // debug output of the first operand only
                 float *dst = xh_out + row * cols + lane;   // element = lane + 64 iota
 #pragma unroll
                 for (int i = 0; i < kGroupI; ++i)
@@ -593,21 +610,22 @@ void hq_mfma_kernel(
 template <int U, int LOG2N, bool FP4 = false, int BITS = 4, typename In = uint16_t, bool ABSMAX = false>
 void launch(const QuantizeArgs &a, hipStream_t stream)
 {
-    const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int64_t blocks_needed = (a.rows + a.rows2 + kRowsPerBlock - 1) / kRowsPerBlock;
     const int64_t max_blocks = 256 * kBlocksPerCu;
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *x = static_cast<const In *>(a.x);
+    const auto *x2 = static_cast<const In *>(a.x2);
     // one row buffer per wave for the rows that are staged through LDS (see the kernel), 45 KiB at most
     constexpr bool kLdsRow = sizeof(In) == 2 && (U % 4) == 0 && U <= 44;
     constexpr unsigned lds_bytes = kLdsRow ? kRowsPerBlock * 256 * U : 0;
     if (a.mask)
         hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, true, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads),
                            lds_bytes, stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales,
-                           a.mask, a.xh_out);
+                           a.mask, a.xh_out, x2, a.rows2, a.ld2, a.codes2, a.scales2, a.mask2);
     else
         hipLaunchKernelGGL((hq_mfma_kernel<U, LOG2N, false, FP4, BITS, In, ABSMAX>), grid, dim3(kThreads),
                            lds_bytes, stream, x, a.rows, a.ld, a.log2n, a.alpha, a.trust_edge, a.codes, a.scales,
-                           a.mask, a.xh_out);
+                           a.mask, a.xh_out, x2, a.rows2, a.ld2, a.codes2, a.scales2, a.mask2);
 }
 
 }  // namespace

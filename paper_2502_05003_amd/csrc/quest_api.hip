@@ -186,29 +186,57 @@ const char *quest_status_string(quest_status status)
 
 namespace {
 
-// Shared by the two quantizer entry points; absmax ignores alpha and outer_trust.
-quest_status quantize_entry(const void *x, quest_dtype dtype, int64_t rows, int64_t cols, int64_t ld,
-                            int32_t had_block, int32_t bits, float alpha, float outer_trust, int mode,
-                            uint8_t *codes, float *scales, uint8_t *mask, float *xh_out, void *stream)
+// One operand of a quantizer call (rows of `cols` elements at stride ld, and its outputs).
+struct QuantOperand {
+    const void *x;
+    int64_t rows, ld;
+    uint8_t *codes;
+    float *scales;
+    uint8_t *mask;
+};
+
+// (`empty_may_be_null`: an operand of a pair call that has no rows needs no buffers)
+quest_status check_quant_operand(const QuantOperand &o, quest_dtype dtype, int64_t cols, int32_t had_block,
+                                 int *log2n, bool empty_may_be_null)
 {
-    if (!x || !codes || !scales)
+    if (!(empty_may_be_null && o.rows == 0) && (!o.x || !o.codes || !o.scales))
         return QUEST_ERR_NULL;
-    if (dtype != QUEST_F32 && dtype != QUEST_BF16)
-        return QUEST_ERR_DTYPE;
-    const int cb = container_bits(bits);
-    if (cb == 0)
-        return QUEST_ERR_BITS;
-    int log2n = 0;
-    const quest_status shape = shape_checks(rows, cols, had_block, &log2n);
+    const quest_status shape = shape_checks(o.rows, cols, had_block, log2n);
     if (shape != QUEST_OK)
         return shape;
-    if (ld < cols)
+    if (o.ld < cols)
         return QUEST_ERR_SHAPE;
     const int64_t elem = dtype == QUEST_BF16 ? 2 : 4;
-    if (!aligned16(x) || !aligned16(codes) || (mask && !aligned16(mask)) ||
-        (xh_out && !aligned16(xh_out)) || ((ld * elem) & 15) ||
-        (reinterpret_cast<uintptr_t>(scales) & 3u))
+    if (!aligned16(o.x) || !aligned16(o.codes) || (o.mask && !aligned16(o.mask)) || ((o.ld * elem) & 15) ||
+        (reinterpret_cast<uintptr_t>(o.scales) & 3u))
         return QUEST_ERR_ALIGN;
+    return QUEST_OK;
+}
+
+// Shared by the quantizer entry points; absmax ignores alpha and outer_trust.  `second` is the other
+// operand of a pair call (same dtype, row length, block, grid and clip), or null.
+quest_status quantize_entry(const QuantOperand &first, const QuantOperand *second, quest_dtype dtype, int64_t cols,
+                            int32_t had_block, int32_t bits, float alpha, float outer_trust, int mode,
+                            float *xh_out, void *stream)
+{
+    if (dtype != QUEST_F32 && dtype != QUEST_BF16)
+        return (second && first.rows == 0) || (first.x && first.codes && first.scales) ? QUEST_ERR_DTYPE
+                                                                                      : QUEST_ERR_NULL;
+    const int cb = container_bits(bits);
+    int log2n = 0;
+    quest_status status = check_quant_operand(first, dtype, cols, had_block, &log2n, second != nullptr);
+    if (status == QUEST_OK && second)
+        status = check_quant_operand(*second, dtype, cols, had_block, &log2n, true);
+    if (status == QUEST_ERR_NULL)
+        return status;
+    if (cb == 0)
+        return QUEST_ERR_BITS;
+    if (status != QUEST_OK)
+        return status;
+    if (xh_out && !aligned16(xh_out))
+        return QUEST_ERR_ALIGN;
+    if (second && first.rows != 0 && second->rows != 0 && ((first.mask == nullptr) != (second->mask == nullptr)))
+        return QUEST_ERR_ARG;   // both masks or neither
     if (isnan(alpha) || isinf(alpha) || isnan(outer_trust) || isinf(outer_trust))
         return QUEST_ERR_ARG;
 
@@ -220,21 +248,29 @@ quest_status quantize_entry(const void *x, quest_dtype dtype, int64_t rows, int6
     const double width = mode == quest::kQuantFp4 ? 1.0 / 6.0 : 1.0 / (double)(levels - 1);
 
     quest::QuantizeArgs args;
-    args.x = x;
+    args.x = first.x;
     args.dtype = dtype;
-    args.rows = rows;
+    args.rows = first.rows;
     args.cols = cols;
-    args.ld = ld;
+    args.ld = first.ld;
     args.log2n = log2n;
     args.bits = bits;
     args.cb = cb;
     args.alpha = (float)a;
     args.trust_edge = (float)(a * (1.0 + ot * width));
-    args.codes = codes;
-    args.scales = scales;
-    args.mask = mask;
+    args.codes = first.codes;
+    args.scales = first.scales;
+    args.mask = first.mask;
     args.xh_out = xh_out;
     args.mode = mode;
+    if (second) {
+        args.x2 = second->x;
+        args.rows2 = second->rows;
+        args.ld2 = second->ld;
+        args.codes2 = second->codes;
+        args.scales2 = second->scales;
+        args.mask2 = second->mask;
+    }
     return quest::launch_hadamard_quantize(args, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUEST_OK
                : QUEST_ERR_LAUNCH;
@@ -247,8 +283,19 @@ quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t r
                                      float outer_trust, uint8_t *codes, float *scales,
                                      uint8_t *mask, float *xh_out, void *stream)
 {
-    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, alpha, outer_trust, quest::kQuantRms, codes,
-                          scales, mask, xh_out, stream);
+    return quantize_entry({x, rows, ld, codes, scales, mask}, nullptr, dtype, cols, had_block, bits, alpha,
+                          outer_trust, quest::kQuantRms, xh_out, stream);
+}
+
+quest_status quest_hadamard_quantize_pair(const void *x, int64_t rows_x, int64_t ld_x, uint8_t *codes_x,
+                                          float *scales_x, uint8_t *mask_x, const void *w, int64_t rows_w,
+                                          int64_t ld_w, uint8_t *codes_w, float *scales_w, uint8_t *mask_w,
+                                          quest_dtype dtype, int64_t cols, int32_t had_block, int32_t bits,
+                                          float alpha, float outer_trust, void *stream)
+{
+    const QuantOperand second = {w, rows_w, ld_w, codes_w, scales_w, mask_w};
+    return quantize_entry({x, rows_x, ld_x, codes_x, scales_x, mask_x}, &second, dtype, cols, had_block, bits,
+                          alpha, outer_trust, quest::kQuantRms, nullptr, stream);
 }
 
 quest_status quest_hadamard_quantize_absmax(const void *x, quest_dtype dtype, int64_t rows,
@@ -256,16 +303,16 @@ quest_status quest_hadamard_quantize_absmax(const void *x, quest_dtype dtype, in
                                             uint8_t *codes, float *scales, uint8_t *mask,
                                             float *xh_out, void *stream)
 {
-    return quantize_entry(x, dtype, rows, cols, ld, had_block, bits, 0.0f, -1.0f, quest::kQuantAbsMax, codes,
-                          scales, mask, xh_out, stream);
+    return quantize_entry({x, rows, ld, codes, scales, mask}, nullptr, dtype, cols, had_block, bits, 0.0f, -1.0f,
+                          quest::kQuantAbsMax, xh_out, stream);
 }
 
 quest_status quest_hadamard_quantize_fp4(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
                                          int64_t ld, int32_t had_block, float alpha, uint8_t *codes,
                                          float *scales, uint8_t *mask, float *xh_out, void *stream)
 {
-    return quantize_entry(x, dtype, rows, cols, ld, had_block, 4, alpha, -1.0f, quest::kQuantFp4, codes,
-                          scales, mask, xh_out, stream);
+    return quantize_entry({x, rows, ld, codes, scales, mask}, nullptr, dtype, cols, had_block, 4, alpha, -1.0f,
+                          quest::kQuantFp4, xh_out, stream);
 }
 
 float quest_alpha_star_fp4(void)

@@ -26,6 +26,13 @@ struct QuantizeArgs {
     float *xh_out;     // may be null
     int mode;          // kQuantRms: Eq. 1 grid, clip alpha * rms;  kQuantAbsMax: Eq. 1 grid, clip = largest
                        // |x_h| of the row (alpha, trust_edge unused);  kQuantFp4: E2M1 grid, clip alpha * rms
+    // a second operand with the same dtype, cols, block, grid and clip, quantized by the same launch
+    // (rows2 = 0: none); its mask is given exactly when `mask` is; it has no xh_out
+    const void *x2 = nullptr;
+    int64_t rows2 = 0, ld2 = 0;
+    uint8_t *codes2 = nullptr;
+    float *scales2 = nullptr;
+    uint8_t *mask2 = nullptr;
 };
 
 hipError_t launch_hadamard_quantize(const QuantizeArgs &a, hipStream_t stream);

@@ -110,6 +110,44 @@ def test_fp32_rows_keep_all_24_bits(cols, n):
     assert np.all(np.abs(got["xh"].astype(np.float64) - expect) <= bound)
 
 
+PAIR_CASES = [
+    # rows_x, rows_w, cols, block, bits, dtype, with masks
+    (130, 70, 2048, 2048, 4, "bf16", True), (4099, 1408, 2048, 2048, 4, "bf16", True),
+    (37, 300, 1024, 128, 4, "bf16", False), (70, 33, 5632, 512, 4, "bf16", True), (33, 9, 2048, 2048, 2, "bf16", True),
+    (0, 70, 2048, 2048, 4, "bf16", True), (70, 0, 2048, 2048, 4, "bf16", True), (1, 1, 2048, 2048, 4, "bf16", True),
+    # shapes the one-launch kernel does not cover: the call falls back to one launch per operand
+    (21, 40, 1536, 512, 3, "f32", True), (19, 5, 24, 8, 4, "f32", False), (37, 12, 1024, 1024, 4, "f32", True),
+]
+
+
+@pytest.mark.parametrize("rows_x,rows_w,cols,block,bits,dtype,masks", PAIR_CASES)
+def test_pair_call_equals_two_single_calls(rows_x, rows_w, cols, block, bits, dtype, masks):
+    """Algorithm 1 for x and w in one call (one launch where the matrix-core kernel covers the shape):
+    every output byte equals that of two calls of quest_hadamard_quantize, which the cases above
+    compare with the oracle."""
+    x = synth.outlier_activations(max(rows_x, 1), cols, 0.01, 20.0, seed=rows_x + cols, dtype=dtype)[:rows_x]
+    w = synth.gaussian(max(rows_w, 1), cols, 0.02, seed=rows_w + bits, dtype=dtype)[:rows_w]
+    cb = qo.container_bits(bits)
+    def outputs(rows):
+        return (torch.zeros(rows, cols * cb // 8, dtype=torch.uint8, device=DEV),
+                torch.zeros(rows, dtype=torch.float32, device=DEV),
+                torch.zeros(rows, cols // 8, dtype=torch.uint8, device=DEV) if masks else None)
+    xd, wd = to_device(x), to_device(w)
+    single = [outputs(rows_x), outputs(rows_w)]
+    for t, (c, s, m) in zip((xd, wd), single):
+        if t.shape[0]:
+            q.quest_hadamard_quantize(t, block, bits, codes=c, scales=s, mask=m)
+    pair = [outputs(rows_x), outputs(rows_w)]
+    q.quest_hadamard_quantize_pair(xd, wd, block, bits, x_codes=pair[0][0], x_scales=pair[0][1], x_mask=pair[0][2],
+                                   w_codes=pair[1][0], w_scales=pair[1][1], w_mask=pair[1][2])
+    torch.cuda.synchronize()
+    for a, b in zip(single, pair):
+        for u, v in zip(a, b):
+            if u is not None:
+                assert torch.equal(u.view(torch.uint8) if u.dtype == torch.uint8 else u.view(torch.int32),
+                                   v.view(torch.uint8) if v.dtype == torch.uint8 else v.view(torch.int32))
+
+
 ABSMAX_CASES = [(37, 1024, 128, 4, "bf16"), (130, 2048, 2048, 4, "bf16"), (70, 5632, 512, 4, "bf16"),
                 (33, 2048, 1, 4, "bf16"), (33, 2048, 2048, 2, "bf16"), (33, 2048, 2048, 8, "f32"),
                 (19, 512, 1, 3, "f32"), (21, 1536, 512, 1, "f32"), (4100, 256, 256, 4, "bf16"),

@@ -60,6 +60,26 @@ def test_quantizer_rejects_bad_arguments(lib):
     assert _hq(lib, rows=0) == 0                      # empty input is a no-op, nothing is launched
 
 
+def _pair(lib, x=FAKE, rows_x=4, ld_x=512, codes_x=FAKE, scales_x=FAKE, mask_x=FAKE, w=FAKE, rows_w=4, ld_w=512,
+          codes_w=FAKE, scales_w=FAKE, mask_w=FAKE, dtype=1, cols=512, n=512, bits=4, alpha=0.0, ot=-1.0):
+    return lib.quest_hadamard_quantize_pair(x, rows_x, ld_x, codes_x, scales_x, mask_x, w, rows_w, ld_w, codes_w,
+                                            scales_w, mask_w, dtype, cols, n, bits, alpha, ot, None)
+
+
+def test_pair_quantizer_rejects_bad_arguments(lib):
+    """Either operand of the two-operand call is validated like the operand of the single call."""
+    assert _pair(lib, x=None) == 1 and _pair(lib, w=None) == 1 and _pair(lib, codes_w=None) == 1
+    assert _pair(lib, scales_x=None) == 1 and _pair(lib, scales_w=None) == 1
+    assert _pair(lib, dtype=7) == 6 and _pair(lib, bits=5) == 3
+    assert _pair(lib, rows_w=-1) == 2 and _pair(lib, ld_w=256) == 2 and _pair(lib, cols=508) == 2
+    assert _pair(lib, n=3) == 4 and _pair(lib, cols=768, ld_x=768, ld_w=768, n=512) == 4
+    assert _pair(lib, w=ctypes.c_void_p(0x10008)) == 5 and _pair(lib, mask_w=ctypes.c_void_p(0x10001)) == 5
+    assert _pair(lib, ld_w=516) == 5
+    assert _pair(lib, mask_x=None) == 8 and _pair(lib, mask_w=None) == 8     # both masks or neither
+    assert _pair(lib, alpha=float("nan")) == 8
+    assert _pair(lib, rows_x=0, rows_w=0) == 0 and _pair(lib, rows_x=0, rows_w=0, mask_x=None, mask_w=None) == 0
+
+
 def test_gemm_backward_and_grad_gemm_reject_bad_arguments(lib):
     def gemm(a=FAKE, sa=FAKE, M=0, b=FAKE, sb=FAKE, N=0, K=512, bits=4, y=FAKE, ld=0, acc=None, ws=None, wsb=0):
         return lib.quest_lowbit_gemm(a, sa, M, b, sb, N, K, bits, y, ld, acc, ws, wsb, None)

@@ -48,7 +48,7 @@ def test_traffic_constants_of_the_benchmark_are_those_of_the_committed_profile()
     table = {}
     for key, read, write in re.findall(r"^\| `(\w+)` \| ([0-9.]+) \| ([0-9.]+) \|$", text, flags=re.M):
         table[key] = (float(read), float(write))
-    assert set(table) == set(bench.MEASURED_TRAFFIC_MIB) == set(bench.KERNELS)
+    assert set(table) == set(bench.MEASURED_TRAFFIC_MIB) == set(bench.STEP_KERNELS)
     for key, pair in bench.MEASURED_TRAFFIC_MIB.items():
         assert table[key] == pair, key
 
