@@ -37,11 +37,12 @@ FP4_PEAK_TOPS = 10100.0      # dense FP4 MFMA (--grid fp4)
 
 WORKLOAD = "mlp_up_1p6b"     # the headline: X 16384x2048, W 5632x2048, Hadamard block 2048, b = 4
 WORKLOADS = ("mlp_up_1p6b", "mlp_down_1p6b")   # down: X 16384x5632, W 2048x5632, block 512
-# launches of a step: the integer grid quantizes activations and weights by one call (Algorithm 1 steps
-# 2-5 for both operands), the FP4 variant by two; --only can also launch either operand's quantizer alone
-STEP_KERNELS = ("quantize_xw", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w", "trust_backward_x", "trust_backward_w")
-STEP_KERNELS_FP4 = ("quantize_x", "quantize_w") + STEP_KERNELS[1:]
-KERNELS = ("quantize_x", "quantize_w") + STEP_KERNELS
+# calls of a step: activations and weights are quantized by one call (Algorithm 1 steps 2-5 for both
+# operands), and the two masked inverse transforms that end Algorithm 2 are one call as well; --only
+# can also launch either operand's quantizer or inverse transform alone
+STEP_KERNELS = ("quantize_xw", "lowbit_gemm", "grad_gemm_x", "grad_gemm_w", "trust_backward_xw")
+SINGLE_OPERAND_KERNELS = ("quantize_x", "quantize_w", "trust_backward_x", "trust_backward_w")
+KERNELS = SINGLE_OPERAND_KERNELS + STEP_KERNELS
 FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the forward (--only)
 
 
@@ -52,12 +53,11 @@ FP4_KERNELS = ("quantize_x_fp4", "lowbit_gemm_fp4")   # the FP4 variant of the f
 # of known size that the same run launches.  A gradient matmul is the sum over the kernels of its call.
 MIB = 1 << 20
 MEASURED_TRAFFIC_MIB = {
-    "quantize_xw": (86.2, 27.3),
-    "lowbit_gemm": (128.2, 176.0),
+    "quantize_xw": (86.1, 27.2),
+    "lowbit_gemm": (126.5, 176.0),
     "grad_gemm_x": (555.7, 102.8),
-    "grad_gemm_w": (1013.0, 205.7),
-    "trust_backward_x": (68.1, 64.0),
-    "trust_backward_w": (23.5, 22.0),
+    "grad_gemm_w": (1005.5, 205.7),
+    "trust_backward_xw": (91.5, 86.0),
 }
 
 
@@ -112,17 +112,17 @@ def step_kernels(q, b, cfg, fp4=False):
     M, N, K, n, bits = cfg["M"], cfg["N"], cfg["K"], cfg["had_block"], cfg["bits"]
     if fp4:   # the FP4 variant of the method (Sec. 4.4): E2M1 codes, FP4 matrix instructions
         return [
-            ("quantize_x", lambda: q.quest_hadamard_quantize_fp4(b.x, n, codes=b.x_codes, scales=b.x_scales,
-                                                                 mask=b.x_mask)),
-            ("quantize_w", lambda: q.quest_hadamard_quantize_fp4(b.w, n, codes=b.w_codes, scales=b.w_scales,
-                                                                 mask=b.w_mask)),
+            ("quantize_xw", lambda: q.quest_hadamard_quantize_fp4_pair(b.x, b.w, n, x_codes=b.x_codes,
+                                                                       x_scales=b.x_scales, x_mask=b.x_mask,
+                                                                       w_codes=b.w_codes, w_scales=b.w_scales,
+                                                                       w_mask=b.w_mask)),
             ("lowbit_gemm", lambda: q.quest_lowbit_gemm_fp4(b.x_codes, b.x_scales, b.w_codes, b.w_scales, K, y=b.y)),
             ("grad_gemm_x", lambda: q.quest_grad_gemm_fp4(0, b.dy, b.w_codes, b.w_scales, M, N, K, out=b.g_x,
                                                           workspace=b.ws_gx)),
             ("grad_gemm_w", lambda: q.quest_grad_gemm_fp4(1, b.dy, b.x_codes, b.x_scales, M, N, K, out=b.g_w,
                                                           workspace=b.ws_gw)),
-            ("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx)),
-            ("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw)),
+            ("trust_backward_xw", lambda: q.quest_trust_backward_pair(b.g_x, b.x_mask, b.g_w, b.w_mask, n,
+                                                                      out_x=b.dx, out_w=b.dw)),
         ]
     return [
         ("quantize_xw", lambda: q.quest_hadamard_quantize_pair(b.x, b.w, n, bits, x_codes=b.x_codes,
@@ -135,9 +135,26 @@ def step_kernels(q, b, cfg, fp4=False):
                                                   out=b.g_x, workspace=b.ws_gx)),
         ("grad_gemm_w", lambda: q.quest_grad_gemm(1, b.dy, b.x_codes, b.x_scales, bits, M, N, K,
                                                   out=b.g_w, workspace=b.ws_gw)),
-        ("trust_backward_x", lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx)),
-        ("trust_backward_w", lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw)),
+        ("trust_backward_xw", lambda: q.quest_trust_backward_pair(b.g_x, b.x_mask, b.g_w, b.w_mask, n,
+                                                                  out_x=b.dx, out_w=b.dw)),
     ]
+
+
+def single_operand_kernels(q, b, cfg, fp4=False):
+    """One operand's quantizer or inverse transform by itself (--only): name -> thunk."""
+    n, bits = cfg["had_block"], cfg["bits"]
+    if fp4:
+        def quantize(t, codes, scales, mask):
+            return lambda: q.quest_hadamard_quantize_fp4(t, n, codes=codes, scales=scales, mask=mask)
+    else:
+        def quantize(t, codes, scales, mask):
+            return lambda: q.quest_hadamard_quantize(t, n, bits, codes=codes, scales=scales, mask=mask)
+    return {
+        "quantize_x": quantize(b.x, b.x_codes, b.x_scales, b.x_mask),
+        "quantize_w": quantize(b.w, b.w_codes, b.w_scales, b.w_mask),
+        "trust_backward_x": lambda: q.quest_trust_backward(b.g_x, b.x_mask, n, out=b.dx),
+        "trust_backward_w": lambda: q.quest_trust_backward(b.g_w, b.w_mask, n, out=b.dw),
+    }
 
 
 def cpu_baseline(x_bits, w_bits, dy_bits, cfg):
@@ -450,12 +467,8 @@ def main():
                                                              scales=b.x_scales, mask=b.x_mask)
             if args.only == "lowbit_gemm_fp4":
                 return lambda: q.quest_lowbit_gemm_fp4(b.x_codes, b.x_scales, b.w_codes, b.w_scales, K, y=b.y)
-            if args.only == "quantize_x":
-                return lambda: q.quest_hadamard_quantize(b.x, cfg["had_block"], cfg["bits"], codes=b.x_codes,
-                                                         scales=b.x_scales, mask=b.x_mask)
-            if args.only == "quantize_w":
-                return lambda: q.quest_hadamard_quantize(b.w, cfg["had_block"], cfg["bits"], codes=b.w_codes,
-                                                         scales=b.w_scales, mask=b.w_mask)
+            if args.only in SINGLE_OPERAND_KERNELS:
+                return single_operand_kernels(q, b, cfg, args.grid == "fp4")[args.only]
             return dict(step_kernels(q, b, cfg, args.grid == "fp4"))[args.only]
 
         launches = [chosen(b) for b in sets]
@@ -481,7 +494,7 @@ def main():
     def event_pair():
         return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
-    step_names = STEP_KERNELS_FP4 if args.grid == "fp4" else STEP_KERNELS
+    step_names = STEP_KERNELS
     events = [{k: event_pair() for k in step_names} for _ in range(args.steps)]
     empty = [event_pair() for _ in range(args.steps)]
     scratch_pair = event_pair()
@@ -533,20 +546,16 @@ def main():
 
     grad_x_bytes = 2 * M * N + N * K * cb // 8 + 4 * N + 2 * M * K     # dY + weight codes + scales + G_x
     grad_w_bytes = 2 * M * N + M * K * cb // 8 + 4 * M + 2 * N * K     # dY + activation codes + scales + G_w
-    if "quantize_xw" in ms:
-        rooflines = {"quantize_xw": hbm("quantize_xw", algorithmic_bytes_quantize(M, K, cb) +
-                                        algorithmic_bytes_quantize(N, K, cb))}
-    else:
-        rooflines = {"quantize_x": hbm("quantize_x", algorithmic_bytes_quantize(M, K, cb)),
-                     "quantize_w": hbm("quantize_w", algorithmic_bytes_quantize(N, K, cb))}
-    quantize_ms = sum(v["ms"] for v in rooflines.values())
+    rooflines = {"quantize_xw": hbm("quantize_xw", algorithmic_bytes_quantize(M, K, cb) +
+                                    algorithmic_bytes_quantize(N, K, cb))}
+    quantize_ms = ms["quantize_xw"]
     rooflines.update({
         "lowbit_gemm": mfma("lowbit_gemm", FP4_PEAK_TOPS if args.grid == "fp4" else INT8_PEAK_TOPS,
                             algorithmic_bytes_gemm(M, N, K, cb)),
         "grad_gemm_x": mfma("grad_gemm_x", BF16_PEAK_TFLOPS, grad_x_bytes),
         "grad_gemm_w": mfma("grad_gemm_w", BF16_PEAK_TFLOPS, grad_w_bytes),
-        "trust_backward_x": hbm("trust_backward_x", algorithmic_bytes_backward(M, K)),
-        "trust_backward_w": hbm("trust_backward_w", algorithmic_bytes_backward(N, K)),
+        "trust_backward_xw": hbm("trust_backward_xw", algorithmic_bytes_backward(M, K) +
+                                 algorithmic_bytes_backward(N, K)),
     })
 
     result = {
@@ -563,7 +572,7 @@ def main():
                                f"{cfg['had_block']}, b={cfg['bits']}, forward+backward",
                    "grid": args.grid, "M": M, "N": N, "K": K, "had_block": cfg["had_block"], "bits": cfg["bits"],
                    "buffer_sets": n_sets, "event_gap_us_subtracted": gap_ms * 1e3},
-        "quantizer_GBps": rooflines["quantize_xw" if "quantize_xw" in rooflines else "quantize_x"]["achieved"],
+        "quantizer_GBps": rooflines["quantize_xw"]["achieved"],
         "gemm_TOPS": rooflines["lowbit_gemm"]["achieved"],
         "forward_TOPS": gemm_ops / ((quantize_ms + ms["lowbit_gemm"]) * 1e-3) / 1e12,
         "roofline": dict(rooflines["lowbit_gemm"]),

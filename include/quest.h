@@ -104,8 +104,9 @@ quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t r
  *   codes_*, scales_*   outputs as in quest_hadamard_quantize, one set per operand
  *   mask_x, mask_w      trust bitmaps; give both or neither (QUEST_ERR_ARG otherwise)
  *   dtype .. outer_trust as in quest_hadamard_quantize
- * rows_x or rows_w may be 0 (that operand's pointers may then be NULL).  The outputs are identical, bit for bit, to those of two calls of
- * quest_hadamard_quantize.  Same limits, alignment rules and errors; no xh_out.
+ * rows_x or rows_w may be 0 (that operand's pointers may then be NULL).  The outputs are identical,
+ * bit for bit, to those of two calls of quest_hadamard_quantize.  Same limits, alignment rules and
+ * errors; no xh_out.
  */
 quest_status quest_hadamard_quantize_pair(const void *x, int64_t rows_x, int64_t ld_x, uint8_t *codes_x,
                                           float *scales_x, uint8_t *mask_x, const void *w, int64_t rows_w,
@@ -141,6 +142,17 @@ quest_status quest_hadamard_quantize_absmax(const void *x, quest_dtype dtype, in
 quest_status quest_hadamard_quantize_fp4(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
                                          int64_t ld, int32_t had_block, float alpha, uint8_t *codes,
                                          float *scales, uint8_t *mask, float *xh_out, void *stream);
+
+/*
+ * quest_hadamard_quantize_fp4 for both operands of one layer in one call (Sec. 4.4 on Algorithm 1,
+ * steps 2-5): arguments, single launch, bit-identical outputs and errors as
+ * quest_hadamard_quantize_pair, with the E2M1 grid, codes and scales of quest_hadamard_quantize_fp4.
+ */
+quest_status quest_hadamard_quantize_fp4_pair(const void *x, int64_t rows_x, int64_t ld_x, uint8_t *codes_x,
+                                              float *scales_x, uint8_t *mask_x, const void *w,
+                                              int64_t rows_w, int64_t ld_w, uint8_t *codes_w,
+                                              float *scales_w, uint8_t *mask_w, quest_dtype dtype,
+                                              int64_t cols, int32_t had_block, float alpha, void *stream);
 
 /* Host: the built-in Gaussian-MSE-optimal clip for the scaled E2M1 grid (Sec. 4.4). */
 float quest_alpha_star_fp4(void);
@@ -217,6 +229,25 @@ quest_status quest_lowbit_gemm_fp4(const uint8_t *a_codes, const float *a_scales
 quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint8_t *mask,
                                   int64_t rows, int64_t cols, int32_t had_block, void *out,
                                   quest_dtype out_dtype, void *stream);
+
+/*
+ * Both masked inverse transforms that end Algorithm 2 (the last two steps of its backward pass: the
+ * input gradient from G_x and M_x, the weight gradient from G_w and M_w) in one call.  The two
+ * Hadamard-domain gradients share the row length (the layer's contraction dimension), the block and
+ * the dtypes; where one kernel covers the shape a single launch transforms both row sets (the
+ * weight gradient's rows alone do not fill the chip).
+ *
+ *   g_x, mask_x, out_x   [rows_x, cols], [rows_x, cols/8] or NULL, [rows_x, cols]
+ *   g_w, mask_w, out_w   [rows_w, cols], [rows_w, cols/8] or NULL, [rows_w, cols]
+ *   g_dtype .. out_dtype as in quest_trust_backward
+ * Give both masks or neither (QUEST_ERR_ARG otherwise).  rows_x or rows_w may be 0 (that gradient's
+ * pointers may then be NULL).  The outputs are identical, bit for bit, to those of two calls of
+ * quest_trust_backward; same limits, alignment rules and errors.
+ */
+quest_status quest_trust_backward_pair(const void *g_x, const uint8_t *mask_x, int64_t rows_x, void *out_x,
+                                       const void *g_w, const uint8_t *mask_w, int64_t rows_w, void *out_w,
+                                       quest_dtype g_dtype, int64_t cols, int32_t had_block,
+                                       quest_dtype out_dtype, void *stream);
 
 /*
  * Algorithm 2, the two 16-bit matmuls against a code-packed operand whose value is

@@ -16,8 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquest.so")
 
 QUEST_F32, QUEST_BF16 = 0, 1
-EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_pair", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_alpha_star_fp4",
-           "quest_lowbit_gemm", "quest_lowbit_gemm_workspace_bytes", "quest_lowbit_gemm_static", "quest_lowbit_gemm_fp4", "quest_trust_backward",
+EXPORTS = ("quest_hadamard_quantize", "quest_hadamard_quantize_pair", "quest_hadamard_quantize_absmax", "quest_hadamard_quantize_fp4", "quest_hadamard_quantize_fp4_pair", "quest_alpha_star_fp4",
+           "quest_lowbit_gemm", "quest_lowbit_gemm_workspace_bytes", "quest_lowbit_gemm_static", "quest_lowbit_gemm_fp4", "quest_trust_backward", "quest_trust_backward_pair",
            "quest_grad_gemm", "quest_grad_gemm_workspace_bytes", "quest_grad_gemm_fp4",
            "quest_grad_gemm_fp4_workspace_bytes", "quest_weight_only_gemm", "quest_weight_only_gemm_workspace_bytes",
            "quest_init", "quest_alpha_star", "quest_container_bits", "quest_status_string")
@@ -49,6 +49,9 @@ def load():
                                                        _p, _p, _p, _p, _p]
         lib.quest_hadamard_quantize_fp4.argtypes = [_p, _i32, _i64, _i64, _i64, _i32, _f32, _p, _p, _p, _p, _p]
         lib.quest_hadamard_quantize_fp4.restype = ctypes.c_int
+        lib.quest_hadamard_quantize_fp4_pair.argtypes = [_p, _i64, _i64, _p, _p, _p, _p, _i64, _i64, _p, _p, _p,
+                                                         _i32, _i64, _i32, _f32, _p]
+        lib.quest_hadamard_quantize_fp4_pair.restype = ctypes.c_int
         lib.quest_alpha_star_fp4.argtypes = []
         lib.quest_alpha_star_fp4.restype = _f32
         lib.quest_lowbit_gemm.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _i32, _p, _i64, _p, _p, _i64, _p]
@@ -59,6 +62,8 @@ def load():
         lib.quest_lowbit_gemm_fp4.argtypes = [_p, _p, _i64, _p, _p, _i64, _i64, _p, _i64, _p, _p]
         lib.quest_lowbit_gemm_fp4.restype = ctypes.c_int
         lib.quest_trust_backward.argtypes = [_p, _i32, _p, _i64, _i64, _i32, _p, _i32, _p]
+        lib.quest_trust_backward_pair.argtypes = [_p, _p, _i64, _p, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p]
+        lib.quest_trust_backward_pair.restype = ctypes.c_int
         lib.quest_grad_gemm.argtypes = [_i32, _p, _p, _p, _i32, _i64, _i64, _i64, _p, _p, _i64, _p]
         lib.quest_weight_only_gemm.argtypes = [_p, _p, _p, _i32, _i64, _i64, _i64, _p, _p, _i64, _p]
         lib.quest_grad_gemm_fp4.argtypes = [_i32, _p, _p, _p, _i64, _i64, _i64, _p, _p, _i64, _p]
@@ -164,6 +169,20 @@ def quest_hadamard_quantize_fp4(x: torch.Tensor, had_block: int, alpha: float = 
            "quest_hadamard_quantize_fp4")
 
 
+def quest_hadamard_quantize_fp4_pair(x: torch.Tensor, w: torch.Tensor, had_block: int, alpha: float = 0.0, *,
+                                     x_codes: torch.Tensor, x_scales: torch.Tensor, w_codes: torch.Tensor,
+                                     w_scales: torch.Tensor, x_mask: torch.Tensor | None = None,
+                                     w_mask: torch.Tensor | None = None) -> None:
+    """As quest_hadamard_quantize_pair, rounding to the scaled E2M1 grid."""
+    if x.shape[1] != w.shape[1] or x.dtype != w.dtype:
+        raise ValueError("the two operands of a pair call share the row length and the dtype")
+    _check(load().quest_hadamard_quantize_fp4_pair(_ptr(x), x.shape[0], x.stride(0), _ptr(x_codes),
+                                                   _ptr(x_scales), _ptr(x_mask), _ptr(w), w.shape[0],
+                                                   w.stride(0), _ptr(w_codes), _ptr(w_scales), _ptr(w_mask),
+                                                   _dtype_code(x), x.shape[1], had_block, alpha, _stream()),
+           "quest_hadamard_quantize_fp4_pair")
+
+
 def quest_alpha_star_fp4() -> float:
     return float(load().quest_alpha_star_fp4())
 
@@ -222,6 +241,18 @@ def quest_trust_backward(g: torch.Tensor, mask: torch.Tensor | None, had_block: 
     _check(load().quest_trust_backward(_ptr(g), _dtype_code(g), _ptr(mask), rows, cols, had_block,
                                        _ptr(out), _dtype_code(out), _stream()),
            "quest_trust_backward")
+
+
+def quest_trust_backward_pair(g_x: torch.Tensor, mask_x: torch.Tensor | None, g_w: torch.Tensor,
+                              mask_w: torch.Tensor | None, had_block: int, *, out_x: torch.Tensor,
+                              out_w: torch.Tensor) -> None:
+    """out_x = IHT(mask_x (.) g_x) and out_w = IHT(mask_w (.) g_w) by one call (contiguous, same row length)."""
+    if g_x.shape[1] != g_w.shape[1] or g_x.dtype != g_w.dtype or out_x.dtype != out_w.dtype:
+        raise ValueError("the two gradients of a pair call share the row length and the dtypes")
+    _check(load().quest_trust_backward_pair(_ptr(g_x), _ptr(mask_x), g_x.shape[0], _ptr(out_x), _ptr(g_w),
+                                            _ptr(mask_w), g_w.shape[0], _ptr(out_w), _dtype_code(g_x),
+                                            g_x.shape[1], had_block, _dtype_code(out_x), _stream()),
+           "quest_trust_backward_pair")
 
 
 def quest_grad_gemm_workspace_bytes(which: int, M: int, N: int, K: int) -> int:

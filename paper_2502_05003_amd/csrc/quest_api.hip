@@ -315,6 +315,17 @@ quest_status quest_hadamard_quantize_fp4(const void *x, quest_dtype dtype, int64
                           quest::kQuantFp4, xh_out, stream);
 }
 
+quest_status quest_hadamard_quantize_fp4_pair(const void *x, int64_t rows_x, int64_t ld_x, uint8_t *codes_x,
+                                              float *scales_x, uint8_t *mask_x, const void *w,
+                                              int64_t rows_w, int64_t ld_w, uint8_t *codes_w,
+                                              float *scales_w, uint8_t *mask_w, quest_dtype dtype,
+                                              int64_t cols, int32_t had_block, float alpha, void *stream)
+{
+    const QuantOperand second = {w, rows_w, ld_w, codes_w, scales_w, mask_w};
+    return quantize_entry({x, rows_x, ld_x, codes_x, scales_x, mask_x}, &second, dtype, cols, had_block, 4,
+                          alpha, -1.0f, quest::kQuantFp4, nullptr, stream);
+}
+
 float quest_alpha_star_fp4(void)
 {
     return (float)kAlphaStarFp4;
@@ -431,34 +442,78 @@ quest_status quest_lowbit_gemm_fp4(const uint8_t *a_codes, const float *a_scales
                                                                                        : QUEST_ERR_LAUNCH;
 }
 
-quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint8_t *mask,
-                                  int64_t rows, int64_t cols, int32_t had_block, void *out,
-                                  quest_dtype out_dtype, void *stream)
+namespace {
+
+// One gradient of an inverse-transform call (rows of `cols` elements, its mask or null, its output).
+struct BackwardOperand {
+    const void *g;
+    const uint8_t *mask;
+    int64_t rows;
+    void *out;
+};
+
+// `second` is the other gradient of a pair call (same dtypes, row length and block), or null; a
+// gradient of a pair call that has no rows needs no buffers.
+quest_status trust_backward_entry(const BackwardOperand &first, const BackwardOperand *second, quest_dtype g_dtype,
+                                  int64_t cols, int32_t had_block, quest_dtype out_dtype, void *stream)
 {
-    if (!g || !out)
-        return QUEST_ERR_NULL;
+    const BackwardOperand *operands[2] = {&first, second};
+    for (const BackwardOperand *o : operands)
+        if (o && !(second && o->rows == 0) && (!o->g || !o->out))
+            return QUEST_ERR_NULL;
     if ((g_dtype != QUEST_F32 && g_dtype != QUEST_BF16) ||
         (out_dtype != QUEST_F32 && out_dtype != QUEST_BF16))
         return QUEST_ERR_DTYPE;
     int log2n = 0;
-    const quest_status shape = shape_checks(rows, cols, had_block, &log2n);
-    if (shape != QUEST_OK)
-        return shape;
-    if (!aligned16(g) || !aligned16(out) || (mask && !aligned16(mask)))
-        return QUEST_ERR_ALIGN;
+    for (const BackwardOperand *o : operands) {
+        if (!o)
+            continue;
+        const quest_status shape = shape_checks(o->rows, cols, had_block, &log2n);
+        if (shape != QUEST_OK)
+            return shape;
+        if (!aligned16(o->g) || !aligned16(o->out) || (o->mask && !aligned16(o->mask)))
+            return QUEST_ERR_ALIGN;
+    }
+    if (second && first.rows != 0 && second->rows != 0 && ((first.mask == nullptr) != (second->mask == nullptr)))
+        return QUEST_ERR_ARG;   // both masks or neither
 
     quest::BackwardArgs args;
-    args.g = g;
+    args.g = first.g;
     args.g_dtype = g_dtype;
-    args.mask = mask;
-    args.rows = rows;
+    args.mask = first.mask;
+    args.rows = first.rows;
     args.cols = cols;
     args.log2n = log2n;
-    args.out = out;
+    args.out = first.out;
     args.out_dtype = out_dtype;
+    if (second) {
+        args.g2 = second->g;
+        args.mask2 = second->mask;
+        args.rows2 = second->rows;
+        args.out2 = second->out;
+    }
     return quest::launch_trust_backward(args, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUEST_OK
                : QUEST_ERR_LAUNCH;
+}
+
+}  // namespace
+
+quest_status quest_trust_backward(const void *g, quest_dtype g_dtype, const uint8_t *mask,
+                                  int64_t rows, int64_t cols, int32_t had_block, void *out,
+                                  quest_dtype out_dtype, void *stream)
+{
+    return trust_backward_entry({g, mask, rows, out}, nullptr, g_dtype, cols, had_block, out_dtype, stream);
+}
+
+quest_status quest_trust_backward_pair(const void *g_x, const uint8_t *mask_x, int64_t rows_x, void *out_x,
+                                       const void *g_w, const uint8_t *mask_w, int64_t rows_w, void *out_w,
+                                       quest_dtype g_dtype, int64_t cols, int32_t had_block,
+                                       quest_dtype out_dtype, void *stream)
+{
+    const BackwardOperand second = {g_w, mask_w, rows_w, out_w};
+    return trust_backward_entry({g_x, mask_x, rows_x, out_x}, &second, g_dtype, cols, had_block, out_dtype,
+                                stream);
 }
 
 namespace {

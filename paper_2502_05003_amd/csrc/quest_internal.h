@@ -79,6 +79,12 @@ struct BackwardArgs {
     int log2n;
     void *out;
     quest_dtype out_dtype;
+    // second gradient of the same row length, dtypes and block, served by the same launch where the
+    // matrix-core kernel covers the shape (rows2 = 0: none)
+    const void *g2 = nullptr;
+    const uint8_t *mask2 = nullptr;
+    int64_t rows2 = 0;
+    void *out2 = nullptr;
 };
 
 hipError_t launch_trust_backward(const BackwardArgs &a, hipStream_t stream);

@@ -89,6 +89,22 @@ hipError_t prepare_trust_backward_kernels()
 
 hipError_t launch_trust_backward(const BackwardArgs &a, hipStream_t stream)
 {
+    if (a.rows2 != 0) {
+        // two gradients: one launch where the matrix-core kernel covers the shape, else one after the other
+        if (a.rows != 0 && launch_trust_backward_mfma(a, stream))
+            return hipGetLastError();
+        BackwardArgs first = a, second = a;
+        first.g2 = nullptr;
+        first.rows2 = 0;
+        second.g = a.g2;
+        second.mask = a.mask2;
+        second.rows = a.rows2;
+        second.out = a.out2;
+        second.g2 = nullptr;
+        second.rows2 = 0;
+        const hipError_t err = launch_trust_backward(first, stream);
+        return err != hipSuccess ? err : launch_trust_backward(second, stream);
+    }
     if (a.rows == 0)
         return hipSuccess;
     if (launch_trust_backward_mfma(a, stream))

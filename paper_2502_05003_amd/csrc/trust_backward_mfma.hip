@@ -61,9 +61,13 @@ constexpr int tb_wave_buffer_bytes(int u)
 
 template <int U, int LOG2N, bool WITH_MASK, typename Out = uint16_t>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4)))
-void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ mask, int64_t rows,
-                    int log2n, Out *__restrict__ out)
+void tb_mfma_kernel(const uint16_t *__restrict__ g_a, const uint8_t *__restrict__ mask_a, int64_t rows_a,
+                    int log2n, Out *__restrict__ out_a, const uint16_t *__restrict__ g_b,
+                    const uint8_t *__restrict__ mask_b, int64_t rows_b, Out *__restrict__ out_b)
 {
+    // One launch serves up to two gradients of the same row length (rows_b = 0: one): rows
+    // [0, rows_a) of the launch are the first one's, the rest the second one's.
+    const int64_t rows = rows_a + rows_b;
     constexpr bool kF32Out = sizeof(Out) == 4;
     constexpr int T = (U + 7) / 8;         // tiles of 1024 elements; the last one may be partial
     constexpr int NI = 2 * U;              // elements per lane
@@ -89,7 +93,11 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
     const uint8_t *my_buffer = row_buffers + wave_u * kWaveBuffer;
     const uint32_t my_buffer_addr = lds_address(row_buffers) + (uint32_t)(wave_u * kWaveBuffer);
     const uint32_t piece_offset = (uint32_t)(64 * (lane >> 2) + 16 * ((lane & 3) ^ ((lane >> 4) & 3)));
-    auto request_row = [&](int64_t row) {
+    auto request_row = [&](int64_t row_of_launch) {
+        const bool second = row_of_launch >= rows_a;
+        const int64_t row = second ? row_of_launch - rows_a : row_of_launch;
+        const uint16_t *g = second ? g_b : g_a;
+        const uint8_t *mask = second ? mask_b : mask_a;
         const char *base = reinterpret_cast<const char *>(g + row * cols);
 #pragma unroll
         for (int i = 0; i < kPieces; ++i)
@@ -104,10 +112,10 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
         }
     };
     const int64_t row_stride = (int64_t)gridDim.x * kRowsPerBlock;
-    int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + wave_u;
+    int64_t row_of_launch = (int64_t)blockIdx.x * kRowsPerBlock + wave_u;
     if constexpr (kLdsRow) {
-        if (row < rows)
-            request_row(row);   // before anything else is set up
+        if (row_of_launch < rows)
+            request_row(row_of_launch);   // before anything else is set up
     }
 
     // B operand: rows q = 16 h + 8 s + e of I (x) H_min(n,32), column q' = m, as bf16 +-1 / 0
@@ -133,7 +141,12 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
     const uint32_t pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
 
     int stores_after_request = 0;   // stores issued since the transfers of the row about to be read
-    for (; row < rows; row += row_stride) {
+    for (; row_of_launch < rows; row_of_launch += row_stride) {
+        const bool second = row_of_launch >= rows_a;
+        const int64_t row = second ? row_of_launch - rows_a : row_of_launch;
+        const uint16_t *g = second ? g_b : g_a;
+        const uint8_t *mask = second ? mask_b : mask_a;
+        Out *out = second ? out_b : out_a;
         const uint16_t *src = g + row * cols + 32 * m + 16 * h;
         const uint8_t *mask_src = mask + row * (cols / 8) + 4 * m + 2 * h;
         // the whole row's inputs, out of LDS, before the buffer is handed to the next row
@@ -150,8 +163,8 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
                                            : 0xffffu;
             }
             __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): the buffer has been read, it may be refilled
-            if (row + row_stride < rows)
-                request_row(row + row_stride);
+            if (row_of_launch + row_stride < rows)
+                request_row(row_of_launch + row_stride);
             stores_after_request = kStoresPerRow;
         }
         // tiles that one Hadamard block couples are transformed together, the others one after another
@@ -247,19 +260,21 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g, const uint8_t *__restrict__ 
 template <int U, int LOG2N, typename Out = uint16_t>
 void launch(const BackwardArgs &a, hipStream_t stream)
 {
-    const int64_t blocks_needed = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int64_t blocks_needed = (a.rows + a.rows2 + kRowsPerBlock - 1) / kRowsPerBlock;
     const int64_t max_blocks = kMaxBlocks;
     const dim3 grid((unsigned)(blocks_needed < max_blocks ? blocks_needed : max_blocks));
     const auto *g = static_cast<const uint16_t *>(a.g);
     auto *out = static_cast<Out *>(a.out);
+    const auto *g2 = static_cast<const uint16_t *>(a.g2);
+    auto *out2 = static_cast<Out *>(a.out2);
     constexpr unsigned lds_bytes = tb_rows_through_lds(U, sizeof(Out) == 4) ? kRowsPerBlock * tb_wave_buffer_bytes(U) : 0;
     static_assert(lds_bytes <= 40960, "four workgroups per CU");
     if (a.mask)
         hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, true, Out>), grid, dim3(kThreads), lds_bytes, stream, g,
-                           a.mask, a.rows, a.log2n, out);
+                           a.mask, a.rows, a.log2n, out, g2, a.mask2, a.rows2, out2);
     else
         hipLaunchKernelGGL((tb_mfma_kernel<U, LOG2N, false, Out>), grid, dim3(kThreads), lds_bytes, stream, g,
-                           a.mask, a.rows, a.log2n, out);
+                           a.mask, a.rows, a.log2n, out, g2, a.mask2, a.rows2, out2);
 }
 
 }  // namespace

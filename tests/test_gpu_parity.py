@@ -148,6 +148,36 @@ def test_pair_call_equals_two_single_calls(rows_x, rows_w, cols, block, bits, dt
                                    v.view(torch.uint8) if v.dtype == torch.uint8 else v.view(torch.int32))
 
 
+@pytest.mark.parametrize("rows_x,rows_w,cols,block,dtype,masks",
+                         [(130, 70, 2048, 2048, "bf16", True), (4099, 1408, 2048, 2048, "bf16", True),
+                          (37, 300, 1024, 128, "bf16", False), (70, 33, 5632, 512, "bf16", True),
+                          (0, 70, 2048, 2048, "bf16", True), (70, 0, 2048, 2048, "bf16", True),
+                          (21, 40, 1536, 512, "f32", True)])
+def test_fp4_pair_call_equals_two_single_calls(rows_x, rows_w, cols, block, dtype, masks):
+    """The FP4 quantizer (Sec. 4.4) for x and w in one call: every output byte equals that of two calls
+    of quest_hadamard_quantize_fp4, which test_fp4_quantizer_matches_oracle compares with the oracle."""
+    x = synth.outlier_activations(max(rows_x, 1), cols, 0.01, 20.0, seed=rows_x + cols, dtype=dtype)[:rows_x]
+    w = synth.gaussian(max(rows_w, 1), cols, 0.02, seed=rows_w + 4, dtype=dtype)[:rows_w]
+    def outputs(rows):
+        return (torch.zeros(rows, cols // 2, dtype=torch.uint8, device=DEV),
+                torch.zeros(rows, dtype=torch.float32, device=DEV),
+                torch.zeros(rows, cols // 8, dtype=torch.uint8, device=DEV) if masks else None)
+    xd, wd = to_device(x), to_device(w)
+    single = [outputs(rows_x), outputs(rows_w)]
+    for t, (c, s, m) in zip((xd, wd), single):
+        if t.shape[0]:
+            q.quest_hadamard_quantize_fp4(t, block, codes=c, scales=s, mask=m)
+    pair = [outputs(rows_x), outputs(rows_w)]
+    q.quest_hadamard_quantize_fp4_pair(xd, wd, block, x_codes=pair[0][0], x_scales=pair[0][1], x_mask=pair[0][2],
+                                       w_codes=pair[1][0], w_scales=pair[1][1], w_mask=pair[1][2])
+    torch.cuda.synchronize()
+    for a, b in zip(single, pair):
+        for u, v in zip(a, b):
+            if u is not None:
+                assert torch.equal(u.view(torch.uint8) if u.dtype == torch.uint8 else u.view(torch.int32),
+                                   v.view(torch.uint8) if v.dtype == torch.uint8 else v.view(torch.int32))
+
+
 ABSMAX_CASES = [(37, 1024, 128, 4, "bf16"), (130, 2048, 2048, 4, "bf16"), (70, 5632, 512, 4, "bf16"),
                 (33, 2048, 1, 4, "bf16"), (33, 2048, 2048, 2, "bf16"), (33, 2048, 2048, 8, "f32"),
                 (19, 512, 1, 3, "f32"), (21, 1536, 512, 1, "f32"), (4100, 256, 256, 4, "bf16"),
@@ -509,6 +539,42 @@ def test_trust_backward_matches_oracle(rows, cols, n, gd, od):
     assert torch.all(out == 0)
 
 
+BACK_PAIR_CASES = [
+    # rows_x, rows_w, cols, block, gradient dtype, output dtype, with masks
+    (130, 70, 2048, 2048, "bf16", "bf16", True), (4099, 1408, 2048, 2048, "bf16", "bf16", True),
+    (5003, 3001, 1024, 128, "bf16", "f32", True), (37, 300, 1024, 128, "bf16", "bf16", False),
+    (70, 33, 5632, 512, "bf16", "bf16", True), (9, 33, 4096, 4096, "bf16", "f32", True),
+    (0, 70, 2048, 2048, "bf16", "bf16", True), (70, 0, 2048, 2048, "bf16", "bf16", True),
+    (1, 1, 2048, 2048, "bf16", "bf16", True),
+    # shapes the one-launch kernel does not cover: the call falls back to one launch per gradient
+    (21, 40, 1536, 512, "f32", "f32", True), (19, 5, 24, 8, "f32", "bf16", False), (37, 12, 1024, 1024, "f32", "bf16", True),
+]
+
+
+@pytest.mark.parametrize("rows_x,rows_w,cols,block,gd,od,masks", BACK_PAIR_CASES)
+def test_backward_pair_call_equals_two_single_calls(rows_x, rows_w, cols, block, gd, od, masks):
+    """The two masked inverse transforms that end Algorithm 2 in one call (one launch where the
+    matrix-core kernel covers the shape): every output bit equals that of two calls of
+    quest_trust_backward, which the cases above compare with the oracle."""
+    rng = np.random.default_rng(rows_x + 3 * rows_w + cols)
+    grads = [to_device(synth.gaussian(max(r, 1), cols, 0.03, seed=r + cols + i, dtype=gd)[:r])
+             for i, r in enumerate((rows_x, rows_w))]
+    bitmaps = [to_device(rng.integers(0, 256, size=(r, cols // 8), dtype=np.uint8) |
+                         rng.integers(0, 256, size=(r, cols // 8), dtype=np.uint8)) if masks else None
+               for r in (rows_x, rows_w)]
+    out_type = torch.bfloat16 if od == "bf16" else torch.float32
+    single = [torch.full((r, cols), 7.0, dtype=out_type, device=DEV) for r in (rows_x, rows_w)]
+    for g, m, o in zip(grads, bitmaps, single):
+        if g.shape[0]:
+            q.quest_trust_backward(g, m, block, out=o)
+    pair = [torch.full((r, cols), 9.0, dtype=out_type, device=DEV) for r in (rows_x, rows_w)]
+    q.quest_trust_backward_pair(grads[0], bitmaps[0], grads[1], bitmaps[1], block, out_x=pair[0], out_w=pair[1])
+    torch.cuda.synchronize()
+    for a, b in zip(single, pair):
+        assert torch.equal(a.view(torch.int16 if od == "bf16" else torch.int32),
+                           b.view(torch.int16 if od == "bf16" else torch.int32))
+
+
 def test_trust_backward_full_size_headline_shape():
     """16384 x 2048 bf16 gradient, block 2048, mask from the quantizer: whole tensor against the oracle."""
     x, _, cfg = synth.make_config("mlp_up_1p6b", seed=0)
@@ -778,11 +844,12 @@ def test_full_linear_forward_backward_small():
 
 
 def test_whole_step_replayed_from_a_graph_matches_eager_launches():
-    """The step's seven calls captured into one HIP graph with no eager call before the capture (only
-    quest_init), then a larger gradient matmul run eagerly with scratch of its own, then replays on
-    new input contents with eager work and synchronisations between them: every replay must
-    reproduce, bit for bit, what the same calls give when launched one by one.  Shapes that split
-    tiles (second launch, partial tiles in the caller's workspace)."""
+    """The step's five calls (both operands quantized by one call, both inverse transforms by one
+    call) captured into one HIP graph with no eager call before the capture (only quest_init), then
+    a larger gradient matmul run eagerly with scratch of its own, then replays on new input contents
+    with eager work and synchronisations between them: every replay must reproduce, bit for bit,
+    what the step gives when launched eagerly as seven single-operand calls.  Shapes that split tiles
+    (second launch, partial tiles in the caller's workspace)."""
     M, N, K, bits, n = 768, 8192, 512, 4, 512
     dev = torch.device(DEV)
     q.quest_init()
@@ -800,14 +867,21 @@ def test_whole_step_replayed_from_a_graph_matches_eager_launches():
     w = torch.empty(N, K, dtype=torch.bfloat16, device=dev)
     dy = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
 
-    def step(b, scratch):
-        q.quest_hadamard_quantize(x, n, bits, codes=b["xc"], scales=b["xs"], mask=b["xm"])
-        q.quest_hadamard_quantize(w, n, bits, codes=b["wc"], scales=b["ws"], mask=b["wm"])
+    def step(b, scratch, paired):
+        if paired:
+            q.quest_hadamard_quantize_pair(x, w, n, bits, x_codes=b["xc"], x_scales=b["xs"], x_mask=b["xm"],
+                                           w_codes=b["wc"], w_scales=b["ws"], w_mask=b["wm"])
+        else:
+            q.quest_hadamard_quantize(x, n, bits, codes=b["xc"], scales=b["xs"], mask=b["xm"])
+            q.quest_hadamard_quantize(w, n, bits, codes=b["wc"], scales=b["ws"], mask=b["wm"])
         q.quest_lowbit_gemm(b["xc"], b["xs"], b["wc"], b["ws"], K, bits, y=b["y"])
         q.quest_grad_gemm(0, dy, b["wc"], b["ws"], bits, M, N, K, out=b["gx"], workspace=scratch[0])
         q.quest_grad_gemm(1, dy, b["xc"], b["xs"], bits, M, N, K, out=b["gw"], workspace=scratch[1])
-        q.quest_trust_backward(b["gx"], b["xm"], n, out=b["dx"])
-        q.quest_trust_backward(b["gw"], b["wm"], n, out=b["dw"])
+        if paired:
+            q.quest_trust_backward_pair(b["gx"], b["xm"], b["gw"], b["wm"], n, out_x=b["dx"], out_w=b["dw"])
+        else:
+            q.quest_trust_backward(b["gx"], b["xm"], n, out=b["dx"])
+            q.quest_trust_backward(b["gw"], b["wm"], n, out=b["dw"])
 
     def fill(seed):
         x.copy_(to_device(synth.outlier_activations(M, K, 0.01, 20.0, seed, "bf16")).view(torch.bfloat16))
@@ -823,7 +897,7 @@ def test_whole_step_replayed_from_a_graph_matches_eager_launches():
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(stream):
         with torch.cuda.graph(graph, stream=stream):
-            step(captured, captured_scratch)
+            step(captured, captured_scratch, paired=True)
     torch.cuda.synchronize()
     # a larger shape, eagerly, after the capture: it brings its own scratch and touches nothing of the graph's
     M2, N2, K2 = 2048, 8192, 1024
@@ -835,7 +909,7 @@ def test_whole_step_replayed_from_a_graph_matches_eager_launches():
     torch.cuda.synchronize()
     for seed in (10, 20, 30):
         fill(seed)
-        step(eager, eager_scratch)
+        step(eager, eager_scratch, paired=False)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()

@@ -80,6 +80,29 @@ def test_pair_quantizer_rejects_bad_arguments(lib):
     assert _pair(lib, rows_x=0, rows_w=0) == 0 and _pair(lib, rows_x=0, rows_w=0, mask_x=None, mask_w=None) == 0
 
 
+def test_fp4_pair_quantizer_and_backward_pair_reject_bad_arguments(lib):
+    """The other two-operand calls validate either operand like their single calls do."""
+    def fp4(x=FAKE, rows_x=4, ld_x=512, codes_x=FAKE, scales_x=FAKE, mask_x=FAKE, w=FAKE, rows_w=4, ld_w=512,
+            codes_w=FAKE, scales_w=FAKE, mask_w=FAKE, dtype=1, cols=512, n=512, alpha=0.0):
+        return lib.quest_hadamard_quantize_fp4_pair(x, rows_x, ld_x, codes_x, scales_x, mask_x, w, rows_w, ld_w,
+                                                    codes_w, scales_w, mask_w, dtype, cols, n, alpha, None)
+    assert fp4(x=None) == 1 and fp4(scales_w=None) == 1 and fp4(dtype=7) == 6
+    assert fp4(rows_x=-1) == 2 and fp4(ld_x=256) == 2 and fp4(n=3) == 4
+    assert fp4(codes_w=ctypes.c_void_p(0x10008)) == 5 and fp4(mask_w=None) == 8 and fp4(alpha=float("inf")) == 8
+    assert fp4(rows_x=0, rows_w=0) == 0 and fp4(rows_x=0, rows_w=0, x=None, codes_x=None, scales_x=None) == 0
+
+    def back(g_x=FAKE, mask_x=FAKE, rows_x=4, out_x=FAKE, g_w=FAKE, mask_w=FAKE, rows_w=4, out_w=FAKE, gd=1,
+             cols=512, n=512, od=1):
+        return lib.quest_trust_backward_pair(g_x, mask_x, rows_x, out_x, g_w, mask_w, rows_w, out_w, gd, cols, n,
+                                             od, None)
+    assert back(g_x=None) == 1 and back(out_w=None) == 1 and back(gd=3) == 6 and back(od=-1) == 6
+    assert back(cols=20) == 2 and back(rows_w=-1) == 2 and back(n=48) == 4
+    assert back(out_w=ctypes.c_void_p(0x10002)) == 5 and back(mask_x=ctypes.c_void_p(0x10001)) == 5
+    assert back(mask_x=None) == 8 and back(mask_w=None) == 8                  # both masks or neither
+    assert back(rows_x=0, rows_w=0) == 0 and back(rows_x=0, rows_w=0, g_w=None, out_w=None) == 0
+    assert back(rows_x=0, rows_w=0, mask_x=None) == 0                         # an empty gradient's mask is not looked at
+
+
 def test_gemm_backward_and_grad_gemm_reject_bad_arguments(lib):
     def gemm(a=FAKE, sa=FAKE, M=0, b=FAKE, sb=FAKE, N=0, K=512, bits=4, y=FAKE, ld=0, acc=None, ws=None, wsb=0):
         return lib.quest_lowbit_gemm(a, sa, M, b, sb, N, K, bits, y, ld, acc, ws, wsb, None)
