@@ -786,6 +786,44 @@ def test_split_tiles_are_summed_in_a_fixed_order():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[1], outs[2])
 
 
+@pytest.mark.parametrize("which,M,N,K", [(1, 8192, 2560, 2304), (0, 2560, 8192, 2304), (1, 4096, 2368, 2560)])
+def test_split_tiles_mid_size_alternating_inputs(which, M, N, K):
+    """Ninety-odd tiles with a long contraction over 256 CUs: every tile is shared by three or four
+    workgroups (the benchmark's weight-gradient situation at a size whose whole output can be
+    checked).  The whole output against the fp64 product of the same 16-bit operands, sampled rows
+    against the oracle, and runs on alternating inputs over one workspace bit-identical (a stale
+    partial tile from the call before would show)."""
+    bits, n = 4, 256
+    src_rows, out_rows = (N, M) if which == 0 else (M, N)
+    ws = grad_ws(which, M, N, K)
+    results = {}
+    for rep, seed in enumerate((5, 6, 5, 6)):
+        src = synth.gaussian(src_rows, K, 1.0 if which else 0.02, seed, "bf16")
+        dy = synth.upstream_gradient(M, N, seed + 10, "bf16")
+        gq = gpu_quantize(src, n, bits, want_xh=False, want_mask=False)
+        out = torch.empty(out_rows, K, dtype=torch.bfloat16, device=DEV)
+        q.quest_grad_gemm(which, to_device(dy), gq["dev"]["codes"], gq["dev"]["scales"], bits, M, N, K, out=out,
+                          workspace=ws)
+        torch.cuda.synchronize()
+        if seed in results:
+            assert torch.equal(results[seed], out), (rep, seed)
+            continue
+        results[seed] = out
+        u = qo.unpack_odd(gq["codes"], K, bits)
+        q16 = qo.widen(synth.to_bf16_bits(gq["scales"][:, None] * u.astype(np.float32)))
+        dyd = qo.widen(dy)
+        left = dyd if which == 0 else dyd.T
+        mirror = left @ q16
+        spread = np.sqrt((left ** 2) @ (q16 ** 2))
+        got = to_host_f64(out)
+        assert np.all(np.abs(got - mirror) <= BF16_HALF_ULP * 1.001 * np.abs(mirror) + 2e-5 * spread)
+        rows = np.sort(np.random.default_rng(seed).choice(out_rows, size=8, replace=False))
+        rows[0], rows[-1] = 0, out_rows - 1
+        s = gq["scales"].astype(np.float64)
+        ref = qo.grad_input(dyd[rows], u, s) if which == 0 else qo.grad_weight(np.ascontiguousarray(dyd[:, rows]), u, s)
+        assert np.all(np.abs(got[rows] - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread[rows])
+
+
 @pytest.mark.parametrize("which,M,N,K", [(0, 512, 256, 512), (1, 512, 256, 512), (0, 768, 8192, 512),
                                           (1, 8192, 768, 512),
                                           (0, 640, 1664, 384), (1, 1664, 640, 896)])   # outputs ending inside a tile
