@@ -3,8 +3,8 @@
 
 A step is one pass of the whole path over one batch of the 1.6B-model MLP up-projection
 (d = 2048, ffn 5632, 16384 tokens; Algorithm 1 + Algorithm 2 of arXiv 2502.05003):
-    quantize X, quantize W, low-bit GEMM with bf16 epilogue,
-    two 16-bit gradient GEMMs, two trust-masked inverse transforms.
+    quantize X and W (one call, one launch), low-bit GEMM with bf16 epilogue,
+    two 16-bit gradient GEMMs, both trust-masked inverse transforms (one call, one launch).
 Inputs are synthetic, seeded and resident in HBM before the timed region.  Prints ONE JSON line.
 
 After the timed region (never inside it) the same run also measures, unless --no-extra:

@@ -178,6 +178,32 @@ def test_fp4_pair_call_equals_two_single_calls(rows_x, rows_w, cols, block, dtyp
                                    v.view(torch.uint8) if v.dtype == torch.uint8 else v.view(torch.int32))
 
 
+def test_pair_call_on_strided_operands():
+    """Row strides above the row length, a different one per operand: the one-launch kernel takes each
+    operand's own stride (a slice of a wider activation buffer next to contiguous weights)."""
+    cols, block, bits = 2048, 2048, 4
+    wide_x = to_device(synth.outlier_activations(300, cols + 64, 0.01, 20.0, seed=3, dtype="bf16"))
+    wide_w = to_device(synth.gaussian(77, cols + 512, 0.02, seed=4, dtype="bf16"))
+    xd, wd = wide_x[:, :cols], wide_w[:, :cols]
+    assert xd.stride(0) == cols + 64 and wd.stride(0) == cols + 512
+
+    def outputs(rows):
+        return (torch.zeros(rows, cols // 2, dtype=torch.uint8, device=DEV),
+                torch.zeros(rows, dtype=torch.float32, device=DEV),
+                torch.zeros(rows, cols // 8, dtype=torch.uint8, device=DEV))
+    single = [outputs(300), outputs(77)]
+    for t, (c, s, m) in zip((xd.contiguous(), wd.contiguous()), single):
+        q.quest_hadamard_quantize(t, block, bits, codes=c, scales=s, mask=m)
+    pair = [outputs(300), outputs(77)]
+    q.quest_hadamard_quantize_pair(xd, wd, block, bits, x_codes=pair[0][0], x_scales=pair[0][1], x_mask=pair[0][2],
+                                   w_codes=pair[1][0], w_scales=pair[1][1], w_mask=pair[1][2])
+    torch.cuda.synchronize()
+    for a, b in zip(single, pair):
+        for u, v in zip(a, b):
+            assert torch.equal(u.view(torch.uint8) if u.dtype == torch.uint8 else u.view(torch.int32),
+                               v.view(torch.uint8) if v.dtype == torch.uint8 else v.view(torch.int32))
+
+
 ABSMAX_CASES = [(37, 1024, 128, 4, "bf16"), (130, 2048, 2048, 4, "bf16"), (70, 5632, 512, 4, "bf16"),
                 (33, 2048, 1, 4, "bf16"), (33, 2048, 2048, 2, "bf16"), (33, 2048, 2048, 8, "f32"),
                 (19, 512, 1, 3, "f32"), (21, 1536, 512, 1, "f32"), (4100, 256, 256, 4, "bf16"),
