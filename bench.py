@@ -343,6 +343,19 @@ def extra_config_100m(torch, q, synth, dev, streaming):
             "us": us, "GBps": gbs, "frac": gbs / HBM_PEAK_GBS, "frac_of_streaming": gbs / streaming,
             "algorithmic": nbytes,
             "relative_error": relative_error(torch, q, xs[0], codes[0], scales[0], block, bits)}
+    # both operands of the layer by one call (the weights are quantized anew in every training step)
+    ws = [w.clone() for _ in range(n_sets)]
+    w_masks = torch.empty(N, K // 8, dtype=torch.uint8, device=dev)
+    pair_bytes = nbytes + algorithmic_bytes_quantize(N, K)
+    out["quantize_xw"] = {}
+    for block in (128, 1024):
+        us = time_launches(torch, [(lambda i=i: q.quest_hadamard_quantize_pair(
+            xs[i], ws[i], block, bits, x_codes=codes[i], x_scales=scales[i], x_mask=masks[i], w_codes=w_codes,
+            w_scales=w_scales, w_mask=w_masks)) for i in range(n_sets)])
+        gbs = pair_bytes / (us * 1e-6) / 1e9
+        out["quantize_xw"][f"block_{block}"] = {"us": us, "GBps": gbs, "frac": gbs / HBM_PEAK_GBS,
+                                                "frac_of_streaming": gbs / streaming, "algorithmic": pair_bytes}
+    del ws
     q.quest_hadamard_quantize(w, 1024, bits, codes=w_codes, scales=w_scales)
     for i in range(n_sets):
         q.quest_hadamard_quantize(xs[i], 1024, bits, codes=codes[i], scales=scales[i])
