@@ -83,7 +83,9 @@ typedef enum { QUEST_F32 = 0, QUEST_BF16 = 1 } quest_dtype;
  *   scales      out [rows] fp32, s = alpha rms / (L - 1)
  *   mask        out [rows, cols/8] bitmap, or NULL when no backward pass will follow
  *   xh_out      out [rows, cols] fp32 Hadamard-domain values x_h, or NULL (NULL in production)
- * Rows whose entries are all zero give s = 0, c = L/2 everywhere and an all-ones mask.
+ * Rows whose entries are all zero give s = 0, c = L/2 everywhere and an all-ones mask.  A row that
+ * holds an infinity or a NaN gets a non-finite scale and unspecified codes and mask bits; other
+ * rows are not affected (the paper defines the projection for finite inputs only).
  * x, codes, mask, xh_out must be 16-byte aligned and ld * sizeof(element) a multiple of 16.
  */
 quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,

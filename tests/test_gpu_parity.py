@@ -248,6 +248,38 @@ def test_transform_and_gaussian_clip_each_reduce_the_error():
     assert err[(2048, False)] < err[(1, False)]
 
 
+@pytest.mark.parametrize("cols,n,dtype", [(2048, 2048, "bf16"), (5632, 512, "bf16"), (1536, 512, "f32"),
+                                          (2048, 2048, "f32")])
+def test_non_finite_rows_stay_in_their_rows(cols, n, dtype):
+    """A row that holds an infinity or a NaN gets a non-finite scale (its codes are unspecified) and
+    leaves every other row's outputs as they are without it; the masked inverse transform likewise
+    keeps a non-finite gradient row to itself.  (Matrix-core kernels and the general ones.)"""
+    rows = 41
+    x = synth.outlier_activations(rows, cols, 0.01, 20.0, seed=cols, dtype=dtype)
+    clean = gpu_quantize(x, n, 4, want_xh=False)
+    bad = x.copy()
+    inf_bits, nan_bits = (0x7F80, 0x7FC0) if dtype == "bf16" else (np.float32(np.inf), np.float32(np.nan))
+    bad[3, 17] = inf_bits
+    bad[29, cols - 1] = nan_bits
+    got = gpu_quantize(bad, n, 4, want_xh=False)
+    assert not np.isfinite(got["scales"][3]) and not np.isfinite(got["scales"][29])
+    keep = np.ones(rows, dtype=bool)
+    keep[[3, 29]] = False
+    for name in ("codes", "scales", "mask"):
+        assert np.array_equal(got[name][keep], clean[name][keep]), name
+    if dtype == "bf16":
+        g = synth.gaussian(rows, cols, 0.03, seed=1, dtype="bf16")
+        out_clean = torch.empty(rows, cols, dtype=torch.bfloat16, device=DEV)
+        q.quest_trust_backward(to_device(g), clean["dev"]["mask"], n, out=out_clean)
+        g_bad = g.copy()
+        g_bad[3, 17], g_bad[29, cols - 1] = inf_bits, nan_bits
+        out_bad = torch.empty(rows, cols, dtype=torch.bfloat16, device=DEV)
+        q.quest_trust_backward(to_device(g_bad), clean["dev"]["mask"], n, out=out_bad)
+        torch.cuda.synchronize()
+        keep_t = torch.from_numpy(keep).to(DEV)
+        assert torch.equal(out_bad[keep_t].view(torch.int16), out_clean[keep_t].view(torch.int16))
+
+
 FP4_CASES = [(37, 1024, 128, "bf16", 0.0), (130, 2048, 2048, "bf16", 0.0), (70, 5632, 512, "bf16", 0.0),
              (33, 2048, 1, "bf16", 2.0), (19, 512, 64, "f32", 0.0), (4100, 256, 256, "bf16", 3.5)]
 
