@@ -85,7 +85,8 @@ typedef enum { QUEST_F32 = 0, QUEST_BF16 = 1 } quest_dtype;
  *   xh_out      out [rows, cols] fp32 Hadamard-domain values x_h, or NULL (NULL in production)
  * Rows whose entries are all zero give s = 0, c = L/2 everywhere and an all-ones mask.  A row that
  * holds an infinity or a NaN gets a non-finite scale and unspecified codes and mask bits; other
- * rows are not affected (the paper defines the projection for finite inputs only).
+ * rows are not affected (the paper defines the projection for finite inputs only; the row's sum of
+ * squares is formed in fp32, so a row whose sum of squares exceeds the fp32 range counts as such).
  * x, codes, mask, xh_out must be 16-byte aligned and ld * sizeof(element) a multiple of 16.
  */
 quest_status quest_hadamard_quantize(const void *x, quest_dtype dtype, int64_t rows, int64_t cols,
