@@ -190,9 +190,9 @@ void hq_mfma_kernel(
     const uint32_t my_buffer_addr = lds_address(row_buffers) + (uint32_t)wave_u * (256u * U);
     const uint32_t piece_offset = (uint32_t)(64 * (lane >> 2) + 16 * ((lane & 3) ^ ((lane >> 4) & 3)));
     auto request_row = [&](int64_t row_of_launch) {
-        const bool second = row_of_launch >= rows_a;
+        const bool from_b = row_of_launch >= rows_a;
         const char *base = reinterpret_cast<const char *>(
-            second ? reinterpret_cast<const uint16_t *>(x_b) + (row_of_launch - rows_a) * ld_b
+            from_b ? reinterpret_cast<const uint16_t *>(x_b) + (row_of_launch - rows_a) * ld_b
                    : reinterpret_cast<const uint16_t *>(x_a) + row_of_launch * ld_a);
 #pragma unroll
         for (int i = 0; i < kPieces; ++i)
@@ -298,13 +298,13 @@ void hq_mfma_kernel(
     int stores_after_request = 0;   // stores issued since the transfers of the row about to be read
     for (; row_of_launch < rows; row_of_launch += row_stride) {
         // this row's operand (wave-uniform)
-        const bool second = row_of_launch >= rows_a;
-        const int64_t row = second ? row_of_launch - rows_a : row_of_launch;
-        const In *x = second ? x_b : x_a;
-        const int64_t ld = second ? ld_b : ld_a;
-        uint8_t *codes = second ? codes_b : codes_a;
-        float *scales = second ? scales_b : scales_a;
-        uint8_t *mask = second ? mask_b : mask_a;
+        const bool from_b = row_of_launch >= rows_a;
+        const int64_t row = from_b ? row_of_launch - rows_a : row_of_launch;
+        const In *x = from_b ? x_b : x_a;
+        const int64_t ld = from_b ? ld_b : ld_a;
+        uint8_t *codes = from_b ? codes_b : codes_a;
+        float *scales = from_b ? scales_b : scales_a;
+        uint8_t *mask = from_b ? mask_b : mask_a;
         RawRow raw;
         if constexpr (kLdsRow) {
             wait_vmcnt_upto(stores_after_request);   // this row has landed
@@ -429,15 +429,15 @@ void hq_mfma_kernel(
                         z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, bmat[0], z, 0, 0, 0);
                         z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, bmat[1], z, 0, 0, 0);
                     } else if constexpr (kFold) {
-                        v8bf f0, f1, g0, g1;
-                        __builtin_memcpy(&f0, &raw.a[0][0], 16);
-                        __builtin_memcpy(&f1, &raw.a[0][1], 16);
-                        __builtin_memcpy(&g0, &raw.a[1][0], 16);
-                        __builtin_memcpy(&g1, &raw.a[1][1], 16);
-                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, bmat[0], z, 0, 0, 0);
-                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, bmat[1], z, 0, 0, 0);
-                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g0, u == 0 ? bmat[0] : bneg[0], z, 0, 0, 0);
-                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g1, u == 0 ? bmat[1] : bneg[1], z, 0, 0, 0);
+                        v8bf tile0_lo, tile0_hi, tile1_lo, tile1_hi;
+                        __builtin_memcpy(&tile0_lo, &raw.a[0][0], 16);
+                        __builtin_memcpy(&tile0_hi, &raw.a[0][1], 16);
+                        __builtin_memcpy(&tile1_lo, &raw.a[1][0], 16);
+                        __builtin_memcpy(&tile1_hi, &raw.a[1][1], 16);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile0_lo, bmat[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile0_hi, bmat[1], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile1_lo, u == 0 ? bmat[0] : bneg[0], z, 0, 0, 0);
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile1_hi, u == 0 ? bmat[1] : bneg[1], z, 0, 0, 0);
                     } else {
                         v8bf f0, f1;
                         __builtin_memcpy(&f0, &raw.a[t][0], 16);
@@ -477,7 +477,7 @@ void hq_mfma_kernel(
             const int first = 16 * g0;
             const int count_i = (NI - first) < kGroupI ? (NI - first) : kGroupI;
 
-            if (xh_out && !second) {   // debug output of the first operand only
+            if (xh_out && !from_b) {   // debug output of the first operand only
                 float *dst = xh_out + row * cols + lane;   // element = lane + 64 iota
 #pragma unroll
                 for (int i = 0; i < kGroupI; ++i)

@@ -94,10 +94,10 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g_a, const uint8_t *__restrict_
     const uint32_t my_buffer_addr = lds_address(row_buffers) + (uint32_t)(wave_u * kWaveBuffer);
     const uint32_t piece_offset = (uint32_t)(64 * (lane >> 2) + 16 * ((lane & 3) ^ ((lane >> 4) & 3)));
     auto request_row = [&](int64_t row_of_launch) {
-        const bool second = row_of_launch >= rows_a;
-        const int64_t row = second ? row_of_launch - rows_a : row_of_launch;
-        const uint16_t *g = second ? g_b : g_a;
-        const uint8_t *mask = second ? mask_b : mask_a;
+        const bool from_b = row_of_launch >= rows_a;
+        const int64_t row = from_b ? row_of_launch - rows_a : row_of_launch;
+        const uint16_t *g = from_b ? g_b : g_a;
+        const uint8_t *mask = from_b ? mask_b : mask_a;
         const char *base = reinterpret_cast<const char *>(g + row * cols);
 #pragma unroll
         for (int i = 0; i < kPieces; ++i)
@@ -142,11 +142,11 @@ void tb_mfma_kernel(const uint16_t *__restrict__ g_a, const uint8_t *__restrict_
 
     int stores_after_request = 0;   // stores issued since the transfers of the row about to be read
     for (; row_of_launch < rows; row_of_launch += row_stride) {
-        const bool second = row_of_launch >= rows_a;
-        const int64_t row = second ? row_of_launch - rows_a : row_of_launch;
-        const uint16_t *g = second ? g_b : g_a;
-        const uint8_t *mask = second ? mask_b : mask_a;
-        Out *out = second ? out_b : out_a;
+        const bool from_b = row_of_launch >= rows_a;
+        const int64_t row = from_b ? row_of_launch - rows_a : row_of_launch;
+        const uint16_t *g = from_b ? g_b : g_a;
+        const uint8_t *mask = from_b ? mask_b : mask_a;
+        Out *out = from_b ? out_b : out_a;
         const uint16_t *src = g + row * cols + 32 * m + 16 * h;
         const uint8_t *mask_src = mask + row * (cols / 8) + 4 * m + 2 * h;
         // the whole row's inputs, out of LDS, before the buffer is handed to the next row
