@@ -789,6 +789,76 @@ def test_down_projection_full_size():
     assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
 
 
+@pytest.mark.parametrize("name", ["mlp_up_7b", "mlp_down_7b"])
+def test_7b_layers_whole_step_sampled(name):
+    """The MLP layers of the 7B model of the paper's per-layer runtime figure (hidden 4096 with one
+    block of 4096, MLP width 11008 = 43 x 256 in blocks of 256), 8192 tokens: the step through the
+    two-operand calls at these launch shapes (wide-K forward kernel, rows that end inside a tile of the
+    quantizer), sampled rows of every stage against the oracle."""
+    x, w, cfg = synth.make_config(name, seed=0, rows=8192)
+    K, bits, n = cfg["K"], cfg["bits"], cfg["had_block"]
+    M, N = x.shape[0], w.shape[0]
+    dev = torch.device(DEV)
+    u8, f32, b16 = torch.uint8, torch.float32, torch.bfloat16
+    xc, xs, xm = (torch.empty(M, K // 2, dtype=u8, device=dev), torch.empty(M, dtype=f32, device=dev),
+                  torch.empty(M, K // 8, dtype=u8, device=dev))
+    wc, ws, wm = (torch.empty(N, K // 2, dtype=u8, device=dev), torch.empty(N, dtype=f32, device=dev),
+                  torch.empty(N, K // 8, dtype=u8, device=dev))
+    q.quest_hadamard_quantize_pair(to_device(x), to_device(w), n, bits, x_codes=xc, x_scales=xs, x_mask=xm,
+                                   w_codes=wc, w_scales=ws, w_mask=wm)
+    y = torch.empty(M, N, dtype=b16, device=dev)
+    q.quest_lowbit_gemm(xc, xs, wc, ws, K, bits, y=y)
+    dy = synth.upstream_gradient(M, N, 5, "bf16")
+    dyd = to_device(dy)
+    g_x, g_w = torch.empty(M, K, dtype=b16, device=dev), torch.empty(N, K, dtype=b16, device=dev)
+    q.quest_grad_gemm(0, dyd, wc, ws, bits, M, N, K, out=g_x, workspace=grad_ws(0, M, N, K))
+    q.quest_grad_gemm(1, dyd, xc, xs, bits, M, N, K, out=g_w, workspace=grad_ws(1, M, N, K))
+    dx, dw = torch.empty_like(g_x), torch.empty_like(g_w)
+    q.quest_trust_backward_pair(g_x, xm, g_w, wm, n, out_x=dx, out_w=dw)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(11)
+    rows = np.sort(rng.choice(M, size=16, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    w_rows = np.sort(rng.choice(N, size=8, replace=False))
+    w_rows[0], w_rows[-1] = 0, N - 1
+    rows_d, w_rows_d = torch.from_numpy(rows).to(dev), torch.from_numpy(w_rows).to(dev)
+    # quantizer: the sampled rows of both operands
+    for src, picked, codes, scales, mask in ((x, rows, xc, xs, xm), (w, w_rows, wc, ws, wm)):
+        picked_d = torch.from_numpy(picked).to(dev)
+        got = dict(codes=codes[picked_d].cpu().numpy(), scales=scales[picked_d].cpu().numpy(),
+                   mask=mask[picked_d].cpu().numpy(), xh=None)
+        compare_quantizer(got, qo.hadamard_quantize(src[picked], n, bits), K, bits)
+    ux_all, uw = qo.unpack_odd(xc.cpu().numpy(), K, bits), qo.unpack_odd(wc.cpu().numpy(), K, bits)
+    sx32, sw32 = xs.cpu().numpy(), ws.cpu().numpy()
+    sx, sw = sx32.astype(np.float64), sw32.astype(np.float64)
+    # forward rows
+    check_gemm_output(y[rows_d], qo.gemm_odd(ux_all[rows], uw), sx32[rows], sw32)
+    # G_x rows and their masked inverse transform
+    d = qo.widen(dy[rows])
+    ref = qo.grad_input(d, uw, sw)
+    q16 = qo.widen(synth.to_bf16_bits(sw32[:, None] * uw.astype(np.float32)))
+    spread = np.sqrt((d ** 2) @ (q16 ** 2))
+    got = to_host_f64(g_x[rows_d])
+    assert np.all(np.abs(got - d @ q16) <= BF16_HALF_ULP * 1.001 * np.abs(d @ q16) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+    ref_dx = qo.trust_backward(got, qo.unpack_mask(xm[rows_d].cpu().numpy(), K), n)
+    scale = np.sqrt(np.mean(ref_dx * ref_dx, axis=1, keepdims=True))
+    assert np.all(np.abs(to_host_f64(dx[rows_d]) - ref_dx) <= BF16_HALF_ULP * np.abs(ref_dx) + 1e-5 * scale + 1e-30)
+    # G_w rows (columns of dy) and their masked inverse transform
+    d = qo.widen(np.ascontiguousarray(dy[:, w_rows]))
+    ref = qo.grad_weight(d, ux_all, sx)
+    q16 = qo.widen(synth.to_bf16_bits(sx32[:, None] * ux_all.astype(np.float32)))
+    mirror = d.T @ q16
+    spread = np.sqrt((d.T ** 2) @ (q16 ** 2))
+    got = to_host_f64(g_w[w_rows_d])
+    assert np.all(np.abs(got - mirror) <= BF16_HALF_ULP * 1.001 * np.abs(mirror) + 2e-5 * spread)
+    assert np.all(np.abs(got - ref) <= BF16_HALF_ULP * np.abs(ref) + 2e-2 * spread)
+    ref_dw = qo.trust_backward(got, qo.unpack_mask(wm[w_rows_d].cpu().numpy(), K), n)
+    scale = np.sqrt(np.mean(ref_dw * ref_dw, axis=1, keepdims=True))
+    assert np.all(np.abs(to_host_f64(dw[w_rows_d]) - ref_dw) <= BF16_HALF_ULP * np.abs(ref_dw) + 1e-5 * scale + 1e-30)
+
+
 @pytest.mark.parametrize("M,N,K,bits", [(256, 256, 64, 4), (512, 256, 2048, 4), (256, 768, 320, 2),
                                         (768, 512, 1024, 1), (256, 256, 5632, 3),
                                         (4096, 2304, 128, 4),   # 144 tiles: split over the CUs
